@@ -1,0 +1,205 @@
+"""CPU oracle for the emulated lane-aware all-reduce (ctypes wrapper around la_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's CPU-baseline leg
+import this package; the product package never does.  Nothing here touches a GPU.
+
+`build()` compiles la_oracle.c with gcc; the functions below load the built library lazily.
+Buffers are numpy arrays: int32, float32, or uint16 holding bf16 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "la_oracle.c")
+_LIB = os.path.join(_HERE, "libla_oracle.so")
+
+I32, F32, BF16 = 0, 1, 2
+RING, LANE, LANE_MULTIPROC = 0, 1, 2
+ALGOS = {"ring": RING, "lane": LANE, "lane_multiproc": LANE_MULTIPROC}
+
+# phases in the message trace
+PH_LANE_S1, PH_LANE_S2A, PH_LANE_S2B, PH_LANE_S3, PH_RING_RS, PH_RING_AG = 1, 2, 3, 4, 10, 11
+
+MSG_DTYPE = np.dtype(
+    [("phase", "<i4"), ("step", "<i4"), ("src", "<i4"), ("dst", "<i4"), ("off", "<u8"), ("cnt", "<u8")]
+)
+
+
+def build(force: bool = True, src: str = _SRC, lib: str = _LIB) -> str:
+    """Compile the oracle (plain C, no fast-math, no contraction)."""
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+        cmd = ["gcc", "-O2", "-std=c99", "-fno-fast-math", "-ffp-contract=off", "-fopenmp",
+               "-fPIC", "-shared", "-Wall", "-Wextra", "-o", lib, src]
+        subprocess.run(cmd, check=True)
+    return lib
+
+
+def dtype_code(arr: np.ndarray) -> int:
+    if arr.dtype == np.int32:
+        return I32
+    if arr.dtype == np.float32:
+        return F32
+    if arr.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle buffers must be int32, float32 or uint16 (bf16 bits), not {arr.dtype}")
+
+
+def _row_ptrs(rows):
+    arr = (ctypes.c_void_p * len(rows))()
+    for i, r in enumerate(rows):
+        assert r.flags["C_CONTIGUOUS"] and r.ndim == 1
+        arr[i] = r.ctypes.data
+    return arr
+
+
+class Oracle:
+    """The functions of one built oracle library.  The module-level functions below use the
+    library built from la_oracle.c; tests that plant mistakes load their own build."""
+
+    I32, F32, BF16 = I32, F32, BF16
+    PH_LANE_S1, PH_LANE_S2A, PH_LANE_S2B, PH_LANE_S3 = PH_LANE_S1, PH_LANE_S2A, PH_LANE_S2B, PH_LANE_S3
+    PH_RING_RS, PH_RING_AG = PH_RING_RS, PH_RING_AG
+
+    def __init__(self, libpath: str):
+        lib = ctypes.CDLL(libpath)
+        u64, i32, vp = ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p
+        lib.oracle_allreduce.argtypes = [i32, i32, i32, i32, u64, i32, ctypes.POINTER(vp), i32,
+                                         vp, u64, ctypes.POINTER(u64)]
+        lib.oracle_allreduce.restype = i32
+        lib.oracle_definition_sum.argtypes = [i32, i32, u64, ctypes.POINTER(vp), vp]
+        lib.oracle_definition_sum.restype = i32
+        lib.oracle_reduce_segments.argtypes = [i32, vp, ctypes.POINTER(vp), i32, vp, u64, u64]
+        lib.oracle_reduce_segments.restype = i32
+        lib.oracle_bf16_round.argtypes = [vp, vp, u64]
+        lib.oracle_bf16_widen.argtypes = [vp, vp, u64]
+        lib.oracle_part.argtypes = [u64, u64, u64, ctypes.POINTER(u64), ctypes.POINTER(u64)]
+        lib.oracle_set_threads.argtypes = [i32]
+        lib.oracle_max_threads.restype = i32
+        self.lib = lib
+
+    def set_threads(self, t: int) -> None:
+        self.lib.oracle_set_threads(int(t))
+
+    def max_threads(self) -> int:
+        return int(self.lib.oracle_max_threads())
+
+    def allreduce(self, algo, N: int, G: int, Q: int, inputs, max_rounds: int = -1,
+                  want_trace: bool = False, in_place: bool = False):
+        """Simulate a schedule over the P = N*G*Q rank buffers `inputs` (a [P, n] array or a
+        list of P 1-D arrays).  Returns the result (and the message trace when asked)."""
+        algo = ALGOS[algo] if isinstance(algo, str) else int(algo)
+        P = N * G * Q
+        if isinstance(inputs, np.ndarray):
+            assert inputs.ndim == 2 and inputs.shape[0] == P
+            work = inputs if in_place else inputs.copy()
+            rows = [work[r] for r in range(P)]
+        else:
+            assert len(inputs) == P
+            rows = list(inputs) if in_place else [np.array(r, copy=True) for r in inputs]
+            work = rows
+        n = rows[0].shape[0]
+        assert all(r.shape[0] == n and r.dtype == rows[0].dtype for r in rows)
+        ptrs = _row_ptrs(rows)
+        tlen = ctypes.c_uint64(0)
+        trace, cap = None, 0
+        if want_trace:
+            # generous bound: ring sends 2(P-1)P messages, lane fewer than 4 P max(R, N)
+            cap = 4 * P * max(P, 2) + 16
+            trace = np.zeros(cap, dtype=MSG_DTYPE)
+        rc = self.lib.oracle_allreduce(algo, N, G, Q, n, dtype_code(rows[0]), ptrs, int(max_rounds),
+                                       trace.ctypes.data if want_trace else None, cap,
+                                       ctypes.byref(tlen))
+        if rc != 0:
+            raise RuntimeError(f"oracle_allreduce failed with code {rc}")
+        if want_trace:
+            assert tlen.value <= cap
+            return work, trace[: tlen.value]
+        return work
+
+    def definition_sum(self, inputs):
+        """The all-reduce by its definition: int32 -> int32 (exact, wrapped); floats -> float64."""
+        rows = [inputs[r] for r in range(len(inputs))]
+        n = rows[0].shape[0]
+        code = dtype_code(rows[0])
+        out = np.empty(n, dtype=np.int32 if code == I32 else np.float64)
+        rc = self.lib.oracle_definition_sum(code, len(rows), n, _row_ptrs(rows), out.ctypes.data)
+        if rc != 0:
+            raise RuntimeError(f"oracle_definition_sum failed with code {rc}")
+        return out
+
+    def reduce_segments(self, dst: np.ndarray, srcs, seg_offsets, seg_len: int) -> np.ndarray:
+        """dst[o] = ((dst[o] + srcs[0][o]) + srcs[1][o]) + ... over every segment; a copy."""
+        out = dst.copy()
+        offs = np.ascontiguousarray(seg_offsets, dtype=np.uint64)
+        srcs = [np.ascontiguousarray(s) for s in srcs]
+        ptrs = _row_ptrs(srcs) if srcs else (ctypes.c_void_p * 1)()
+        rc = self.lib.oracle_reduce_segments(dtype_code(out), out.ctypes.data, ptrs, len(srcs),
+                                             offs.ctypes.data, len(offs), int(seg_len))
+        if rc != 0:
+            raise RuntimeError(f"oracle_reduce_segments failed with code {rc}")
+        return out
+
+    def bf16_round(self, x: np.ndarray) -> np.ndarray:
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        out = np.empty(x.shape, dtype=np.uint16)
+        self.lib.oracle_bf16_round(x.ctypes.data, out.ctypes.data, x.size)
+        return out
+
+    def bf16_widen(self, h: np.ndarray) -> np.ndarray:
+        h = np.ascontiguousarray(h, dtype=np.uint16)
+        out = np.empty(h.shape, dtype=np.float32)
+        self.lib.oracle_bf16_widen(h.ctypes.data, out.ctypes.data, h.size)
+        return out
+
+    def part(self, length: int, m: int, i: int):
+        off, cnt = ctypes.c_uint64(), ctypes.c_uint64()
+        self.lib.oracle_part(length, m, i, ctypes.byref(off), ctypes.byref(cnt))
+        return off.value, cnt.value
+
+
+_default = None
+
+
+def default() -> Oracle:
+    global _default
+    if _default is None:
+        build(force=False)
+        _default = Oracle(_LIB)
+    return _default
+
+
+def set_threads(t):
+    default().set_threads(t)
+
+
+def max_threads():
+    return default().max_threads()
+
+
+def allreduce(*a, **k):
+    return default().allreduce(*a, **k)
+
+
+def definition_sum(inputs):
+    return default().definition_sum(inputs)
+
+
+def reduce_segments(dst, srcs, seg_offsets, seg_len):
+    return default().reduce_segments(dst, srcs, seg_offsets, seg_len)
+
+
+def bf16_round(x):
+    return default().bf16_round(x)
+
+
+def bf16_widen(h):
+    return default().bf16_widen(h)
+
+
+def part(length, m, i):
+    return default().part(length, m, i)

@@ -1,0 +1,569 @@
+/*
+ * la_oracle.c -- CPU oracle for the emulated lane-aware all-reduce.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+ * GPU library is checked against.  It shares no code, header, table or
+ * constant with the HIP path, and the product never calls it: only the tests,
+ * the smoke check and the benchmark's CPU-baseline leg load it.
+ *
+ * Two oracles live here.
+ *
+ *   oracle_definition_sum   the definition of an all-reduce with SUM: every
+ *                           rank ends with the element-wise sum of all P
+ *                           input buffers (paper, Introduction: each process
+ *                           exchanges and reduces data with all others; the
+ *                           MPI_Allreduce(..., MPI_SUM, ...) call of the
+ *                           "Standard Approach" subsection).
+ *
+ *   oracle_allreduce        a rank-centric, message-by-message simulation of
+ *                           the schedules: Algorithm 1 (ring_allreduce) and
+ *                           Algorithm 2 (lane_allreduce), the latter also in
+ *                           its multiple-processes-per-GPU form ("Multi-lane
+ *                           Approach" subsection).  P virtual ranks own
+ *                           private buffers.  A step has two halves: first
+ *                           every rank posts copies of what it sends (so all
+ *                           sends see the state at the start of the step),
+ *                           then every rank consumes what it received.
+ *
+ * Readings where the paper is silent (all are this build's, stated once):
+ *   - rank r = (node*G + gpu)*Q + proc, following l_r = r mod PPG
+ *     ("Multiple Processes Per GPU" subsection);
+ *   - every one of the P ranks contributes a private buffer of n elements;
+ *   - a length is split into m parts in a balanced way: part i has
+ *     floor(len/m) elements plus one if i < len mod m (Algorithms 1 and 2
+ *     print an integer division that would drop the remainder);
+ *   - the loops of Algorithm 1 run P-1 times (text under Algorithm 1);
+ *   - MPI_Reduce_scatter and MPI_Allreduce of Algorithm 2 are vendor black
+ *     boxes; here each is a direct exchange: every member sends its copy of a
+ *     part to the part's owner, who adds the operands in ascending
+ *     communicator rank (its own copy taking its place in that order), and
+ *     the all-reduce is that reduce-scatter followed by an all-gather;
+ *   - lanes first (one per GPU), then sub-chunks (one per process) inside a
+ *     lane; "lane" without the multi-process split gives each lane to the
+ *     GPU's leader process (local rank 0);
+ *   - int32 wraps (two's complement); fp32 is IEEE binary32 add, left to
+ *     right; bf16 operands are widened exactly to fp32, added in fp32 and
+ *     rounded once (nearest, ties to even) when a step stores its result.
+ *
+ * Parity pins: see tests/test_oracle_*.py (definition, closed forms, the
+ * index walk of Algorithm 1, stage boundaries of Algorithm 2, brute force).
+ * The paper prints no worked numeric example, so no pin comes from printed
+ * values.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_I32 = 0, ORACLE_F32 = 1, ORACLE_BF16 = 2 };
+enum { ORACLE_RING = 0, ORACLE_LANE = 1, ORACLE_LANE_MULTIPROC = 2 };
+
+/* phases recorded in the message trace */
+enum {
+    PH_LANE_S1 = 1,  /* intra-node reduce-scatter          */
+    PH_LANE_S2A = 2, /* inter-node reduce-scatter of parts */
+    PH_LANE_S2B = 3, /* inter-node all-gather of pieces    */
+    PH_LANE_S3 = 4,  /* intra-node all-gather              */
+    PH_RING_RS = 10, /* ring reduce-scatter loop           */
+    PH_RING_AG = 11  /* ring all-gather loop               */
+};
+
+typedef struct {
+    int32_t phase;
+    int32_t step; /* round counter, from 0 */
+    int32_t src;
+    int32_t dst;
+    uint64_t off; /* element offset in the rank buffers */
+    uint64_t cnt; /* elements */
+} oracle_msg_t;
+
+static int g_threads = 1;
+
+void oracle_set_threads(int t)
+{
+    g_threads = t < 1 ? 1 : t;
+}
+
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+static size_t elem_size(int dtype)
+{
+    return dtype == ORACLE_BF16 ? 2 : 4;
+}
+
+/* ---- bf16 <-> fp32 ------------------------------------------------------ */
+
+/* bf16 is the upper half of a binary32: widening appends 16 zero bits. */
+static float bf16_widen(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* Round a binary32 to the nearest bf16, ties to the even mantissa.  Written
+ * from the definition: look at the 16 discarded bits, compare with half. */
+static uint16_t bf16_round(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint32_t exp = (u >> 23) & 0xffu, man = u & 0x7fffffu;
+    if (exp == 0xffu && man != 0) /* NaN stays NaN: keep sign, set quiet bit */
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t kept = u >> 16, lost = u & 0xffffu;
+    if (lost > 0x8000u)
+        kept += 1; /* above half: away; a carry into the exponent is right */
+    else if (lost == 0x8000u && (kept & 1u))
+        kept += 1; /* exactly half: to even */
+    return (uint16_t)kept;
+}
+
+void oracle_bf16_round(const float* in, uint16_t* out, uint64_t n)
+{
+    for (uint64_t i = 0; i < n; ++i) out[i] = bf16_round(in[i]);
+}
+
+void oracle_bf16_widen(const uint16_t* in, float* out, uint64_t n)
+{
+    for (uint64_t i = 0; i < n; ++i) out[i] = bf16_widen(in[i]);
+}
+
+/* ---- balanced split ------------------------------------------------------ */
+
+/* part i of m of a length len: offset (relative) and count */
+static void part(uint64_t len, uint64_t m, uint64_t i, uint64_t* off, uint64_t* cnt)
+{
+    uint64_t q = len / m, rem = len % m;
+    *cnt = q + (i < rem ? 1 : 0);
+    *off = i * q + (i < rem ? i : rem);
+}
+
+void oracle_part(uint64_t len, uint64_t m, uint64_t i, uint64_t* off, uint64_t* cnt)
+{
+    part(len, m, i, off, cnt);
+}
+
+/* ---- the definition ------------------------------------------------------ */
+
+/* out[i] = sum over p of in[p][i].  int32: exact in int64, then wrapped to
+ * 32 bits, out is int32[n].  fp32 / bf16: summed in fp64 in ascending rank,
+ * out is double[n] (the caller applies the tolerance). */
+int oracle_definition_sum(int dtype, int P, uint64_t n, const void* const* in, void* out)
+{
+    if (P < 1 || !in || !out) return 1;
+    if (dtype == ORACLE_I32) {
+        int32_t* o = (int32_t*)out;
+        for (uint64_t i = 0; i < n; ++i) {
+            int64_t s = 0;
+            for (int p = 0; p < P; ++p) s += ((const int32_t*)in[p])[i];
+            o[i] = (int32_t)(uint32_t)(uint64_t)s;
+        }
+    } else if (dtype == ORACLE_F32) {
+        double* o = (double*)out;
+        for (uint64_t i = 0; i < n; ++i) {
+            double s = 0.0;
+            for (int p = 0; p < P; ++p) s += (double)((const float*)in[p])[i];
+            o[i] = s;
+        }
+    } else if (dtype == ORACLE_BF16) {
+        double* o = (double*)out;
+        for (uint64_t i = 0; i < n; ++i) {
+            double s = 0.0;
+            for (int p = 0; p < P; ++p) s += (double)bf16_widen(((const uint16_t*)in[p])[i]);
+            o[i] = s;
+        }
+    } else {
+        return 2;
+    }
+    return 0;
+}
+
+/* ---- element-wise k-operand sum, operands in the order given -------------- */
+
+static void sum_operands(int dtype, void* dst, const void* const* ops, int k, uint64_t cnt)
+{
+    int64_t m = (int64_t)cnt;
+    if (dtype == ORACLE_I32) {
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+        for (int64_t i = 0; i < m; ++i) {
+            uint32_t s = ((const uint32_t*)ops[0])[i];
+            for (int t = 1; t < k; ++t) s = s + ((const uint32_t*)ops[t])[i];
+            ((uint32_t*)dst)[i] = s;
+        }
+    } else if (dtype == ORACLE_F32) {
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+        for (int64_t i = 0; i < m; ++i) {
+            float s = ((const float*)ops[0])[i];
+            for (int t = 1; t < k; ++t) s = s + ((const float*)ops[t])[i];
+            ((float*)dst)[i] = s;
+        }
+    } else {
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+        for (int64_t i = 0; i < m; ++i) {
+            float s = bf16_widen(((const uint16_t*)ops[0])[i]);
+            for (int t = 1; t < k; ++t) s = s + bf16_widen(((const uint16_t*)ops[t])[i]);
+            ((uint16_t*)dst)[i] = bf16_round(s);
+        }
+    }
+}
+
+/* dst[o] = ((dst[o] + srcs[0][o]) + srcs[1][o]) + ... for o in every segment:
+ * "k incoming segments summed into the owned segment". */
+int oracle_reduce_segments(int dtype, void* dst, const void* const* srcs, int k,
+                           const uint64_t* seg_offsets, uint64_t num_segments, uint64_t seg_len)
+{
+    if (k < 0 || k > 4096) return 1;
+    size_t e = elem_size(dtype);
+    const void* ops[4097];
+    for (uint64_t s = 0; s < num_segments; ++s) {
+        uint64_t o = seg_offsets[s];
+        ops[0] = (const char*)dst + o * e;
+        for (int t = 0; t < k; ++t) ops[t + 1] = (const char*)srcs[t] + o * e;
+        sum_operands(dtype, (char*)dst + o * e, ops, k + 1, seg_len);
+    }
+    return 0;
+}
+
+/* ---- the virtual machine: P ranks, private buffers, a mailbox ------------ */
+
+typedef struct {
+    int src;
+    uint64_t off, cnt;
+    void* data; /* private copy of the payload */
+} letter_t;
+
+typedef struct {
+    letter_t* v;
+    size_t len, cap;
+} inbox_t;
+
+typedef struct {
+    int P;
+    int dtype;
+    size_t esz;
+    uint64_t n;
+    void** buf;     /* buf[r]: rank r's buffer (caller's memory, updated in place) */
+    inbox_t* inbox; /* inbox[r]: letters addressed to rank r in this round */
+    oracle_msg_t* trace;
+    uint64_t trace_cap, trace_len;
+    int phase, round;
+    int failed;
+} world_t;
+
+static void post(world_t* w, int src, int dst, uint64_t off, uint64_t cnt)
+{
+    if (w->trace && w->trace_len < w->trace_cap) {
+        oracle_msg_t* t = &w->trace[w->trace_len];
+        t->phase = w->phase;
+        t->step = w->round;
+        t->src = src;
+        t->dst = dst;
+        t->off = off;
+        t->cnt = cnt;
+    }
+    w->trace_len++;
+    inbox_t* b = &w->inbox[dst];
+    if (b->len == b->cap) {
+        size_t nc = b->cap ? 2 * b->cap : 8;
+        letter_t* nv = (letter_t*)realloc(b->v, nc * sizeof(letter_t));
+        if (!nv) {
+            w->failed = 1;
+            return;
+        }
+        b->v = nv;
+        b->cap = nc;
+    }
+    letter_t* l = &b->v[b->len++];
+    l->src = src;
+    l->off = off;
+    l->cnt = cnt;
+    l->data = malloc(cnt * w->esz + 1);
+    if (!l->data) {
+        w->failed = 1;
+        l->cnt = 0;
+        return;
+    }
+    memcpy(l->data, (const char*)w->buf[src] + off * w->esz, cnt * w->esz);
+}
+
+static const letter_t* letter_from(const world_t* w, int at, int src)
+{
+    const inbox_t* b = &w->inbox[at];
+    for (size_t i = 0; i < b->len; ++i)
+        if (b->v[i].src == src) return &b->v[i];
+    return NULL;
+}
+
+static void end_round(world_t* w)
+{
+    for (int r = 0; r < w->P; ++r) {
+        inbox_t* b = &w->inbox[r];
+        for (size_t i = 0; i < b->len; ++i) free(b->v[i].data);
+        b->len = 0;
+    }
+    w->round++;
+}
+
+static void overwrite(world_t* w, int at, const letter_t* l)
+{
+    memcpy((char*)w->buf[at] + l->off * w->esz, l->data, l->cnt * w->esz);
+}
+
+/* ---- Algorithm 1: ring_allreduce ---------------------------------------- */
+
+static int imod(int a, int m)
+{
+    int r = a % m;
+    return r < 0 ? r + m : r;
+}
+
+static int run_ring(world_t* w, int max_rounds)
+{
+    int P = w->P;
+    uint64_t* D = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)P);   /* displacements */
+    uint64_t* cnt = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)P); /* counts per chunk */
+    if (!D || !cnt) return 3;
+    for (int c = 0; c < P; ++c) part(w->n, (uint64_t)P, (uint64_t)c, &D[c], &cnt[c]);
+
+    /* first loop: in round i rank r sends chunk sp = r - i to its successor
+     * and adds the chunk rp = r - 1 - i it receives from its predecessor */
+    w->phase = PH_RING_RS;
+    for (int i = 0; i < P - 1 && w->round < max_rounds; ++i) {
+        for (int r = 0; r < P; ++r) {
+            int sp = imod(r - i, P);
+            post(w, r, (r + 1) % P, D[sp], cnt[sp]);
+        }
+        for (int r = 0; r < P; ++r) {
+            const letter_t* l = letter_from(w, r, imod(r - 1, P));
+            if (!l) return 4;
+            char* own = (char*)w->buf[r] + l->off * w->esz;
+            const void* ops[2] = {own, l->data}; /* own = own + incoming */
+            sum_operands(w->dtype, own, ops, 2, l->cnt);
+        }
+        end_round(w);
+    }
+    /* second loop: sp starts at r + 1, rp at r; received chunks overwrite */
+    w->phase = PH_RING_AG;
+    for (int i = 0; i < P - 1 && w->round < max_rounds; ++i) {
+        for (int r = 0; r < P; ++r) {
+            int sp = imod(r + 1 - i, P);
+            post(w, r, (r + 1) % P, D[sp], cnt[sp]);
+        }
+        for (int r = 0; r < P; ++r) {
+            const letter_t* l = letter_from(w, r, imod(r - 1, P));
+            if (!l) return 4;
+            overwrite(w, r, l);
+        }
+        end_round(w);
+    }
+    free(D);
+    free(cnt);
+    return w->failed ? 3 : 0;
+}
+
+/* ---- Algorithm 2: lane_allreduce, with or without the per-process split -- */
+
+typedef struct {
+    int N, G, Q;
+    int split_procs; /* 1: every process owns a sub-chunk; 0: the GPU's leader owns the lane */
+} lane_cfg_t;
+
+static int rank_of(const lane_cfg_t* c, int node, int local)
+{
+    return node * c->G * c->Q + local; /* local = gpu*Q + proc */
+}
+
+static int num_parts(const lane_cfg_t* c)
+{
+    return c->split_procs ? c->G * c->Q : c->G;
+}
+
+/* node-local index of the process that owns part j */
+static int owner_local(const lane_cfg_t* c, int j)
+{
+    return c->split_procs ? j : j * c->Q;
+}
+
+/* part j of the buffer: lane g of G, then (if split) sub-chunk q of Q inside it */
+static void part_of_buffer(const lane_cfg_t* c, uint64_t n, int j, uint64_t* off, uint64_t* cnt)
+{
+    if (!c->split_procs) {
+        part(n, (uint64_t)c->G, (uint64_t)j, off, cnt);
+        return;
+    }
+    int g = j / c->Q, q = j % c->Q;
+    uint64_t lo, lc, so, sc;
+    part(n, (uint64_t)c->G, (uint64_t)g, &lo, &lc);
+    part(lc, (uint64_t)c->Q, (uint64_t)q, &so, &sc);
+    *off = lo + so;
+    *cnt = sc;
+}
+
+static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
+{
+    int N = c->N, R = c->G * c->Q, J = num_parts(c);
+    const void** ops = (const void**)malloc(sizeof(void*) * (size_t)(R > N ? R : N));
+    if (!ops) return 3;
+
+    /* stage 1: reduce-scatter on the node group.  Every process of the node
+     * sends its copy of part j to the part's owner; the owner adds the R
+     * copies in ascending node-local index. */
+    if (w->round < max_rounds) {
+        w->phase = PH_LANE_S1;
+        for (int node = 0; node < N; ++node)
+            for (int j = 0; j < J; ++j) {
+                uint64_t off, cnt;
+                part_of_buffer(c, w->n, j, &off, &cnt);
+                int own = owner_local(c, j);
+                for (int l = 0; l < R; ++l)
+                    if (l != own) post(w, rank_of(c, node, l), rank_of(c, node, own), off, cnt);
+            }
+        for (int node = 0; node < N; ++node)
+            for (int j = 0; j < J; ++j) {
+                uint64_t off, cnt;
+                part_of_buffer(c, w->n, j, &off, &cnt);
+                int own = owner_local(c, j), me = rank_of(c, node, own);
+                char* mine = (char*)w->buf[me] + off * w->esz;
+                for (int l = 0; l < R; ++l) {
+                    if (l == own) {
+                        ops[l] = mine;
+                    } else {
+                        const letter_t* le = letter_from(w, me, rank_of(c, node, l));
+                        if (!le || le->off != off) return 4;
+                        ops[l] = le->data;
+                    }
+                }
+                sum_operands(w->dtype, mine, ops, R, cnt);
+            }
+        end_round(w);
+    }
+
+    /* stage 2: all-reduce of part j on the lane communicator (the owners of
+     * part j on the N nodes), as reduce-scatter of N pieces + all-gather. */
+    if (w->round < max_rounds) {
+        w->phase = PH_LANE_S2A;
+        for (int j = 0; j < J; ++j) {
+            uint64_t off, cnt;
+            part_of_buffer(c, w->n, j, &off, &cnt);
+            int own = owner_local(c, j);
+            for (int from = 0; from < N; ++from)
+                for (int to = 0; to < N; ++to) {
+                    uint64_t po, pc;
+                    part(cnt, (uint64_t)N, (uint64_t)to, &po, &pc);
+                    if (to != from) post(w, rank_of(c, from, own), rank_of(c, to, own), off + po, pc);
+                }
+        }
+        for (int j = 0; j < J; ++j) {
+            uint64_t off, cnt;
+            part_of_buffer(c, w->n, j, &off, &cnt);
+            int own = owner_local(c, j);
+            for (int node = 0; node < N; ++node) {
+                uint64_t po, pc;
+                part(cnt, (uint64_t)N, (uint64_t)node, &po, &pc);
+                int me = rank_of(c, node, own);
+                char* mine = (char*)w->buf[me] + (off + po) * w->esz;
+                for (int from = 0; from < N; ++from) {
+                    if (from == node) {
+                        ops[from] = mine;
+                    } else {
+                        const letter_t* le = letter_from(w, me, rank_of(c, from, own));
+                        if (!le || le->off != off + po) return 4;
+                        ops[from] = le->data;
+                    }
+                }
+                sum_operands(w->dtype, mine, ops, N, pc);
+            }
+        }
+        end_round(w);
+    }
+    if (w->round < max_rounds) {
+        w->phase = PH_LANE_S2B;
+        for (int j = 0; j < J; ++j) {
+            uint64_t off, cnt;
+            part_of_buffer(c, w->n, j, &off, &cnt);
+            int own = owner_local(c, j);
+            for (int from = 0; from < N; ++from) {
+                uint64_t po, pc;
+                part(cnt, (uint64_t)N, (uint64_t)from, &po, &pc);
+                for (int to = 0; to < N; ++to)
+                    if (to != from) post(w, rank_of(c, from, own), rank_of(c, to, own), off + po, pc);
+            }
+        }
+        for (int r = 0; r < w->P; ++r)
+            for (size_t i = 0; i < w->inbox[r].len; ++i) overwrite(w, r, &w->inbox[r].v[i]);
+        end_round(w);
+    }
+
+    /* stage 3: all-gather on the node group: each owner sends its part to
+     * the other R-1 processes of its node. */
+    if (w->round < max_rounds) {
+        w->phase = PH_LANE_S3;
+        for (int node = 0; node < N; ++node)
+            for (int j = 0; j < J; ++j) {
+                uint64_t off, cnt;
+                part_of_buffer(c, w->n, j, &off, &cnt);
+                int own = owner_local(c, j);
+                for (int l = 0; l < R; ++l)
+                    if (l != own) post(w, rank_of(c, node, own), rank_of(c, node, l), off, cnt);
+            }
+        for (int r = 0; r < w->P; ++r)
+            for (size_t i = 0; i < w->inbox[r].len; ++i) overwrite(w, r, &w->inbox[r].v[i]);
+        end_round(w);
+    }
+    free(ops);
+    return w->failed ? 3 : 0;
+}
+
+/*
+ * Run a schedule over P = N*G*Q private buffers of n elements, in place.
+ *   max_rounds < 0: run to the end; otherwise stop after that many rounds
+ *   (ring: one round per loop iteration; lane: S1, S2a, S2b, S3 are one round
+ *   each), so that tests can look at intermediate states.
+ *   trace / trace_cap: optional log of every message; *trace_len receives the
+ *   number of messages sent (which may exceed trace_cap).
+ * Returns 0 on success.
+ */
+int oracle_allreduce(int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
+                     int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
+{
+    if (N < 1 || G < 1 || Q < 1 || !bufs) return 1;
+    if (dtype != ORACLE_I32 && dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 2;
+    world_t w;
+    memset(&w, 0, sizeof w);
+    w.P = N * G * Q;
+    w.dtype = dtype;
+    w.esz = elem_size(dtype);
+    w.n = n;
+    w.buf = bufs;
+    w.inbox = (inbox_t*)calloc((size_t)w.P, sizeof(inbox_t));
+    if (!w.inbox) return 3;
+    w.trace = trace;
+    w.trace_cap = trace ? trace_cap : 0;
+    int limit = max_rounds < 0 ? 0x7fffffff : max_rounds;
+    int rc;
+    if (algo == ORACLE_RING) {
+        rc = run_ring(&w, limit);
+    } else if (algo == ORACLE_LANE || algo == ORACLE_LANE_MULTIPROC) {
+        lane_cfg_t c = {N, G, Q, algo == ORACLE_LANE_MULTIPROC};
+        rc = run_lane(&w, &c, limit);
+    } else {
+        rc = 2;
+    }
+    for (int r = 0; r < w.P; ++r) {
+        for (size_t i = 0; i < w.inbox[r].len; ++i) free(w.inbox[r].v[i].data);
+        free(w.inbox[r].v);
+    }
+    free(w.inbox);
+    if (trace_len) *trace_len = w.trace_len;
+    return rc;
+}

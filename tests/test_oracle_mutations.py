@@ -1,0 +1,109 @@
+"""Are the pins sharp?  Each case plants one plausible mistake in a copy of the oracle's C source
+(a wrong index, sign, order, bound or rounding rule), builds it, and requires that at least one
+pin of tests/test_oracle_pins.py fails on the broken build.  CPU only."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+import oracle as oracle_pkg
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(oracle_pkg.__file__), "la_oracle.c")
+
+# (name, text in la_oracle.c, replacement)
+MUTATIONS = [
+    ("split_remainder_dropped", "*cnt = q + (i < rem ? 1 : 0);", "*cnt = q;"),
+    ("split_offset_wrong", "*off = i * q + (i < rem ? i : rem);", "*off = i * q;"),
+    ("ring_rs_walks_forward", "int sp = imod(r - i, P);", "int sp = imod(r + i, P);"),
+    ("ring_ag_starts_at_r", "int sp = imod(r + 1 - i, P);", "int sp = imod(r - i, P);"),
+    ("ring_one_round_short", "for (int i = 0; i < P - 1 && w->round < max_rounds; ++i) {\n        for (int r = 0; r < P; ++r) {\n            int sp = imod(r + 1",
+     "for (int i = 0; i < P - 2 && w->round < max_rounds; ++i) {\n        for (int r = 0; r < P; ++r) {\n            int sp = imod(r + 1"),
+    ("ring_sends_to_predecessor", "post(w, r, (r + 1) % P, D[sp], cnt[sp]);\n        }\n        for (int r = 0; r < P; ++r) {\n            const letter_t* l = letter_from(w, r, imod(r - 1, P));\n            if (!l) return 4;\n            char* own",
+     "post(w, r, imod(r - 1, P), D[sp], cnt[sp]);\n        }\n        for (int r = 0; r < P; ++r) {\n            const letter_t* l = letter_from(w, r, (r + 1) % P);\n            if (!l) return 4;\n            char* own"),
+    ("s1_owner_first", "                for (int l = 0; l < R; ++l) {\n                    if (l == own) {\n                        ops[l] = mine;",
+     "                ops[0] = mine;\n                for (int l = 0; l < R; ++l) {\n                    if (l == own) {\n                        if (l) ops[l] = ops[0]; if (l) ops[0] = mine;"),
+    ("s1_drops_last_operand", "sum_operands(w->dtype, mine, ops, R, cnt);", "sum_operands(w->dtype, mine, ops, R > 1 ? R - 1 : R, cnt);"),
+    ("s2a_piece_index_swapped", "part(cnt, (uint64_t)N, (uint64_t)to, &po, &pc);\n                    if (to != from) post",
+     "part(cnt, (uint64_t)N, (uint64_t)from, &po, &pc);\n                    if (to != from) post"),
+    ("s2a_descending_order", "ops[from] = le->data;", "ops[N - 1 - from] = le->data;"),
+    ("s2b_skipped", "w->phase = PH_LANE_S2B;\n        for (int j = 0; j < J; ++j) {", "w->phase = PH_LANE_S2B;\n        for (int j = 0; j < 0; ++j) {"),
+    ("s3_misses_last_local", "for (int l = 0; l < R; ++l)\n                    if (l != own) post(w, rank_of(c, node, own), rank_of(c, node, l), off, cnt);",
+     "for (int l = 0; l < R - 1; ++l)\n                    if (l != own) post(w, rank_of(c, node, own), rank_of(c, node, l), off, cnt);"),
+    ("proc_major_split", "*off = lo + so;", "*off = (uint64_t)q * (n / (uint64_t)c->Q) + so + lo / (uint64_t)c->Q;"),
+    ("lane_owner_not_leader", "return c->split_procs ? j : j * c->Q;", "return c->split_procs ? j : j * c->Q + (c->Q - 1);"),
+    ("rank_numbering_gpu_minor", "return node * c->G * c->Q + local;", "return local * c->N + node;"),
+    ("bf16_truncates", "if (lost > 0x8000u)\n        kept += 1;", "if (lost > 0xffffu)\n        kept += 1;"),
+    ("bf16_ties_away", "else if (lost == 0x8000u && (kept & 1u))", "else if (lost == 0x8000u)"),
+    ("bf16_rounds_every_add", "for (int t = 1; t < k; ++t) s = s + bf16_widen(((const uint16_t*)ops[t])[i]);",
+     "for (int t = 1; t < k; ++t) s = bf16_widen(bf16_round(s + bf16_widen(((const uint16_t*)ops[t])[i])));"),
+    ("f32_accumulates_in_double", "float s = ((const float*)ops[0])[i];\n            for (int t = 1; t < k; ++t) s = s + ((const float*)ops[t])[i];",
+     "double s = ((const float*)ops[0])[i];\n            for (int t = 1; t < k; ++t) s = s + ((const float*)ops[t])[i];"),
+    ("int_saturates", "for (int t = 1; t < k; ++t) s = s + ((const uint32_t*)ops[t])[i];",
+     "for (int t = 1; t < k; ++t) { int64_t z = (int64_t)(int32_t)s + ((const int32_t*)ops[t])[i]; s = (uint32_t)(z > 2147483647 ? 2147483647 : z < -2147483648LL ? -2147483648LL : z); }"),
+    ("definition_skips_rank0", "for (int p = 0; p < P; ++p) s += ((const int32_t*)in[p])[i];", "for (int p = 1; p < P; ++p) s += ((const int32_t*)in[p])[i];"),
+    ("definition_float_in_single", "double s = 0.0;\n            for (int p = 0; p < P; ++p) s += (double)((const float*)in[p])[i];",
+     "float s = 0.0f;\n            for (int p = 0; p < P; ++p) s += ((const float*)in[p])[i];"),
+    ("reduce_segments_ignores_dst", "sum_operands(dtype, (char*)dst + o * e, ops, k + 1, seg_len);", "sum_operands(dtype, (char*)dst + o * e, ops + (k > 0), k > 0 ? k : 1, seg_len);"),
+    ("overwrite_wrong_offset", "memcpy((char*)w->buf[at] + l->off * w->esz, l->data, l->cnt * w->esz);", "memcpy((char*)w->buf[at] + (l->off ? l->off - 1 : 0) * w->esz, l->data, l->cnt * w->esz);"),
+]
+
+
+def pin_calls(o):
+    """every pin, bound to oracle build `o`, cheapest first"""
+    calls = [
+        lambda: pins.test_part_is_numpy_array_split(o),
+        lambda: pins.test_bf16_round_closed_forms(o),
+        lambda: pins.test_bf16_round_matches_torch_on_random_bit_patterns(o),
+        lambda: pins.test_bf16_widen_all_patterns(o),
+        lambda: pins.test_definition_int32_vs_python_integers_with_wrap(o),
+        lambda: pins.test_definition_float_vs_fsum(o),
+        lambda: pins.test_golden_ring_three_ranks_cancellation(o),
+        lambda: pins.test_golden_lane_two_by_two_cancellation(o),
+        lambda: pins.test_bf16_rounds_once_per_reduce_step(o),
+        lambda: pins.test_ring_order_is_chunk_owner_first_then_successors(o),
+        lambda: pins.test_lane_order_is_node_sums_then_across_nodes(o),
+        lambda: pins.test_ring_message_pattern(o),
+        lambda: pins.test_ring_after_first_loop_rank_owns_next_chunk(o),
+        lambda: pins.test_lane_stage_boundaries(o, "lane"),
+        lambda: pins.test_lane_stage_boundaries(o, "lane_multiproc"),
+        lambda: pins.test_lane_message_shapes(o),
+        lambda: pins.test_reduce_segments_vs_numpy(o),
+        lambda: pins.test_lane_equals_lane_multiproc_when_one_process_per_gpu(o),
+    ]
+    for algo in pins.ALGOS:
+        for topo in ((2, 1, 1), (1, 2, 1), (1, 1, 2)):
+            calls.append(lambda a=algo, t=topo: pins.test_two_ranks_is_one_ieee_add(o, a, t))
+        calls.append(lambda a=algo: pins.test_bruteforce_int32_every_small_topology(o, a))
+    return calls
+
+
+@pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_planted_mistake_is_caught(tmp_path, name, old, new):
+    text = open(SRC).read()
+    assert text.count(old) >= 1, f"mutation {name}: anchor text not found in la_oracle.c"
+    src = tmp_path / "mutant.c"
+    src.write_text(text.replace(old, new, 1))
+    lib = str(tmp_path / "libmutant.so")
+    subprocess.run(["gcc", "-O2", "-std=c99", "-fno-fast-math", "-ffp-contract=off", "-fopenmp", "-fPIC",
+                    "-shared", "-w", "-o", lib, str(src)], check=True)
+    # a broken build may read or write out of bounds: run its pins in a child process
+    code = (
+        "import sys; sys.path[:0] = %r\n"
+        "import oracle, test_oracle_mutations as m\n"
+        "o = oracle.Oracle(%r)\n"
+        "for call in m.pin_calls(o):\n"
+        "    try:\n"
+        "        call()\n"
+        "    except (AssertionError, RuntimeError):\n"
+        "        sys.exit(3)\n"
+        "sys.exit(0)\n"
+    ) % ([os.path.dirname(os.path.dirname(SRC)), os.path.dirname(__file__)], lib)
+    rc = subprocess.run([sys.executable, "-c", code], capture_output=True).returncode
+    assert rc != 0, f"no pin notices the planted mistake {name!r}"
+
+
+def test_unmutated_source_passes_the_same_calls(oracle):
+    for call in pin_calls(oracle):
+        call()
