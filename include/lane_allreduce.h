@@ -1,0 +1,187 @@
+/*
+ * lane_allreduce.h -- C ABI of the emulated lane-aware all-reduce for one MI355X (gfx950).
+ *
+ * P = nodes * gpus_per_node * procs_per_gpu virtual ranks each own a private buffer of n
+ * elements; all P buffers live in the HBM of the one GPU.  A schedule turns a topology into a
+ * list of steps; every step is a table of segments, and a segment says "add these k source
+ * ranges element by element, in this order, and store the sum to these m destination ranges".
+ * Message exchanges of the distributed algorithm become reads of a peer's buffer; all
+ * arithmetic runs in HIP kernels, one launch per step.
+ *
+ * Rank numbering follows l_r = r mod PPG ("Multiple Processes Per GPU" subsection):
+ *   r = (node * gpus_per_node + gpu) * procs_per_gpu + proc.
+ *
+ * Pointer arguments marked [host] are read by the CPU before the call returns (the caller may
+ * free them at once); arguments marked [device] are HIP device pointers owned by the caller.
+ * The library never frees or reallocates caller memory.  Handles are owned by the library and
+ * released by their *_destroy call; destroying NULL is a no-op.
+ *
+ * Every function returns LA_OK or an error; after an error nothing has been enqueued.
+ * la_last_error() gives a thread-local description of the most recent failure.
+ */
+#ifndef LANE_ALLREDUCE_H
+#define LANE_ALLREDUCE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct la_topology la_topology_t; /* opaque, host only */
+typedef struct la_schedule la_schedule_t; /* opaque; owns host tables and (once run) device tables */
+
+typedef enum {
+    LA_OK = 0,
+    LA_ERR_INVALID_ARG = 1,   /* null pointer, dimension <= 0, n == 0, mismatch with the schedule,
+                                 misaligned or overlapping buffers */
+    LA_ERR_UNSUPPORTED = 2,   /* unknown dtype / algorithm / flag, op other than SUM */
+    LA_ERR_OUT_OF_MEMORY = 3, /* host or device allocation failed */
+    LA_ERR_DEVICE = 4         /* a HIP call failed (no GPU, launch error, ...) */
+} la_status_t;
+
+typedef enum {
+    LA_ALGO_RING = 0,          /* Algorithm 1, ring_allreduce, over all P ranks */
+    LA_ALGO_LANE = 1,          /* Algorithm 2, lane_allreduce: one lane per GPU, owned by the GPU's
+                                  leader process (local rank 0) */
+    LA_ALGO_LANE_MULTIPROC = 2 /* Algorithm 2 run per process ("Multi-lane Approach"): each lane
+                                  is split again into one sub-chunk per process of the GPU */
+} la_algo_t;
+
+typedef enum { LA_I32 = 0, LA_F32 = 1, LA_BF16 = 2 } la_dtype_t;
+typedef enum { LA_SUM = 0 } la_op_t; /* MPI_SUM, the only operation the paper uses */
+
+/* Flags of la_schedule_build_ex (bit set). */
+enum {
+    LA_SCHED_DEFAULT = 0u,
+    /* All-gather stages as one copy segment per (source, destination) pair, and the inter-node
+     * all-reduce as two steps (reduce-scatter of pieces, then all-gather of pieces).  Without
+     * it a reduced piece is written to all its destinations by the launch that produces or
+     * first reads it (multi-destination store), so it is read from HBM once. */
+    LA_SCHED_P2P_GATHER = 1u,
+    /* Staged exchange: before every reduce step the incoming segments are first copied into a
+     * contiguous staging area owned by the library ("the message"), and the reduce reads them
+     * from there and stores into the rank buffer.  This is the copy to and from a private
+     * device buffer that the GPUDirect runs needed (Results, "GPUDirect RDMA Analysis").
+     * Without it the reduce reads the peers' segments in place (fused pack + reduce). */
+    LA_SCHED_STAGED = 2u
+};
+
+/* Step kinds and stage labels reported by la_schedule_step_info. */
+enum { LA_STEP_REDUCE = 0, LA_STEP_COPY = 1 };
+enum {
+    LA_STAGE_S1 = 1,       /* intra-node reduce-scatter (MPI_Reduce_scatter of Algorithm 2) */
+    LA_STAGE_S2A = 2,      /* inter-node reduce-scatter of the N pieces of each part */
+    LA_STAGE_S2B = 3,      /* inter-node all-gather of the pieces */
+    LA_STAGE_S3 = 4,       /* intra-node all-gather (MPI_Allgatherv of Algorithm 2) */
+    LA_STAGE_S2 = 5,       /* S2A and S2B in one launch (multi-destination store) */
+    LA_STAGE_RING_RS = 10, /* one iteration of the first loop of Algorithm 1 */
+    LA_STAGE_RING_AG = 11, /* one iteration of the second loop of Algorithm 1 */
+    LA_STAGE_PACK = 20     /* staged exchange: copy of incoming segments into the staging area */
+};
+
+/* ---- topology ------------------------------------------------------------------------- */
+
+/* All three counts must be >= 1 and their product must fit in 2^20. */
+la_status_t la_topology_create(int nodes, int gpus_per_node, int procs_per_gpu, la_topology_t** out);
+la_status_t la_topology_destroy(la_topology_t* topo);
+int la_topology_num_ranks(const la_topology_t* topo); /* P, or -1 for NULL */
+
+/* ---- schedules ------------------------------------------------------------------------ */
+
+/*
+ * Build the per-step segment tables of an all-reduce over n elements per rank (host work only;
+ * device tables are created by the first run).  n need not be divisible: every split is
+ * balanced (part i of m gets floor(len/m) elements, plus one if i < len mod m); parts of length
+ * zero produce no segment.
+ *
+ *   ring            Algorithm 1: P chunks; P-1 reduce steps (rank r adds the chunk it receives
+ *                   from r-1 to its own copy) and P-1 copy steps.
+ *   lane, lane_multiproc
+ *                   Algorithm 2: S1 reduce-scatter inside each node (fan-in = ranks per node),
+ *                   S2 all-reduce of each part across the nodes (fan-in = nodes), S3 all-gather
+ *                   inside each node.  Operands are added in ascending communicator rank.
+ *
+ * Every schedule is checked at build time: no step reads a range that another segment of the
+ * same step writes.
+ */
+la_status_t la_schedule_build(const la_topology_t* topo, la_algo_t algo, size_t n, la_dtype_t dtype,
+                              la_schedule_t** out);
+la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size_t n, la_dtype_t dtype,
+                                 unsigned flags, la_schedule_t** out);
+la_status_t la_schedule_destroy(la_schedule_t* sched);
+
+int la_schedule_num_steps(const la_schedule_t* sched);       /* -1 for NULL */
+size_t la_schedule_staging_elems(const la_schedule_t* sched); /* elements of library-owned staging */
+
+/* Shape of one step.  Any out pointer may be NULL.  bytes_* are the algorithmic bytes of the
+ * step: sum over segments of len * fan_in (resp. fan_out) * element size. */
+la_status_t la_schedule_step_info(const la_schedule_t* sched, int step, int* kind, int* stage,
+                                  size_t* num_segments, size_t* seg_len_max, int* fan_in, int* fan_out,
+                                  size_t* bytes_read, size_t* bytes_written);
+
+/* Copy out the table of one step [host arrays sized from la_schedule_step_info]:
+ * seg_len[S]; src_buf/src_off[S*fan_in]; dst_buf/dst_off[S*fan_out].  A buffer index in [0,P)
+ * is a rank; index P is the staging area.  Offsets are in elements. */
+la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_t* seg_len, int32_t* src_buf,
+                                   uint64_t* src_off, int32_t* dst_buf, uint64_t* dst_off);
+
+/* ---- execution ------------------------------------------------------------------------ */
+
+/*
+ * In-place all-reduce: on return of the enqueued work every bufs[r] holds the element-wise SUM
+ * of the P input buffers (the MPI_Allreduce(..., MPI_SUM, ...) of the "Standard Approach"
+ * listing, with send and receive buffer the same).
+ *   bufs        [host] array of P [device] pointers, each to n elements of dtype, aligned to
+ *               the element size, pairwise disjoint.  128-bit accesses are used when all
+ *               buffers share the same address modulo 16 bytes; otherwise a slower
+ *               element-wise path runs.
+ *   n, dtype    must equal the values the schedule was built with.
+ *   hip_stream  a hipStream_t (NULL = the default stream).  The call enqueues one kernel per
+ *               step and returns without synchronising.
+ * A schedule caches the device addresses it was last run with; a call with other buffers waits
+ * for the schedule's previous work before rebinding.  Calls on one schedule must come from one
+ * thread at a time.
+ * int32 wraps; fp32 adds are IEEE, in the fixed operand order of the tables; bf16 operands are
+ * widened to fp32, summed in fp32 and rounded to nearest-even once per reduce step.
+ */
+la_status_t la_allreduce_emulated(const la_schedule_t* sched, void* const* bufs, size_t n, la_dtype_t dtype,
+                                  la_op_t op, void* hip_stream);
+
+/* Enqueue a single step of the schedule (same conventions): for per-step timing and for tests
+ * that look at intermediate states. */
+la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* const* bufs, void* hip_stream);
+
+/*
+ * k incoming segments summed into the owned segment (the local reduction that follows each
+ * received message, "GPU-Aware All-Reduce Operations" subsection), for num_segments segments
+ * in one launch.  For every segment s and i < seg_len, with o = seg_offsets[s] + i:
+ *     dst[o] = ((dst[o] + srcs[0][o]) + srcs[1][o]) + ... + srcs[k-1][o]
+ *   dst          [device] owned buffer
+ *   srcs         [host] array of k [device] pointers (k >= 0; k == 0 leaves dst unchanged)
+ *   seg_offsets  [host] array of num_segments element offsets, applied to dst and every src;
+ *                segments must not overlap each other
+ * dst and srcs must be aligned to the element size and srcs must not overlap the written
+ * ranges of dst.  Enqueues on hip_stream, no synchronisation.
+ */
+la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const size_t* seg_offsets,
+                               size_t num_segments, size_t seg_len, la_dtype_t dtype, la_op_t op,
+                               void* hip_stream);
+
+/* ---- diagnostics and tuning ----------------------------------------------------------- */
+
+const char* la_status_string(la_status_t status);
+const char* la_last_error(void);
+
+/* Launch-shape knobs for measurements (process-wide, read at each launch).
+ *   "unroll"     16-byte vectors per thread and operand: 1, 2, 4 or 8
+ *   "nontemporal" bit 0: non-temporal loads, bit 1: non-temporal stores
+ * Returns LA_ERR_INVALID_ARG for an unknown key or value.  la_tuning_get returns -1 if unknown. */
+la_status_t la_tuning_set(const char* key, int value);
+int la_tuning_get(const char* key);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LANE_ALLREDUCE_H */

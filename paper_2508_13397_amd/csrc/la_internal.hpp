@@ -1,0 +1,104 @@
+// Internal declarations shared by the host-side sources of liblaneallreduce.
+#pragma once
+
+#include <cstdarg>
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "lane_allreduce.h"
+
+namespace la {
+
+// Balanced split of `len` into `m` parts: part i has floor(len/m) elements plus one if
+// i < len mod m; offsets are the exclusive prefix sums of the counts (the counts and
+// displacement arrays c_on_chunk / D of Algorithms 1 and 2, without dropping a remainder).
+struct Part {
+    uint64_t off, cnt;
+};
+inline Part split_part(uint64_t len, uint64_t m, uint64_t i)
+{
+    const uint64_t q = len / m, rem = len % m;
+    return Part{i * q + (i < rem ? i : rem), q + (i < rem ? 1u : 0u)};
+}
+
+inline size_t dtype_size(la_dtype_t d)
+{
+    return d == LA_BF16 ? 2 : 4;
+}
+
+struct Operand {
+    int32_t buf;  // rank index, or P for the staging area
+    uint64_t off; // elements
+};
+
+// One launch: S segments, each with k sources and m destinations.
+struct Step {
+    int kind = LA_STEP_REDUCE;
+    int stage = 0;
+    int k = 0, m = 0;
+    std::vector<uint64_t> len; // [S]
+    std::vector<Operand> src;  // [S*k]
+    std::vector<Operand> dst;  // [S*m]
+    size_t num_segments() const { return len.size(); }
+};
+
+// Per-segment record the kernels read.
+struct SegInfo {
+    uint64_t len;    // elements
+    uint32_t head;   // elements before the first 16-byte boundary (vector path only)
+    uint32_t vec_ok; // 1: all operands of the segment share the address modulo 16
+};
+
+// Device view of one step, passed to the kernels by value.
+struct StepTable {
+    const SegInfo* seg;      // [S]
+    const uint64_t* src_ptr; // [S*k] byte addresses
+    const uint64_t* dst_ptr; // [S*m]
+    uint32_t k, m;
+    uint32_t tiles_per_seg;  // grid = S * tiles_per_seg blocks
+    uint32_t num_segments;
+};
+
+struct Tuning {
+    int unroll = 4;
+    int nontemporal = 0;
+};
+Tuning current_tuning();
+
+// kernels.hip
+la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream);
+uint32_t tiles_for(uint64_t max_units, int unroll); // units = 16-byte vectors per operand
+
+// error reporting
+la_status_t fail(la_status_t st, const char* fmt, ...);
+
+} // namespace la
+
+struct la_topology {
+    int nodes, gpus, procs;
+    int ranks() const { return nodes * gpus * procs; }
+    int per_node() const { return gpus * procs; }
+    int rank_of(int node, int local) const { return node * gpus * procs + local; }
+};
+
+struct la_binding; // runtime.cpp
+
+struct la_schedule {
+    la_topology topo;
+    la_algo_t algo;
+    la_dtype_t dtype;
+    uint64_t n;
+    unsigned flags;
+    uint64_t staging_elems = 0;
+    std::vector<la::Step> steps;
+    // device-side state, created by the first run
+    mutable std::mutex mu;
+    mutable la_binding* bound = nullptr;
+};
+
+namespace la {
+la_status_t generate_steps(la_schedule& s);
+la_status_t validate_hazards(const la_schedule& s);
+void release_binding(la_binding* b);
+} // namespace la

@@ -1,0 +1,439 @@
+// Execution side of the C ABI: binds a schedule to device addresses, uploads the per-step
+// tables, and enqueues one kernel per step.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "la_internal.hpp"
+
+using namespace la;
+
+#define LA_HIP(call)                                                                                  \
+    do {                                                                                              \
+        hipError_t e_ = (call);                                                                       \
+        if (e_ != hipSuccess) return fail(LA_ERR_DEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- tuning ---------------------------------------------------------------------------------
+
+namespace la {
+static std::atomic<int> g_unroll{4};
+static std::atomic<int> g_nontemporal{0};
+
+Tuning current_tuning()
+{
+    Tuning t;
+    t.unroll = g_unroll.load();
+    t.nontemporal = g_nontemporal.load();
+    return t;
+}
+} // namespace la
+
+// ---- a schedule bound to device addresses -------------------------------------------------------
+
+struct la_binding {
+    std::vector<uint64_t> bufs; // the P device addresses the tables were resolved with
+    int device = -1;
+    int unroll = 0;             // tiles_per_seg depends on it
+    void* tables = nullptr;     // one device allocation holding every step's tables
+    void* staging = nullptr;    // library-owned staging area (LA_SCHED_STAGED)
+    hipEvent_t last_use = nullptr;
+    bool used = false;
+    std::vector<StepTable> step; // device views
+};
+
+namespace la {
+
+void release_binding(la_binding* b)
+{
+    if (!b) return;
+    if (b->used && b->last_use) (void)hipEventSynchronize(b->last_use);
+    if (b->tables) (void)hipFree(b->tables);
+    if (b->staging) (void)hipFree(b->staging);
+    if (b->last_use) (void)hipEventDestroy(b->last_use);
+    delete b;
+}
+
+namespace {
+
+inline uint64_t align_up(uint64_t x, uint64_t a)
+{
+    return (x + a - 1) / a * a;
+}
+
+// Fill SegInfo for one segment from its resolved operand addresses; returns its length in
+// 16-byte units as the launch sees it.
+uint64_t describe_segment(SegInfo& si, uint64_t len, const uint64_t* ptrs, size_t count, size_t esize)
+{
+    const uint64_t vec = 16 / esize;
+    bool congruent = true;
+    for (size_t i = 1; i < count; ++i)
+        if (((ptrs[i] ^ ptrs[0]) & 15u) != 0) congruent = false;
+    si.len = len;
+    if (!congruent) {
+        si.head = 0;
+        si.vec_ok = 0;
+        return (len + vec - 1) / vec;
+    }
+    uint64_t head = ((16 - (ptrs[0] & 15u)) & 15u) / esize;
+    if (head > len) head = len;
+    si.head = (uint32_t)head;
+    si.vec_ok = 1;
+    return (len - head) / vec;
+}
+
+struct HostTables {
+    std::vector<unsigned char> blob;
+    std::vector<StepTable> view; // pointers are offsets until relocated
+};
+
+// Resolve every (buffer, offset) operand of `steps` against `base` addresses and lay the tables
+// out in one blob.  base[P] is the staging area.
+void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>& base, size_t esize, int unroll,
+                    HostTables& out)
+{
+    uint64_t total = 0;
+    std::vector<uint64_t> seg_at(steps.size()), src_at(steps.size()), dst_at(steps.size());
+    for (size_t i = 0; i < steps.size(); ++i) {
+        const Step& p = steps[i];
+        const size_t S = p.num_segments();
+        seg_at[i] = total;
+        total = align_up(total + S * sizeof(SegInfo), 256);
+        src_at[i] = total;
+        total = align_up(total + S * p.k * sizeof(uint64_t), 256);
+        dst_at[i] = total;
+        total = align_up(total + S * p.m * sizeof(uint64_t), 256);
+    }
+    out.blob.assign(total ? total : 256, 0);
+    out.view.resize(steps.size());
+    std::vector<uint64_t> all;
+    for (size_t i = 0; i < steps.size(); ++i) {
+        const Step& p = steps[i];
+        const size_t S = p.num_segments();
+        SegInfo* seg = reinterpret_cast<SegInfo*>(out.blob.data() + seg_at[i]);
+        uint64_t* sp = reinterpret_cast<uint64_t*>(out.blob.data() + src_at[i]);
+        uint64_t* dp = reinterpret_cast<uint64_t*>(out.blob.data() + dst_at[i]);
+        uint64_t longest = 0;
+        for (size_t g = 0; g < S; ++g) {
+            all.clear();
+            for (int t = 0; t < p.k; ++t) {
+                const Operand& o = p.src[g * p.k + t];
+                sp[g * p.k + t] = base[o.buf] + o.off * esize;
+                all.push_back(sp[g * p.k + t]);
+            }
+            for (int d = 0; d < p.m; ++d) {
+                const Operand& o = p.dst[g * p.m + d];
+                dp[g * p.m + d] = base[o.buf] + o.off * esize;
+                all.push_back(dp[g * p.m + d]);
+            }
+            longest = std::max(longest, describe_segment(seg[g], p.len[g], all.data(), all.size(), esize));
+        }
+        StepTable& v = out.view[i];
+        v.seg = reinterpret_cast<const SegInfo*>(seg_at[i]);
+        v.src_ptr = reinterpret_cast<const uint64_t*>(src_at[i]);
+        v.dst_ptr = reinterpret_cast<const uint64_t*>(dst_at[i]);
+        v.k = (uint32_t)p.k;
+        v.m = (uint32_t)p.m;
+        v.num_segments = (uint32_t)S;
+        v.tiles_per_seg = tiles_for(longest, unroll);
+    }
+}
+
+void relocate(std::vector<StepTable>& view, const void* device_base)
+{
+    const uint64_t b = reinterpret_cast<uint64_t>(device_base);
+    for (StepTable& v : view) {
+        v.seg = reinterpret_cast<const SegInfo*>(b + reinterpret_cast<uint64_t>(v.seg));
+        v.src_ptr = reinterpret_cast<const uint64_t*>(b + reinterpret_cast<uint64_t>(v.src_ptr));
+        v.dst_ptr = reinterpret_cast<const uint64_t*>(b + reinterpret_cast<uint64_t>(v.dst_ptr));
+    }
+}
+
+la_status_t check_buffers(const la_schedule& s, void* const* bufs, std::vector<uint64_t>& addr)
+{
+    const int P = s.topo.ranks();
+    const size_t e = dtype_size(s.dtype);
+    addr.resize(P + 1);
+    for (int r = 0; r < P; ++r) {
+        if (!bufs[r]) return fail(LA_ERR_INVALID_ARG, "bufs[%d] is NULL", r);
+        addr[r] = reinterpret_cast<uint64_t>(bufs[r]);
+        if (addr[r] % e) return fail(LA_ERR_INVALID_ARG, "bufs[%d] is not aligned to the element size", r);
+    }
+    std::vector<uint64_t> sorted(addr.begin(), addr.begin() + P);
+    std::sort(sorted.begin(), sorted.end());
+    for (int r = 1; r < P; ++r)
+        if (sorted[r] < sorted[r - 1] + s.n * e)
+            return fail(LA_ERR_INVALID_ARG, "rank buffers overlap (or one pointer was passed twice)");
+    addr[P] = 0;
+    return LA_OK;
+}
+
+// Make sched.bound describe `addr` on the current device with the current tile shape.
+la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning& tune)
+{
+    int dev = -1;
+    LA_HIP(hipGetDevice(&dev));
+    la_binding* b = s.bound;
+    const int P = s.topo.ranks();
+    if (b && b->device == dev && b->unroll == tune.unroll && b->bufs.size() == (size_t)P &&
+        std::equal(addr.begin(), addr.begin() + P, b->bufs.begin()))
+        return LA_OK;
+    if (b && b->used) LA_HIP(hipEventSynchronize(b->last_use)); // earlier work still reads the tables
+    if (b && b->device != dev) {
+        release_binding(b);
+        s.bound = b = nullptr;
+    }
+    if (!b) {
+        b = new (std::nothrow) la_binding;
+        if (!b) return fail(LA_ERR_OUT_OF_MEMORY, "out of host memory");
+        b->device = dev;
+        s.bound = b;
+        LA_HIP(hipEventCreateWithFlags(&b->last_use, hipEventDisableTiming));
+    }
+    const size_t e = dtype_size(s.dtype);
+    if (s.staging_elems && !b->staging) {
+        if (hipMalloc(&b->staging, s.staging_elems * e) != hipSuccess) {
+            b->staging = nullptr;
+            return fail(LA_ERR_OUT_OF_MEMORY, "cannot allocate %llu bytes of staging",
+                        (unsigned long long)(s.staging_elems * e));
+        }
+    }
+    addr[P] = reinterpret_cast<uint64_t>(b->staging);
+    HostTables ht;
+    try {
+        resolve_tables(s.steps, addr, e, tune.unroll, ht);
+    } catch (const std::bad_alloc&) {
+        return fail(LA_ERR_OUT_OF_MEMORY, "out of host memory");
+    }
+    if (b->tables) {
+        LA_HIP(hipFree(b->tables));
+        b->tables = nullptr;
+    }
+    b->bufs.clear();
+    if (hipMalloc(&b->tables, ht.blob.size()) != hipSuccess) {
+        b->tables = nullptr;
+        return fail(LA_ERR_OUT_OF_MEMORY, "cannot allocate %zu bytes of device tables", ht.blob.size());
+    }
+    LA_HIP(hipMemcpy(b->tables, ht.blob.data(), ht.blob.size(), hipMemcpyHostToDevice));
+    relocate(ht.view, b->tables);
+    b->step = std::move(ht.view);
+    b->bufs.assign(addr.begin(), addr.begin() + P);
+    b->unroll = tune.unroll;
+    b->used = false;
+    return LA_OK;
+}
+
+la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, int first, int last, void* hip_stream)
+{
+    std::vector<uint64_t> addr;
+    la_status_t st = check_buffers(*sched, bufs, addr);
+    if (st != LA_OK) return st;
+    std::lock_guard<std::mutex> lock(sched->mu);
+    const Tuning tune = current_tuning();
+    st = bind(*sched, addr, tune);
+    if (st != LA_OK) return st;
+    la_binding* b = sched->bound;
+    for (int i = first; i < last; ++i) {
+        st = launch_step(b->step[i], sched->dtype, tune, hip_stream);
+        if (st != LA_OK) return st;
+    }
+    LA_HIP(hipEventRecord(b->last_use, static_cast<hipStream_t>(hip_stream)));
+    b->used = true;
+    return LA_OK;
+}
+
+} // namespace
+} // namespace la
+
+// ---- pinned upload chunks for one-shot tables ----------------------------------------------------
+// la_reduce_segments builds its tables in pinned host memory so that the upload is a true
+// asynchronous copy and the call never waits for the GPU.  A chunk is reused once the copy that
+// read it has completed (its event has fired).
+
+namespace la {
+namespace {
+
+struct PinnedChunk {
+    void* host = nullptr;
+    uint64_t bytes = 0;
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+    int device = -1;
+};
+
+std::mutex g_pool_mu;
+std::vector<PinnedChunk*> g_pool;
+
+la_status_t acquire_pinned(uint64_t bytes, PinnedChunk** out)
+{
+    int dev = -1;
+    LA_HIP(hipGetDevice(&dev));
+    for (PinnedChunk* c : g_pool) {
+        if (c->device != dev || c->bytes < bytes) continue;
+        if (c->in_flight) {
+            if (hipEventQuery(c->done) != hipSuccess) continue;
+            c->in_flight = false;
+        }
+        *out = c;
+        return LA_OK;
+    }
+    PinnedChunk* c = new (std::nothrow) PinnedChunk;
+    if (!c) return fail(LA_ERR_OUT_OF_MEMORY, "out of host memory");
+    c->bytes = std::max<uint64_t>(align_up(bytes, 4096), 64 * 1024);
+    c->device = dev;
+    if (hipHostMalloc(&c->host, c->bytes, hipHostMallocDefault) != hipSuccess) {
+        delete c;
+        return fail(LA_ERR_OUT_OF_MEMORY, "cannot allocate %llu bytes of pinned host memory",
+                    (unsigned long long)bytes);
+    }
+    if (hipEventCreateWithFlags(&c->done, hipEventDisableTiming) != hipSuccess) {
+        (void)hipHostFree(c->host);
+        delete c;
+        return fail(LA_ERR_DEVICE, "hipEventCreate failed");
+    }
+    g_pool.push_back(c);
+    *out = c;
+    return LA_OK;
+}
+
+} // namespace
+} // namespace la
+
+// ---- C ABI --------------------------------------------------------------------------------------
+
+extern "C" {
+
+la_status_t la_allreduce_emulated(const la_schedule_t* sched, void* const* bufs, size_t n, la_dtype_t dtype,
+                                  la_op_t op, void* hip_stream)
+{
+    if (!sched) return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated: schedule is NULL");
+    if (!bufs) return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated: bufs is NULL");
+    if (op != LA_SUM) return fail(LA_ERR_UNSUPPORTED, "la_allreduce_emulated: only LA_SUM is supported");
+    if (dtype != LA_I32 && dtype != LA_F32 && dtype != LA_BF16)
+        return fail(LA_ERR_UNSUPPORTED, "la_allreduce_emulated: unknown dtype %d", (int)dtype);
+    if (n != sched->n || dtype != sched->dtype)
+        return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated: n/dtype differ from the schedule's (%llu, %d)",
+                    (unsigned long long)sched->n, (int)sched->dtype);
+    return run_steps(sched, bufs, 0, (int)sched->steps.size(), hip_stream);
+}
+
+la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* const* bufs, void* hip_stream)
+{
+    if (!sched) return fail(LA_ERR_INVALID_ARG, "la_schedule_run_step: schedule is NULL");
+    if (!bufs) return fail(LA_ERR_INVALID_ARG, "la_schedule_run_step: bufs is NULL");
+    if (step < 0 || step >= (int)sched->steps.size())
+        return fail(LA_ERR_INVALID_ARG, "la_schedule_run_step: step %d out of range", step);
+    return run_steps(sched, bufs, step, step + 1, hip_stream);
+}
+
+la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const size_t* seg_offsets,
+                               size_t num_segments, size_t seg_len, la_dtype_t dtype, la_op_t op,
+                               void* hip_stream)
+{
+    if (op != LA_SUM) return fail(LA_ERR_UNSUPPORTED, "la_reduce_segments: only LA_SUM is supported");
+    if (dtype != LA_I32 && dtype != LA_F32 && dtype != LA_BF16)
+        return fail(LA_ERR_UNSUPPORTED, "la_reduce_segments: unknown dtype %d", (int)dtype);
+    if (k < 0) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: k is negative");
+    if (!dst) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: dst is NULL");
+    if (k > 0 && !srcs) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: srcs is NULL");
+    if (num_segments > 0 && !seg_offsets) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: seg_offsets is NULL");
+    const size_t e = dtype_size(dtype);
+    const uint64_t d = reinterpret_cast<uint64_t>(dst);
+    if (d % e) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: dst is not aligned to the element size");
+    for (int t = 0; t < k; ++t) {
+        if (!srcs[t]) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: srcs[%d] is NULL", t);
+        if (reinterpret_cast<uint64_t>(srcs[t]) % e)
+            return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: srcs[%d] is not aligned to the element size", t);
+        if (srcs[t] == dst) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: srcs[%d] aliases dst", t);
+    }
+    if (k == 0 || num_segments == 0 || seg_len == 0) return LA_OK; // nothing to add
+    if (num_segments > 0xffffffffull) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: too many segments");
+    {
+        std::vector<size_t> sorted(seg_offsets, seg_offsets + num_segments);
+        std::sort(sorted.begin(), sorted.end());
+        for (size_t s = 1; s < num_segments; ++s)
+            if (sorted[s] < sorted[s - 1] + seg_len)
+                return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: segments overlap");
+    }
+
+    // Tables for one step with k+1 sources (dst first) and one destination.
+    const Tuning tune = current_tuning();
+    const size_t K = (size_t)k + 1;
+    const uint64_t seg_bytes = align_up(num_segments * sizeof(SegInfo), 256);
+    const uint64_t src_bytes = align_up(num_segments * K * sizeof(uint64_t), 256);
+    const uint64_t dst_bytes = align_up(num_segments * sizeof(uint64_t), 256);
+    const uint64_t total_bytes = seg_bytes + src_bytes + dst_bytes;
+    std::lock_guard<std::mutex> lock(g_pool_mu);
+    PinnedChunk* chunk = nullptr;
+    la_status_t pst = acquire_pinned(total_bytes, &chunk);
+    if (pst != LA_OK) return pst;
+    unsigned char* blob = static_cast<unsigned char*>(chunk->host);
+    SegInfo* seg = reinterpret_cast<SegInfo*>(blob);
+    uint64_t* sp = reinterpret_cast<uint64_t*>(blob + seg_bytes);
+    uint64_t* dp = reinterpret_cast<uint64_t*>(blob + seg_bytes + src_bytes);
+    uint64_t longest = 0;
+    for (size_t s = 0; s < num_segments; ++s) {
+        const uint64_t byte_off = (uint64_t)seg_offsets[s] * e;
+        sp[s * K] = d + byte_off;
+        for (int t = 0; t < k; ++t) sp[s * K + 1 + t] = reinterpret_cast<uint64_t>(srcs[t]) + byte_off;
+        dp[s] = d + byte_off;
+        longest = std::max(longest, describe_segment(seg[s], seg_len, sp + s * K, K, e));
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    void* dev = nullptr;
+    if (hipMallocAsync(&dev, total_bytes, stream) != hipSuccess)
+        return fail(LA_ERR_OUT_OF_MEMORY, "la_reduce_segments: cannot allocate %llu bytes of device tables",
+                    (unsigned long long)total_bytes);
+    hipError_t he = hipMemcpyAsync(dev, chunk->host, total_bytes, hipMemcpyHostToDevice, stream);
+    if (he == hipSuccess) he = hipEventRecord(chunk->done, stream); // the chunk is free again after the copy
+    if (he != hipSuccess) {
+        (void)hipFreeAsync(dev, stream);
+        return fail(LA_ERR_DEVICE, "la_reduce_segments: table upload failed: %s", hipGetErrorString(he));
+    }
+    chunk->in_flight = true;
+    StepTable t;
+    const uint64_t b = reinterpret_cast<uint64_t>(dev);
+    t.seg = reinterpret_cast<const SegInfo*>(b);
+    t.src_ptr = reinterpret_cast<const uint64_t*>(b + seg_bytes);
+    t.dst_ptr = reinterpret_cast<const uint64_t*>(b + seg_bytes + src_bytes);
+    t.k = (uint32_t)K;
+    t.m = 1;
+    t.num_segments = (uint32_t)num_segments;
+    t.tiles_per_seg = tiles_for(longest, tune.unroll);
+    la_status_t st = launch_step(t, dtype, tune, hip_stream);
+    (void)hipFreeAsync(dev, stream); // stream-ordered: freed after the kernel has run
+    return st;
+}
+
+la_status_t la_tuning_set(const char* key, int value)
+{
+    if (!key) return fail(LA_ERR_INVALID_ARG, "la_tuning_set: key is NULL");
+    const std::string k(key);
+    if (k == "unroll") {
+        if (value != 1 && value != 2 && value != 4 && value != 8)
+            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: unroll must be 1, 2, 4 or 8");
+        g_unroll.store(value);
+        return LA_OK;
+    }
+    if (k == "nontemporal") {
+        if (value < 0 || value > 3) return fail(LA_ERR_INVALID_ARG, "la_tuning_set: nontemporal must be 0..3");
+        g_nontemporal.store(value);
+        return LA_OK;
+    }
+    return fail(LA_ERR_INVALID_ARG, "la_tuning_set: unknown key '%s'", key);
+}
+
+int la_tuning_get(const char* key)
+{
+    if (!key) return -1;
+    const std::string k(key);
+    if (k == "unroll") return g_unroll.load();
+    if (k == "nontemporal") return g_nontemporal.load();
+    return -1;
+}
+
+} // extern "C"

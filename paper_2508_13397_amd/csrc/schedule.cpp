@@ -1,0 +1,453 @@
+// Topology and schedule generator: turns (nodes, GPUs per node, processes per GPU) into the
+// per-step segment tables of Algorithm 1 (ring_allreduce) and Algorithm 2 (lane_allreduce, also
+// in its multiple-processes-per-GPU form).  Host code only.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "la_internal.hpp"
+
+namespace la {
+
+static thread_local char g_err[512] = "";
+
+la_status_t fail(la_status_t st, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+namespace {
+
+inline int imod(int a, int m)
+{
+    const int r = a % m;
+    return r < 0 ? r + m : r;
+}
+
+// Sequential allocator of staging slots (elements).
+struct Staging {
+    uint64_t next = 0, peak = 0;
+    uint64_t take(uint64_t cnt)
+    {
+        const uint64_t at = next;
+        next += (cnt + 63) & ~uint64_t(63); // keep slots 16-byte aligned for every dtype
+        peak = std::max(peak, next);
+        return at;
+    }
+    void reset() { next = 0; }
+};
+
+// A reduce whose operands are `ops` (in summation order) into `dst`; with LA_SCHED_STAGED the
+// operands that are not already in the destination's own buffer are first copied to staging.
+struct ReduceBuilder {
+    const la_schedule& s;
+    Step pack, red;
+    Staging& st;
+    bool staged;
+    int P;
+    ReduceBuilder(const la_schedule& sc, Staging& stg, int stage, int k, int m) : s(sc), st(stg)
+    {
+        staged = (sc.flags & LA_SCHED_STAGED) != 0;
+        P = sc.topo.ranks();
+        pack.kind = LA_STEP_COPY;
+        pack.stage = LA_STAGE_PACK;
+        pack.k = 1;
+        pack.m = 1;
+        red.kind = LA_STEP_REDUCE;
+        red.stage = stage;
+        red.k = k;
+        red.m = m;
+    }
+    // ops.size() == k, dsts.size() == m; `home` is the rank that performs the reduction
+    void add(uint64_t len, const std::vector<Operand>& ops, const std::vector<Operand>& dsts, int home)
+    {
+        if (len == 0) return;
+        red.len.push_back(len);
+        for (const Operand& o : ops) {
+            if (staged && o.buf != home) {
+                const uint64_t slot = st.take(len);
+                pack.len.push_back(len);
+                pack.src.push_back(o);
+                pack.dst.push_back(Operand{P, slot});
+                red.src.push_back(Operand{P, slot});
+            } else {
+                red.src.push_back(o);
+            }
+        }
+        for (const Operand& d : dsts) red.dst.push_back(d);
+    }
+    void emit(std::vector<Step>& out)
+    {
+        if (red.len.empty()) return;
+        if (staged && !pack.len.empty()) out.push_back(std::move(pack));
+        out.push_back(std::move(red));
+        st.reset(); // the next reduce step may reuse the staging area
+    }
+};
+
+void push_copy(Step& c, uint64_t len, Operand from, Operand to)
+{
+    if (len == 0) return;
+    c.len.push_back(len);
+    c.src.push_back(from);
+    c.dst.push_back(to);
+}
+
+// ---- Algorithm 1 ---------------------------------------------------------------------------
+// Chunk c starts at rank c and travels to c+1, c+2, ...  In reduce iteration i rank r receives
+// chunk rp = r-1-i from its predecessor and adds it to its own copy; in gather iteration i it
+// receives the finished chunk r-i.  One launch holds the P segments of an iteration.
+void gen_ring(la_schedule& s, Staging& st)
+{
+    const int P = s.topo.ranks();
+    std::vector<Part> chunk(P);
+    for (int c = 0; c < P; ++c) chunk[c] = split_part(s.n, P, c);
+    for (int i = 0; i < P - 1; ++i) {
+        ReduceBuilder rb(s, st, LA_STAGE_RING_RS, 2, 1);
+        for (int r = 0; r < P; ++r) {
+            const Part c = chunk[imod(r - 1 - i, P)];
+            const int prev = imod(r - 1, P);
+            rb.add(c.cnt, {Operand{r, c.off}, Operand{prev, c.off}}, {Operand{r, c.off}}, r);
+        }
+        rb.emit(s.steps);
+    }
+    for (int i = 0; i < P - 1; ++i) {
+        Step cp;
+        cp.kind = LA_STEP_COPY;
+        cp.stage = LA_STAGE_RING_AG;
+        cp.k = cp.m = 1;
+        for (int r = 0; r < P; ++r) {
+            const Part c = chunk[imod(r - i, P)];
+            push_copy(cp, c.cnt, Operand{imod(r - 1, P), c.off}, Operand{r, c.off});
+        }
+        if (!cp.len.empty()) s.steps.push_back(std::move(cp));
+    }
+}
+
+// ---- Algorithm 2 ---------------------------------------------------------------------------
+// The buffer is cut into J parts: one lane per GPU, and with the per-process split one
+// sub-chunk per process inside each lane.  Part j is owned, on every node, by the process with
+// node-local index owner(j).
+void gen_lane(la_schedule& s, Staging& st, bool split_procs)
+{
+    const la_topology& t = s.topo;
+    const int N = t.nodes, G = t.gpus, Q = t.procs, R = G * Q;
+    const int J = split_procs ? R : G;
+    const bool p2p = (s.flags & LA_SCHED_P2P_GATHER) != 0;
+    auto owner = [&](int j) { return split_procs ? j : j * Q; };
+    std::vector<Part> part(J);
+    for (int j = 0; j < J; ++j) {
+        if (!split_procs) {
+            part[j] = split_part(s.n, G, j);
+        } else {
+            const Part lane = split_part(s.n, G, j / Q);
+            const Part sub = split_part(lane.cnt, Q, j % Q);
+            part[j] = Part{lane.off + sub.off, sub.cnt};
+        }
+    }
+
+    // S1: reduce-scatter on the node group; the owner adds the R node-local copies of its part
+    // in ascending node-local index (its own copy taking its place in that order).
+    if (R > 1) {
+        ReduceBuilder rb(s, st, LA_STAGE_S1, R, 1);
+        for (int node = 0; node < N; ++node)
+            for (int j = 0; j < J; ++j) {
+                std::vector<Operand> ops(R);
+                for (int l = 0; l < R; ++l) ops[l] = Operand{t.rank_of(node, l), part[j].off};
+                const int me = t.rank_of(node, owner(j));
+                rb.add(part[j].cnt, ops, {Operand{me, part[j].off}}, me);
+            }
+        rb.emit(s.steps);
+    }
+
+    // S2: all-reduce of part j among its N owners (the lane communicator): member v reduces
+    // piece v of the part over the N members in ascending node order, then every member gets
+    // every piece.
+    if (N > 1) {
+        ReduceBuilder rb(s, st, p2p ? LA_STAGE_S2A : LA_STAGE_S2, N, p2p ? 1 : N);
+        Step ag;
+        ag.kind = LA_STEP_COPY;
+        ag.stage = LA_STAGE_S2B;
+        ag.k = ag.m = 1;
+        for (int j = 0; j < J; ++j)
+            for (int v = 0; v < N; ++v) {
+                const Part piece = split_part(part[j].cnt, N, v);
+                const uint64_t off = part[j].off + piece.off;
+                std::vector<Operand> ops(N), dsts;
+                for (int w = 0; w < N; ++w) ops[w] = Operand{t.rank_of(w, owner(j)), off};
+                const int me = t.rank_of(v, owner(j));
+                dsts.push_back(Operand{me, off});
+                for (int w = 0; w < N; ++w) {
+                    if (w == v) continue;
+                    if (p2p)
+                        push_copy(ag, piece.cnt, Operand{me, off}, Operand{t.rank_of(w, owner(j)), off});
+                    else
+                        dsts.push_back(Operand{t.rank_of(w, owner(j)), off});
+                }
+                rb.add(piece.cnt, ops, dsts, me);
+            }
+        rb.emit(s.steps);
+        if (p2p && !ag.len.empty()) s.steps.push_back(std::move(ag));
+    }
+
+    // S3: all-gather on the node group: every owner's part goes to the other R-1 processes.
+    if (R > 1) {
+        Step ag;
+        ag.kind = LA_STEP_COPY;
+        ag.stage = LA_STAGE_S3;
+        ag.k = 1;
+        ag.m = p2p ? 1 : R - 1;
+        for (int node = 0; node < N; ++node)
+            for (int j = 0; j < J; ++j) {
+                if (part[j].cnt == 0) continue;
+                const Operand from{t.rank_of(node, owner(j)), part[j].off};
+                if (!p2p) {
+                    ag.len.push_back(part[j].cnt);
+                    ag.src.push_back(from);
+                }
+                for (int l = 0; l < R; ++l) {
+                    if (l == owner(j)) continue;
+                    const Operand to{t.rank_of(node, l), part[j].off};
+                    if (p2p)
+                        push_copy(ag, part[j].cnt, from, to);
+                    else
+                        ag.dst.push_back(to);
+                }
+            }
+        if (!ag.len.empty()) s.steps.push_back(std::move(ag));
+    }
+}
+
+} // namespace
+
+la_status_t generate_steps(la_schedule& s)
+{
+    Staging st;
+    switch (s.algo) {
+    case LA_ALGO_RING: gen_ring(s, st); break;
+    case LA_ALGO_LANE: gen_lane(s, st, false); break;
+    case LA_ALGO_LANE_MULTIPROC: gen_lane(s, st, true); break;
+    default: return fail(LA_ERR_UNSUPPORTED, "unknown algorithm %d", (int)s.algo);
+    }
+    s.staging_elems = st.peak;
+    for (const Step& p : s.steps) {
+        const size_t S = p.num_segments();
+        if (p.src.size() != S * (size_t)p.k || p.dst.size() != S * (size_t)p.m)
+            return fail(LA_ERR_INVALID_ARG, "internal: malformed step table");
+    }
+    return LA_OK;
+}
+
+// No segment of a step may write a range that another segment of the same step reads or
+// writes; inside a segment a destination may coincide exactly with a source (in-place
+// element-wise update) but not overlap it partially.
+la_status_t validate_hazards(const la_schedule& s)
+{
+    struct Iv {
+        int32_t buf;
+        uint64_t lo, hi;
+        uint32_t seg;
+        bool write;
+    };
+    const uint64_t limit_stage = s.staging_elems;
+    const int P = s.topo.ranks();
+    std::vector<Iv> iv;
+    for (size_t si = 0; si < s.steps.size(); ++si) {
+        const Step& p = s.steps[si];
+        iv.clear();
+        for (size_t g = 0; g < p.num_segments(); ++g) {
+            for (int t = 0; t < p.k; ++t) {
+                const Operand& o = p.src[g * p.k + t];
+                iv.push_back(Iv{o.buf, o.off, o.off + p.len[g], (uint32_t)g, false});
+            }
+            for (int d = 0; d < p.m; ++d) {
+                const Operand& o = p.dst[g * p.m + d];
+                iv.push_back(Iv{o.buf, o.off, o.off + p.len[g], (uint32_t)g, true});
+            }
+        }
+        for (const Iv& x : iv) {
+            const uint64_t cap = x.buf == P ? limit_stage : s.n;
+            if (x.buf < 0 || x.buf > P || x.hi > cap)
+                return fail(LA_ERR_INVALID_ARG, "internal: step %zu has a range outside its buffer", si);
+        }
+        std::sort(iv.begin(), iv.end(), [](const Iv& a, const Iv& b) {
+            if (a.buf != b.buf) return a.buf < b.buf;
+            if (a.lo != b.lo) return a.lo < b.lo;
+            return a.hi < b.hi;
+        });
+        // sweep: compare each interval with the ones that start before its end
+        for (size_t a = 0; a < iv.size(); ++a) {
+            for (size_t b = a + 1; b < iv.size() && iv[b].buf == iv[a].buf && iv[b].lo < iv[a].hi; ++b) {
+                if (!iv[a].write && !iv[b].write) continue;
+                const bool same_seg = iv[a].seg == iv[b].seg;
+                const bool identical = iv[a].lo == iv[b].lo && iv[a].hi == iv[b].hi;
+                if (same_seg && identical && !(iv[a].write && iv[b].write)) continue;
+                return fail(LA_ERR_INVALID_ARG, "internal: step %zu has a read/write hazard on buffer %d", si,
+                            iv[a].buf);
+            }
+        }
+    }
+    return LA_OK;
+}
+
+} // namespace la
+
+// ---- C ABI: topology and schedule objects ------------------------------------------------------
+
+using namespace la;
+
+extern "C" {
+
+la_status_t la_topology_create(int nodes, int gpus_per_node, int procs_per_gpu, la_topology_t** out)
+{
+    if (!out) return fail(LA_ERR_INVALID_ARG, "la_topology_create: out is NULL");
+    *out = nullptr;
+    if (nodes < 1 || gpus_per_node < 1 || procs_per_gpu < 1)
+        return fail(LA_ERR_INVALID_ARG, "la_topology_create: counts must be >= 1 (got %d, %d, %d)", nodes,
+                    gpus_per_node, procs_per_gpu);
+    const uint64_t P = (uint64_t)nodes * (uint64_t)gpus_per_node * (uint64_t)procs_per_gpu;
+    if (P > (1u << 20)) return fail(LA_ERR_INVALID_ARG, "la_topology_create: more than 2^20 ranks");
+    la_topology* t = new (std::nothrow) la_topology{nodes, gpus_per_node, procs_per_gpu};
+    if (!t) return fail(LA_ERR_OUT_OF_MEMORY, "la_topology_create: out of host memory");
+    *out = t;
+    return LA_OK;
+}
+
+la_status_t la_topology_destroy(la_topology_t* topo)
+{
+    delete topo;
+    return LA_OK;
+}
+
+int la_topology_num_ranks(const la_topology_t* topo)
+{
+    return topo ? topo->ranks() : -1;
+}
+
+la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size_t n, la_dtype_t dtype,
+                                 unsigned flags, la_schedule_t** out)
+{
+    if (!out) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: out is NULL");
+    *out = nullptr;
+    if (!topo) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: topology is NULL");
+    if (n == 0) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: n is 0");
+    if (n > (uint64_t(1) << 40)) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: n exceeds 2^40");
+    if (dtype != LA_I32 && dtype != LA_F32 && dtype != LA_BF16)
+        return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown dtype %d", (int)dtype);
+    if (algo != LA_ALGO_RING && algo != LA_ALGO_LANE && algo != LA_ALGO_LANE_MULTIPROC)
+        return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown algorithm %d", (int)algo);
+    if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED))
+        return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown flag bits 0x%x", flags);
+    la_schedule* s = new (std::nothrow) la_schedule;
+    if (!s) return fail(LA_ERR_OUT_OF_MEMORY, "la_schedule_build: out of host memory");
+    s->topo = *topo;
+    s->algo = algo;
+    s->dtype = dtype;
+    s->n = n;
+    s->flags = flags;
+    la_status_t st;
+    try {
+        st = generate_steps(*s);
+        if (st == LA_OK) st = validate_hazards(*s);
+    } catch (const std::bad_alloc&) {
+        st = fail(LA_ERR_OUT_OF_MEMORY, "la_schedule_build: out of host memory");
+    }
+    if (st != LA_OK) {
+        delete s;
+        return st;
+    }
+    *out = s;
+    return LA_OK;
+}
+
+la_status_t la_schedule_build(const la_topology_t* topo, la_algo_t algo, size_t n, la_dtype_t dtype,
+                              la_schedule_t** out)
+{
+    return la_schedule_build_ex(topo, algo, n, dtype, LA_SCHED_DEFAULT, out);
+}
+
+la_status_t la_schedule_destroy(la_schedule_t* sched)
+{
+    if (!sched) return LA_OK;
+    release_binding(sched->bound);
+    delete sched;
+    return LA_OK;
+}
+
+int la_schedule_num_steps(const la_schedule_t* sched)
+{
+    return sched ? (int)sched->steps.size() : -1;
+}
+
+size_t la_schedule_staging_elems(const la_schedule_t* sched)
+{
+    return sched ? (size_t)sched->staging_elems : 0;
+}
+
+la_status_t la_schedule_step_info(const la_schedule_t* sched, int step, int* kind, int* stage,
+                                  size_t* num_segments, size_t* seg_len_max, int* fan_in, int* fan_out,
+                                  size_t* bytes_read, size_t* bytes_written)
+{
+    if (!sched) return fail(LA_ERR_INVALID_ARG, "la_schedule_step_info: schedule is NULL");
+    if (step < 0 || step >= (int)sched->steps.size())
+        return fail(LA_ERR_INVALID_ARG, "la_schedule_step_info: step %d out of range", step);
+    const Step& p = sched->steps[step];
+    uint64_t total = 0, longest = 0;
+    for (uint64_t l : p.len) {
+        total += l;
+        longest = std::max(longest, l);
+    }
+    const size_t e = dtype_size(sched->dtype);
+    if (kind) *kind = p.kind;
+    if (stage) *stage = p.stage;
+    if (num_segments) *num_segments = p.num_segments();
+    if (seg_len_max) *seg_len_max = (size_t)longest;
+    if (fan_in) *fan_in = p.k;
+    if (fan_out) *fan_out = p.m;
+    if (bytes_read) *bytes_read = (size_t)(total * (uint64_t)p.k * e);
+    if (bytes_written) *bytes_written = (size_t)(total * (uint64_t)p.m * e);
+    return LA_OK;
+}
+
+la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_t* seg_len, int32_t* src_buf,
+                                   uint64_t* src_off, int32_t* dst_buf, uint64_t* dst_off)
+{
+    if (!sched) return fail(LA_ERR_INVALID_ARG, "la_schedule_step_table: schedule is NULL");
+    if (step < 0 || step >= (int)sched->steps.size())
+        return fail(LA_ERR_INVALID_ARG, "la_schedule_step_table: step %d out of range", step);
+    const Step& p = sched->steps[step];
+    if (seg_len) std::copy(p.len.begin(), p.len.end(), seg_len);
+    for (size_t i = 0; i < p.src.size(); ++i) {
+        if (src_buf) src_buf[i] = p.src[i].buf;
+        if (src_off) src_off[i] = p.src[i].off;
+    }
+    for (size_t i = 0; i < p.dst.size(); ++i) {
+        if (dst_buf) dst_buf[i] = p.dst[i].buf;
+        if (dst_off) dst_off[i] = p.dst[i].off;
+    }
+    return LA_OK;
+}
+
+const char* la_status_string(la_status_t status)
+{
+    switch (status) {
+    case LA_OK: return "LA_OK";
+    case LA_ERR_INVALID_ARG: return "LA_ERR_INVALID_ARG";
+    case LA_ERR_UNSUPPORTED: return "LA_ERR_UNSUPPORTED";
+    case LA_ERR_OUT_OF_MEMORY: return "LA_ERR_OUT_OF_MEMORY";
+    case LA_ERR_DEVICE: return "LA_ERR_DEVICE";
+    }
+    return "LA_ERR_UNKNOWN";
+}
+
+const char* la_last_error(void)
+{
+    return g_err;
+}
+
+} // extern "C"

@@ -1,0 +1,319 @@
+"""Host logic of the library, on the CPU: the C ABI loads and exports what the header declares,
+argument errors are reported, and the generated step tables -- executed here by a small numpy
+interpreter that knows nothing but "sum the sources in order, store to the destinations" --
+reproduce the oracle bit for bit.  No GPU call is made."""
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2508_13397_amd as la
+from paper_2508_13397_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ALGOS = ("ring", "lane", "lane_multiproc")
+FLAG_SETS = (la.LA_SCHED_DEFAULT, la.LA_SCHED_P2P_GATHER, la.LA_SCHED_STAGED,
+             la.LA_SCHED_P2P_GATHER | la.LA_SCHED_STAGED)
+
+
+# ----------------------------------------------------------------------------- ABI surface
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "lane_allreduce.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(la_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(la.EXPORTS)
+    L = la.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings():
+    assert la.la_status_string(la.LA_OK) == "LA_OK"
+    assert la.la_status_string(la.LA_ERR_INVALID_ARG) == "LA_ERR_INVALID_ARG"
+    assert la.la_status_string(la.LA_ERR_UNSUPPORTED) == "LA_ERR_UNSUPPORTED"
+    assert la.la_status_string(la.LA_ERR_OUT_OF_MEMORY) == "LA_ERR_OUT_OF_MEMORY"
+    assert la.la_status_string(la.LA_ERR_DEVICE) == "LA_ERR_DEVICE"
+
+
+@pytest.mark.parametrize("dims", [(0, 1, 1), (1, 0, 1), (1, 1, 0), (-2, 4, 1), (1 << 10, 1 << 10, 2)])
+def test_topology_rejects_bad_dimensions(dims):
+    with pytest.raises(la.LaError) as e:
+        la.la_topology_create(*dims)
+    assert e.value.status == la.LA_ERR_INVALID_ARG
+
+
+def test_topology_rank_count_and_null_handling():
+    t = la.la_topology_create(32, 4, 8)
+    assert t.num_ranks == 1024
+    L = la.lib()
+    assert L.la_topology_num_ranks(None) == -1
+    assert L.la_schedule_num_steps(None) == -1
+    assert L.la_topology_destroy(None) == la.LA_OK and L.la_schedule_destroy(None) == la.LA_OK
+    assert L.la_topology_create(1, 1, 1, None) == la.LA_ERR_INVALID_ARG
+
+
+def test_schedule_build_errors():
+    t = la.la_topology_create(2, 2, 1)
+    for kwargs, status in (
+        (dict(algo="lane", n=0, dtype="float32"), la.LA_ERR_INVALID_ARG),
+        (dict(algo=7, n=16, dtype="float32"), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype=9), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=64), la.LA_ERR_UNSUPPORTED),
+    ):
+        with pytest.raises(la.LaError) as e:
+            la.la_schedule_build(t, **kwargs)
+        assert e.value.status == status
+        assert la.la_last_error() != ""
+    import ctypes
+
+    out = ctypes.c_void_p()
+    assert la.lib().la_schedule_build(None, 1, 16, 1, ctypes.byref(out)) == la.LA_ERR_INVALID_ARG
+    s = la.la_schedule_build(t, "lane", 16, "float32")
+    with pytest.raises(la.LaError):
+        s.step_info(99)
+
+
+def test_tuning_knobs():
+    assert la.la_tuning_get("unroll") in (1, 2, 4, 8)
+    old = la.la_tuning_get("unroll")
+    la.la_tuning_set("unroll", 2)
+    assert la.la_tuning_get("unroll") == 2
+    la.la_tuning_set("unroll", old)
+    with pytest.raises(la.LaError):
+        la.la_tuning_set("unroll", 3)
+    with pytest.raises(la.LaError):
+        la.la_tuning_set("no_such_knob", 1)
+    assert la.la_tuning_get("no_such_knob") == -1
+
+
+def test_run_calls_reject_bad_arguments_before_touching_a_device():
+    import ctypes
+
+    t = la.la_topology_create(2, 1, 1)
+    s = la.la_schedule_build(t, "lane", 64, "float32")
+    L = la.lib()
+    bufs = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    assert L.la_allreduce_emulated(None, bufs, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert L.la_allreduce_emulated(s.handle, None, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert L.la_allreduce_emulated(s.handle, bufs, 32, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert L.la_allreduce_emulated(s.handle, bufs, 64, la.LA_I32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert L.la_allreduce_emulated(s.handle, bufs, 64, la.LA_F32, 3, None) == la.LA_ERR_UNSUPPORTED
+    null_buf = (ctypes.c_void_p * 2)(0x1000, 0)
+    assert L.la_allreduce_emulated(s.handle, null_buf, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    odd = (ctypes.c_void_p * 2)(0x1001, 0x2000)
+    assert L.la_allreduce_emulated(s.handle, odd, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    same = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    assert L.la_allreduce_emulated(s.handle, same, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    overlap = (ctypes.c_void_p * 2)(0x1000, 0x1080)
+    assert L.la_allreduce_emulated(s.handle, overlap, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert L.la_schedule_run_step(s.handle, 5, bufs, None) == la.LA_ERR_INVALID_ARG
+    offs = (ctypes.c_size_t * 2)(0, 8)
+    srcs = (ctypes.c_void_p * 1)(0x3000)
+    rs = L.la_reduce_segments
+    assert rs(None, srcs, 1, offs, 2, 8, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert rs(0x1000, None, 1, offs, 2, 8, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert rs(0x1000, srcs, -1, offs, 2, 8, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert rs(0x1000, srcs, 1, None, 2, 8, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert rs(0x1002, srcs, 1, offs, 2, 8, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert rs(0x1000, srcs, 1, offs, 2, 9, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG  # overlap
+    assert rs(0x1000, srcs, 1, offs, 2, 8, 5, la.LA_SUM, None) == la.LA_ERR_UNSUPPORTED
+    assert rs(0x1000, srcs, 1, offs, 2, 8, la.LA_F32, 1, None) == la.LA_ERR_UNSUPPORTED
+    alias = (ctypes.c_void_p * 1)(0x1000)
+    assert rs(0x1000, alias, 1, offs, 2, 8, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    # nothing to do: accepted without any device work
+    assert rs(0x1000, srcs, 0, offs, 2, 8, la.LA_F32, la.LA_SUM, None) == la.LA_OK
+    assert rs(0x1000, srcs, 1, offs, 0, 8, la.LA_F32, la.LA_SUM, None) == la.LA_OK
+    assert rs(0x1000, srcs, 1, offs, 2, 0, la.LA_F32, la.LA_SUM, None) == la.LA_OK
+
+
+# ----------------------------------------------------------------------------- table interpreter
+
+def bf16_narrow(x32):
+    import torch
+
+    return torch.from_numpy(x32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def run_tables(sched, inputs, snapshot=True, upto=None):
+    """Execute the step tables on host arrays.  With snapshot=True every step reads the state
+    from before the step (what concurrent workgroups see if the step is hazard-free)."""
+    P, n = inputs.shape
+    state = [inputs[r].copy() for r in range(P)] + [np.zeros(max(sched.staging_elems, 1), dtype=inputs.dtype)]
+    steps = range(sched.num_steps if upto is None else upto)
+    for i in steps:
+        t = sched.step_table(i)
+        old = [b.copy() for b in state] if snapshot else state
+        for g in range(t["num_segments"]):
+            ln = int(t["seg_len"][g])
+            ops = [old[int(b)][int(o):int(o) + ln] for b, o in zip(t["src_buf"][g], t["src_off"][g])]
+            if inputs.dtype == np.uint16:
+                acc = (ops[0].astype(np.uint32) << 16).view(np.float32)
+                for x in ops[1:]:
+                    acc = acc + (x.astype(np.uint32) << 16).view(np.float32)
+                res = bf16_narrow(np.ascontiguousarray(acc))
+            elif inputs.dtype == np.int32:
+                acc = ops[0].view(np.uint32).copy()
+                for x in ops[1:]:
+                    acc = acc + x.view(np.uint32)
+                res = acc.view(np.int32)
+            else:
+                acc = ops[0].copy()
+                for x in ops[1:]:
+                    acc = acc + x
+                res = acc
+            for b, o in zip(t["dst_buf"][g], t["dst_off"][g]):
+                state[int(b)][int(o):int(o) + ln] = res
+    return np.stack(state[:P])
+
+
+TOPOS = [t for t in itertools.product((1, 2, 3), repeat=3)]
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("flags", FLAG_SETS)
+def test_tables_reproduce_oracle_bitwise_small_topologies(oracle, algo, flags):
+    for (N, G, Q) in TOPOS:
+        P = N * G * Q
+        topo = la.la_topology_create(N, G, Q)
+        for n in (1, 2, 5, 17, 36, 40):
+            for kind in ("i32", "f32", "bf16"):
+                if kind == "i32":
+                    x = np.random.default_rng(n).integers(-(1 << 31), 1 << 31, size=(P, n), dtype=np.int64).astype(np.int32)
+                elif kind == "f32":
+                    x = synth.order_sensitive_f32(P, n)
+                else:
+                    x = synth.to_bf16_bits(synth.order_sensitive_f32(P, n) * np.float32(2.0 ** -20))
+                dt = {"i32": "int32", "f32": "float32", "bf16": "bfloat16"}[kind]
+                sched = la.la_schedule_build(topo, algo, n, dt, flags)
+                got = run_tables(sched, x)
+                ref = oracle.allreduce(algo, N, G, Q, x)
+                assert np.array_equal(got.view(np.uint8), ref.view(np.uint8)), (algo, flags, N, G, Q, n, kind)
+                if n == 17:
+                    seq = run_tables(sched, x, snapshot=False)
+                    assert np.array_equal(seq.view(np.uint8), got.view(np.uint8))
+
+
+def test_hazard_freedom_every_step_reads_no_range_another_segment_writes():
+    for algo, flags, (N, G, Q), n in itertools.product(ALGOS, FLAG_SETS, [(2, 2, 2), (3, 1, 2), (2, 3, 1)], (7, 48)):
+        sched = la.la_schedule_build(la.la_topology_create(N, G, Q), algo, n, "float32", flags)
+        for i in range(sched.num_steps):
+            t = sched.step_table(i)
+            writes, reads = {}, []
+            for g in range(t["num_segments"]):
+                ln = int(t["seg_len"][g])
+                for b, o in zip(t["dst_buf"][g], t["dst_off"][g]):
+                    for e in range(int(o), int(o) + ln):
+                        assert (int(b), e) not in writes, "two writers"
+                        writes[(int(b), e)] = g
+                for b, o in zip(t["src_buf"][g], t["src_off"][g]):
+                    reads.append((int(b), int(o), ln, g, [int(v) for v in t["src_off"][g]]))
+            for b, o, ln, g, _ in reads:
+                for e in range(o, o + ln):
+                    w = writes.get((b, e))
+                    assert w is None or w == g, "a segment reads what another one writes"
+
+
+# ----------------------------------------------------------------------------- shapes and bytes
+
+def totals(sched):
+    rd = sum(s["bytes_read"] for s in sched.steps())
+    wr = sum(s["bytes_written"] for s in sched.steps())
+    return rd, wr
+
+
+@pytest.mark.parametrize("topo,algo,n,e,dtype", [
+    ((2, 4, 1), "lane", 65536, 4, "float32"),
+    ((4, 4, 1), "lane", 1 << 24, 4, "float32"),
+    ((8, 4, 4), "lane_multiproc", 1 << 22, 4, "float32"),
+    ((2, 4, 2), "lane_multiproc", 1 << 27, 2, "bfloat16"),
+    ((32, 4, 8), "lane_multiproc", 1 << 20, 4, "float32"),
+])
+def test_lane_bytes_match_closed_forms(topo, algo, n, e, dtype):
+    N, G, Q = topo
+    P = N * G * Q
+    t = la.la_topology_create(*topo)
+    unit = n * e
+    # one copy per (source, destination): S1, S2a, S2b, S3
+    s = la.la_schedule_build(t, algo, n, dtype, la.LA_SCHED_P2P_GATHER)
+    st = {x["stage"]: x for x in s.steps()}
+    assert [x["stage"] for x in s.steps()] == [la.LA_STAGE_S1, la.LA_STAGE_S2A, la.LA_STAGE_S2B, la.LA_STAGE_S3]
+    assert (st[la.LA_STAGE_S1]["bytes_read"], st[la.LA_STAGE_S1]["bytes_written"]) == (P * unit, N * unit)
+    assert (st[la.LA_STAGE_S2A]["bytes_read"], st[la.LA_STAGE_S2A]["bytes_written"]) == (N * unit, unit)
+    assert (st[la.LA_STAGE_S2B]["bytes_read"], st[la.LA_STAGE_S2B]["bytes_written"]) == ((N - 1) * unit, (N - 1) * unit)
+    assert (st[la.LA_STAGE_S3]["bytes_read"], st[la.LA_STAGE_S3]["bytes_written"]) == ((P - N) * unit, (P - N) * unit)
+    assert sum(totals(s)) == (3 * P + 2 * N - 1) * unit
+    # multi-destination stores: every reduced range is read once
+    d = la.la_schedule_build(t, algo, n, dtype)
+    assert [x["stage"] for x in d.steps()] == [la.LA_STAGE_S1, la.LA_STAGE_S2, la.LA_STAGE_S3]
+    assert totals(d) == ((P + 2 * N) * unit, (P + N) * unit)
+
+
+def test_ring_bytes_match_closed_form():
+    P, n, e = 16, 1 << 24, 4
+    s = la.la_schedule_build(la.la_topology_create(4, 4, 1), "ring", n, "float32")
+    assert s.num_steps == 2 * (P - 1)
+    kinds = [x["stage"] for x in s.steps()]
+    assert kinds == [la.LA_STAGE_RING_RS] * (P - 1) + [la.LA_STAGE_RING_AG] * (P - 1)
+    assert all(x["num_segments"] == P and x["seg_len_max"] == n // P for x in s.steps())
+    assert all(x["fan_in"] == 2 for x in s.steps()[: P - 1]) and all(x["fan_in"] == 1 for x in s.steps()[P - 1:])
+    assert sum(totals(s)) == 5 * (P - 1) * n * e
+
+
+def test_scale_out_shape_segment_counts_and_fan_in():
+    t = la.la_topology_create(32, 4, 8)
+    s = la.la_schedule_build(t, "lane_multiproc", 1 << 20, "float32", la.LA_SCHED_P2P_GATHER)
+    by = {x["stage"]: x for x in s.steps()}
+    assert (by[la.LA_STAGE_S1]["num_segments"], by[la.LA_STAGE_S1]["fan_in"], by[la.LA_STAGE_S1]["seg_len_max"]) == (1024, 32, 32768)
+    assert (by[la.LA_STAGE_S2A]["num_segments"], by[la.LA_STAGE_S2A]["fan_in"], by[la.LA_STAGE_S2A]["seg_len_max"]) == (1024, 32, 1024)
+    assert (by[la.LA_STAGE_S2B]["num_segments"], by[la.LA_STAGE_S2B]["seg_len_max"]) == (31744, 1024)
+    assert (by[la.LA_STAGE_S3]["num_segments"], by[la.LA_STAGE_S3]["seg_len_max"]) == (31744, 32768)
+    d = la.la_schedule_build(t, "lane_multiproc", 1 << 20, "float32")
+    by = {x["stage"]: x for x in d.steps()}
+    assert (by[la.LA_STAGE_S2]["num_segments"], by[la.LA_STAGE_S2]["fan_in"], by[la.LA_STAGE_S2]["fan_out"]) == (1024, 32, 32)
+    assert (by[la.LA_STAGE_S3]["num_segments"], by[la.LA_STAGE_S3]["fan_in"], by[la.LA_STAGE_S3]["fan_out"]) == (1024, 1, 31)
+
+
+def test_lane_tables_equal_lane_multiproc_tables_with_one_process_per_gpu():
+    t = la.la_topology_create(3, 4, 1)
+    for flags in FLAG_SETS:
+        a = la.la_schedule_build(t, "lane", 1000, "float32", flags)
+        b = la.la_schedule_build(t, "lane_multiproc", 1000, "float32", flags)
+        assert a.num_steps == b.num_steps
+        for i in range(a.num_steps):
+            ta, tb = a.step_table(i), b.step_table(i)
+            for key in ta:
+                assert np.array_equal(ta[key], tb[key]), key
+
+
+def test_degenerate_topologies():
+    one = la.la_schedule_build(la.la_topology_create(1, 1, 1), "lane", 100, "float32")
+    assert one.num_steps == 0  # a single rank: nothing to do
+    assert la.la_schedule_build(la.la_topology_create(1, 1, 1), "ring", 100, "float32").num_steps == 0
+    single_node = la.la_schedule_build(la.la_topology_create(1, 4, 2), "lane_multiproc", 100, "float32")
+    assert [x["stage"] for x in single_node.steps()] == [la.LA_STAGE_S1, la.LA_STAGE_S3]
+    only_nodes = la.la_schedule_build(la.la_topology_create(5, 1, 1), "lane", 100, "float32")
+    assert [x["stage"] for x in only_nodes.steps()] == [la.LA_STAGE_S2]
+    # fewer elements than parts: empty parts vanish from the tables
+    tiny = la.la_schedule_build(la.la_topology_create(2, 3, 2), "lane_multiproc", 3, "int32")
+    assert all(x["num_segments"] <= 6 for x in tiny.steps())
+
+
+def test_staged_schedule_reads_remote_operands_only_from_staging():
+    N, G, Q, n = 2, 2, 2, 64
+    P = N * G * Q
+    s = la.la_schedule_build(la.la_topology_create(N, G, Q), "lane_multiproc", n, "float32", la.LA_SCHED_STAGED)
+    assert s.staging_elems > 0
+    stages = [x["stage"] for x in s.steps()]
+    assert stages == [la.LA_STAGE_PACK, la.LA_STAGE_S1, la.LA_STAGE_PACK, la.LA_STAGE_S2, la.LA_STAGE_S3]
+    for i, x in enumerate(s.steps()):
+        t = s.step_table(i)
+        if x["stage"] in (la.LA_STAGE_S1, la.LA_STAGE_S2):
+            for g in range(t["num_segments"]):
+                home = int(t["dst_buf"][g][0])
+                assert all(int(b) in (home, P) for b in t["src_buf"][g])
+                assert sum(int(b) == home for b in t["src_buf"][g]) == 1
+        if x["stage"] == la.LA_STAGE_PACK:
+            assert np.all(t["dst_buf"] == P) and np.all(t["src_buf"] < P)
