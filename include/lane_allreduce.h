@@ -174,10 +174,14 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
 const char* la_status_string(la_status_t status);
 const char* la_last_error(void);
 
-/* Launch-shape knobs for measurements (process-wide, read at each launch).
- *   "unroll"     16-byte vectors per thread and operand: 1, 2, 4 or 8
- *   "nontemporal" bit 0: non-temporal loads, bit 1: non-temporal stores
- * Returns LA_ERR_INVALID_ARG for an unknown key or value.  la_tuning_get returns -1 if unknown. */
+/* Launch-shape knobs for measurements (process-wide, read when a schedule is bound or a
+ * la_reduce_segments call is made).  By default every step picks its own shape from its fan-in,
+ * fan-out and segment length; a knob set to a fixed value overrides that choice for all steps.
+ *   "unroll"      16-byte vectors per lane and operand: 1, 2, 4, 8; 0 = automatic
+ *   "nontemporal" bit 0: non-temporal loads, bit 1: non-temporal stores; -1 = automatic
+ *   "block"       lanes per workgroup: 256, 512, 1024; 0 = automatic
+ * la_tuning_set returns LA_ERR_INVALID_ARG for an unknown key or value; la_tuning_get returns
+ * the current setting, or -2 for an unknown key. */
 la_status_t la_tuning_set(const char* key, int value);
 int la_tuning_get(const char* key);
 

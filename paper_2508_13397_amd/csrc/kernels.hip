@@ -8,7 +8,7 @@
 //
 // The work is HBM-bound (at most k-1 adds per (k+m) elements moved), so the kernel is built
 // around 16-byte coalesced accesses with many independent loads in flight per lane; no LDS and
-// no matrix cores.  A workgroup of 256 lanes owns a tile of UNROLL*256 vectors of one segment;
+// no matrix cores.  A workgroup of BLOCK lanes owns a tile of UNROLL*BLOCK vectors of one segment;
 // consecutive workgroups own consecutive tiles, so the eight XCDs (which receive workgroups
 // round-robin) stream disjoint, adjacent 4-16 KiB pieces of the same operand rows at once.
 #include <hip/hip_runtime.h>
@@ -21,7 +21,6 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BLOCK = 256;
 constexpr int KBATCH = 4; // operands whose loads are issued together
 
 // ---- element types ---------------------------------------------------------------------------
@@ -158,7 +157,7 @@ __device__ inline void reduce_one(const uint64_t* sp, const uint64_t* dp, uint32
 
 // ---- the kernel -------------------------------------------------------------------------------
 
-template <typename T, int U, bool NTL, bool NTS>
+template <typename T, int U, bool NTL, bool NTS, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
 {
     const uint32_t seg = blockIdx.x / tab.tiles_per_seg;
@@ -262,44 +261,55 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     }
 }
 
-template <typename T, int U>
+template <typename T, int U, int BLOCK>
 la_status_t launch_nt(const StepTable& t, int nt, dim3 grid, hipStream_t s)
 {
     switch (nt & 3) {
-    case 0: hipLaunchKernelGGL((seg_reduce_kernel<T, U, false, false>), grid, dim3(BLOCK), 0, s, t); break;
-    case 1: hipLaunchKernelGGL((seg_reduce_kernel<T, U, true, false>), grid, dim3(BLOCK), 0, s, t); break;
-    case 2: hipLaunchKernelGGL((seg_reduce_kernel<T, U, false, true>), grid, dim3(BLOCK), 0, s, t); break;
-    default: hipLaunchKernelGGL((seg_reduce_kernel<T, U, true, true>), grid, dim3(BLOCK), 0, s, t); break;
+    case 0: hipLaunchKernelGGL((seg_reduce_kernel<T, U, false, false, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    case 1: hipLaunchKernelGGL((seg_reduce_kernel<T, U, true, false, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    case 2: hipLaunchKernelGGL((seg_reduce_kernel<T, U, false, true, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    default: hipLaunchKernelGGL((seg_reduce_kernel<T, U, true, true, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LA_ERR_DEVICE, "kernel launch failed: %s", hipGetErrorString(e));
     return LA_OK;
 }
 
-template <typename T>
+template <typename T, int BLOCK>
 la_status_t launch_unroll(const StepTable& t, const Tuning& tune, dim3 grid, hipStream_t s)
 {
     switch (tune.unroll) {
-    case 1: return launch_nt<T, 1>(t, tune.nontemporal, grid, s);
-    case 2: return launch_nt<T, 2>(t, tune.nontemporal, grid, s);
-    case 4: return launch_nt<T, 4>(t, tune.nontemporal, grid, s);
-    case 8: return launch_nt<T, 8>(t, tune.nontemporal, grid, s);
+    case 1: return launch_nt<T, 1, BLOCK>(t, tune.nontemporal, grid, s);
+    case 2: return launch_nt<T, 2, BLOCK>(t, tune.nontemporal, grid, s);
+    case 4: return launch_nt<T, 4, BLOCK>(t, tune.nontemporal, grid, s);
+    case 8: return launch_nt<T, 8, BLOCK>(t, tune.nontemporal, grid, s);
     }
     return fail(LA_ERR_INVALID_ARG, "unsupported unroll %d", tune.unroll);
 }
 
+template <typename T>
+la_status_t launch_block(const StepTable& t, const Tuning& tune, dim3 grid, hipStream_t s)
+{
+    switch (tune.block) {
+    case 256: return launch_unroll<T, 256>(t, tune, grid, s);
+    case 512: return launch_unroll<T, 512>(t, tune, grid, s);
+    case 1024: return launch_unroll<T, 1024>(t, tune, grid, s);
+    }
+    return fail(LA_ERR_INVALID_ARG, "unsupported block size %d", tune.block);
+}
+
 } // namespace
 
-uint32_t tiles_for(uint64_t max_units, int unroll)
+uint32_t tiles_for(uint64_t max_units, const Tuning& tune)
 {
-    const uint64_t tile = (uint64_t)BLOCK * (uint64_t)unroll;
+    const uint64_t tile = (uint64_t)tune.block * (uint64_t)tune.unroll;
     const uint64_t tiles = (max_units + tile - 1) / tile;
     return (uint32_t)(tiles ? tiles : 1);
 }
 
 // The caller guarantees: tables are device-resident and hold num_segments * k (resp. m)
 // pointers; every pointer range [ptr, ptr + len*esize) is valid device memory;
-// tiles_per_seg == tiles_for(longest segment in vectors, tune.unroll).
+// tiles_per_seg == tiles_for(longest segment in vectors, tune).
 la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream)
 {
     if (t.num_segments == 0) return LA_OK;
@@ -309,9 +319,9 @@ la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune
     const dim3 grid((uint32_t)blocks);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     switch (dtype) {
-    case LA_I32: return launch_unroll<I32>(t, tune, grid, s);
-    case LA_F32: return launch_unroll<F32>(t, tune, grid, s);
-    case LA_BF16: return launch_unroll<BF16>(t, tune, grid, s);
+    case LA_I32: return launch_block<I32>(t, tune, grid, s);
+    case LA_F32: return launch_block<F32>(t, tune, grid, s);
+    case LA_BF16: return launch_block<BF16>(t, tune, grid, s);
     }
     return fail(LA_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
 }

@@ -60,15 +60,25 @@ struct StepTable {
     uint32_t num_segments;
 };
 
+// Launch shape of one step.  In the process-wide setting 0 (unroll, block) and -1 (nontemporal)
+// mean "choose per step from its fan-in, fan-out and segment length".
 struct Tuning {
-    int unroll = 4;
-    int nontemporal = 0;
+    int unroll = 0;       // 16-byte vectors per lane and operand: 1, 2, 4, 8
+    int nontemporal = -1; // bit 0: loads, bit 1: stores
+    int block = 0;        // lanes per workgroup: 256, 512, 1024
+    bool operator==(const Tuning& o) const
+    {
+        return unroll == o.unroll && block == o.block && nontemporal == o.nontemporal;
+    }
 };
 Tuning current_tuning();
+// Fill the automatic fields of `requested` for a step with k sources, m destinations and a
+// longest segment of `longest_units` 16-byte vectors.
+Tuning resolve_tuning(const Tuning& requested, uint32_t k, uint32_t m, uint64_t longest_units);
 
 // kernels.hip
 la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream);
-uint32_t tiles_for(uint64_t max_units, int unroll); // units = 16-byte vectors per operand
+uint32_t tiles_for(uint64_t max_units, const Tuning& tune); // units = 16-byte vectors per operand
 
 // error reporting
 la_status_t fail(la_status_t st, const char* fmt, ...);

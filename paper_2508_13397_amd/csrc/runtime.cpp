@@ -21,14 +21,69 @@ using namespace la;
 // ---- tuning ---------------------------------------------------------------------------------
 
 namespace la {
-static std::atomic<int> g_unroll{4};
-static std::atomic<int> g_nontemporal{0};
+static std::atomic<int> g_unroll{0};
+static std::atomic<int> g_nontemporal{-1};
+static std::atomic<int> g_block{0};
 
 Tuning current_tuning()
 {
     Tuning t;
     t.unroll = g_unroll.load();
     t.nontemporal = g_nontemporal.load();
+    t.block = g_block.load();
+    return t;
+}
+
+// Launch shapes measured on MI355X (HBM-bound; see the roofline notes of the build):
+//  - pure reduce (k >= 2, one destination): every operand is read once and the result is not
+//    read again by this launch, so loads and stores are non-temporal; large tiles keep each
+//    workgroup on long contiguous runs of every operand, which matters more as k grows;
+//  - copy / broadcast (k == 1): the source was produced by the previous launch and is often still
+//    cache-resident, so it is read with ordinary loads; with few destinations non-temporal stores
+//    keep the written stream from evicting it;
+//  - reduce with multi-destination store: ordinary accesses, 256-lane workgroups.
+Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longest_units)
+{
+    Tuning t;
+    if (k >= 2 && m == 1) {
+        t.nontemporal = 3;
+        if (k >= 8) {
+            t.block = 1024;
+            t.unroll = 4;
+        } else if (k >= 3) {
+            t.block = 1024;
+            t.unroll = 1;
+        } else {
+            t.block = 256;
+            t.unroll = 4;
+        }
+    } else if (k == 1) {
+        if (m == 1) {
+            t.nontemporal = 0;
+            t.block = 256;
+            t.unroll = 4;
+        } else if (m <= 4) {
+            t.nontemporal = 2;
+            t.block = 256;
+            t.unroll = 1;
+        } else {
+            t.nontemporal = 0;
+            t.block = 1024;
+            t.unroll = 4;
+        }
+    } else {
+        t.nontemporal = 0;
+        t.block = 256;
+        t.unroll = 4;
+    }
+    if (req.unroll > 0) t.unroll = req.unroll;
+    if (req.block > 0) t.block = req.block;
+    if (req.nontemporal >= 0) t.nontemporal = req.nontemporal;
+    // a tile should not be much longer than the longest segment of the step
+    if (req.unroll <= 0)
+        while (t.unroll > 1 && (uint64_t)t.block * t.unroll > longest_units) t.unroll /= 2;
+    if (req.block <= 0)
+        while (t.block > 256 && (uint64_t)t.block * t.unroll > longest_units) t.block /= 2;
     return t;
 }
 } // namespace la
@@ -38,7 +93,8 @@ Tuning current_tuning()
 struct la_binding {
     std::vector<uint64_t> bufs; // the P device addresses the tables were resolved with
     int device = -1;
-    int unroll = 0;             // tiles_per_seg depends on it
+    Tuning requested;           // the process-wide setting the launch shapes were derived from
+    std::vector<Tuning> shape;  // per step
     void* tables = nullptr;     // one device allocation holding every step's tables
     void* staging = nullptr;    // library-owned staging area (LA_SCHED_STAGED)
     hipEvent_t last_use = nullptr;
@@ -93,8 +149,8 @@ struct HostTables {
 
 // Resolve every (buffer, offset) operand of `steps` against `base` addresses and lay the tables
 // out in one blob.  base[P] is the staging area.
-void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>& base, size_t esize, int unroll,
-                    HostTables& out)
+void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>& base, size_t esize, const Tuning& tune,
+                    HostTables& out, std::vector<Tuning>& shapes)
 {
     uint64_t total = 0;
     std::vector<uint64_t> seg_at(steps.size()), src_at(steps.size()), dst_at(steps.size());
@@ -110,6 +166,7 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
     }
     out.blob.assign(total ? total : 256, 0);
     out.view.resize(steps.size());
+    shapes.resize(steps.size());
     std::vector<uint64_t> all;
     for (size_t i = 0; i < steps.size(); ++i) {
         const Step& p = steps[i];
@@ -139,7 +196,8 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
         v.k = (uint32_t)p.k;
         v.m = (uint32_t)p.m;
         v.num_segments = (uint32_t)S;
-        v.tiles_per_seg = tiles_for(longest, unroll);
+        shapes[i] = resolve_tuning(tune, v.k, v.m, longest);
+        v.tiles_per_seg = tiles_for(longest, shapes[i]);
     }
 }
 
@@ -179,7 +237,7 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     LA_HIP(hipGetDevice(&dev));
     la_binding* b = s.bound;
     const int P = s.topo.ranks();
-    if (b && b->device == dev && b->unroll == tune.unroll && b->bufs.size() == (size_t)P &&
+    if (b && b->device == dev && b->requested == tune && b->bufs.size() == (size_t)P &&
         std::equal(addr.begin(), addr.begin() + P, b->bufs.begin()))
         return LA_OK;
     if (b && b->used) LA_HIP(hipEventSynchronize(b->last_use)); // earlier work still reads the tables
@@ -204,8 +262,9 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     }
     addr[P] = reinterpret_cast<uint64_t>(b->staging);
     HostTables ht;
+    std::vector<Tuning> shapes;
     try {
-        resolve_tables(s.steps, addr, e, tune.unroll, ht);
+        resolve_tables(s.steps, addr, e, tune, ht, shapes);
     } catch (const std::bad_alloc&) {
         return fail(LA_ERR_OUT_OF_MEMORY, "out of host memory");
     }
@@ -222,7 +281,8 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     relocate(ht.view, b->tables);
     b->step = std::move(ht.view);
     b->bufs.assign(addr.begin(), addr.begin() + P);
-    b->unroll = tune.unroll;
+    b->requested = tune;
+    b->shape = std::move(shapes);
     b->used = false;
     return LA_OK;
 }
@@ -238,7 +298,7 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, int first, 
     if (st != LA_OK) return st;
     la_binding* b = sched->bound;
     for (int i = first; i < last; ++i) {
-        st = launch_step(b->step[i], sched->dtype, tune, hip_stream);
+        st = launch_step(b->step[i], sched->dtype, b->shape[i], hip_stream);
         if (st != LA_OK) return st;
     }
     LA_HIP(hipEventRecord(b->last_use, static_cast<hipStream_t>(hip_stream)));
@@ -361,7 +421,6 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
     }
 
     // Tables for one step with k+1 sources (dst first) and one destination.
-    const Tuning tune = current_tuning();
     const size_t K = (size_t)k + 1;
     const uint64_t seg_bytes = align_up(num_segments * sizeof(SegInfo), 256);
     const uint64_t src_bytes = align_up(num_segments * K * sizeof(uint64_t), 256);
@@ -403,7 +462,8 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
     t.k = (uint32_t)K;
     t.m = 1;
     t.num_segments = (uint32_t)num_segments;
-    t.tiles_per_seg = tiles_for(longest, tune.unroll);
+    const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest);
+    t.tiles_per_seg = tiles_for(longest, tune);
     la_status_t st = launch_step(t, dtype, tune, hip_stream);
     (void)hipFreeAsync(dev, stream); // stream-ordered: freed after the kernel has run
     return st;
@@ -414,14 +474,21 @@ la_status_t la_tuning_set(const char* key, int value)
     if (!key) return fail(LA_ERR_INVALID_ARG, "la_tuning_set: key is NULL");
     const std::string k(key);
     if (k == "unroll") {
-        if (value != 1 && value != 2 && value != 4 && value != 8)
-            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: unroll must be 1, 2, 4 or 8");
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: unroll must be 0 (auto), 1, 2, 4 or 8");
         g_unroll.store(value);
         return LA_OK;
     }
     if (k == "nontemporal") {
-        if (value < 0 || value > 3) return fail(LA_ERR_INVALID_ARG, "la_tuning_set: nontemporal must be 0..3");
+        if (value < -1 || value > 3)
+            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: nontemporal must be -1 (auto) or 0..3");
         g_nontemporal.store(value);
+        return LA_OK;
+    }
+    if (k == "block") {
+        if (value != 0 && value != 256 && value != 512 && value != 1024)
+            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: block must be 0 (auto), 256, 512 or 1024");
+        g_block.store(value);
         return LA_OK;
     }
     return fail(LA_ERR_INVALID_ARG, "la_tuning_set: unknown key '%s'", key);
@@ -429,11 +496,12 @@ la_status_t la_tuning_set(const char* key, int value)
 
 int la_tuning_get(const char* key)
 {
-    if (!key) return -1;
+    if (!key) return -2;
     const std::string k(key);
     if (k == "unroll") return g_unroll.load();
     if (k == "nontemporal") return g_nontemporal.load();
-    return -1;
+    if (k == "block") return g_block.load();
+    return -2;
 }
 
 } // extern "C"

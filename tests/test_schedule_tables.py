@@ -77,16 +77,23 @@ def test_schedule_build_errors():
 
 
 def test_tuning_knobs():
-    assert la.la_tuning_get("unroll") in (1, 2, 4, 8)
-    old = la.la_tuning_get("unroll")
-    la.la_tuning_set("unroll", 2)
-    assert la.la_tuning_get("unroll") == 2
-    la.la_tuning_set("unroll", old)
-    with pytest.raises(la.LaError):
-        la.la_tuning_set("unroll", 3)
+    assert (la.la_tuning_get("unroll"), la.la_tuning_get("nontemporal"), la.la_tuning_get("block")) == (0, -1, 0)
+    try:
+        for key, good, bad in (("unroll", (1, 2, 4, 8, 0), (3, -1, 16)), ("nontemporal", (0, 1, 2, 3, -1), (4, -2)),
+                               ("block", (256, 512, 1024, 0), (128, 100, 2048))):
+            for v in good:
+                la.la_tuning_set(key, v)
+                assert la.la_tuning_get(key) == v
+            for v in bad:
+                with pytest.raises(la.LaError):
+                    la.la_tuning_set(key, v)
+    finally:
+        la.la_tuning_set("unroll", 0)
+        la.la_tuning_set("nontemporal", -1)
+        la.la_tuning_set("block", 0)
     with pytest.raises(la.LaError):
         la.la_tuning_set("no_such_knob", 1)
-    assert la.la_tuning_get("no_such_knob") == -1
+    assert la.la_tuning_get("no_such_knob") == -2
 
 
 def test_run_calls_reject_bad_arguments_before_touching_a_device():
