@@ -24,8 +24,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # file (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors calibrated on the ring's plain-copy launches
 # of known size; profiles/seg_reduce_kernel_c2_lane_pmc.md).  Keyed by (config, algo, flags, stage).
 MEASURED_TRAFFIC = {
-    ("c2", "lane", 0, "S1"): 1342233600,
-    ("c2", "lane", 0, "S3"): 1075821876,
+    ("c2", "lane", 0, "S1"): 1342245069,
+    ("c2", "lane", 0, "S2"): 536945664,
+    ("c2", "lane", 0, "S3"): 1075162829,
 }
 
 CONFIGS = {
@@ -52,8 +53,12 @@ def parse():
     ap.add_argument("--algo", default=None, choices=["ring", "lane", "lane_multiproc"])
     ap.add_argument("--flags", type=int, default=0, help="LA_SCHED_* bits: 1 = point-to-point gather, 2 = staged")
     ap.add_argument("--unroll", type=int, default=None)
-    ap.add_argument("--nontemporal", type=int, default=None)
+    ap.add_argument("--cache-policy", type=int, default=None)
     ap.add_argument("--skew", type=int, default=0, help="extra bytes between consecutive rank buffers")
+    ap.add_argument("--flush-cache", action="store_true",
+                    help="overwrite a 1 GiB scratch buffer before every timed all-reduce, so that nothing "
+                         "the previous one wrote is left in the last-level cache (the flush is outside "
+                         "the per-launch events; ms_per_step then comes from the events)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ring", action="store_true", help="skip the ring comparison leg of C2")
     return ap.parse_args()
@@ -84,7 +89,7 @@ def device_buffers(x, skew_bytes):
     return bufs, slab
 
 
-def time_schedule(la, torch, sched, bufs, steps, warmup):
+def time_schedule(la, torch, sched, bufs, steps, warmup, flush=None):
     """W warm-up all-reduces, then K timed ones with an event after every launch."""
     stream = torch.cuda.current_stream()
     ptrs = la.ptr_array([b.data_ptr() for b in bufs])
@@ -95,6 +100,8 @@ def time_schedule(la, torch, sched, bufs, steps, warmup):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
+        if flush is not None:
+            flush.add_(1.0)
         ev[k][0].record(stream)
         for s in range(ns):
             la.la_schedule_run_step(sched, s, ptrs, stream.cuda_stream)
@@ -102,6 +109,9 @@ def time_schedule(la, torch, sched, bufs, steps, warmup):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     per_step_ms = [sum(ev[k][s].elapsed_time(ev[k][s + 1]) for k in range(steps)) / steps for s in range(ns)]
+    wall_ms = (t1 - t0) / steps * 1e3
+    if flush is not None:  # the wall clock contains the flushes: use the event-to-event time of the launches
+        wall_ms = sum(per_step_ms)
     # the same K all-reduces through the one-call entry point, no events in between
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -109,7 +119,7 @@ def time_schedule(la, torch, sched, bufs, steps, warmup):
         la.la_allreduce_emulated(sched, ptrs, sched.n, sched.dtype, la.LA_SUM, stream.cuda_stream)
     torch.cuda.synchronize()
     t3 = time.perf_counter()
-    return (t1 - t0) / steps * 1e3, per_step_ms, (t3 - t2) / steps * 1e3
+    return wall_ms, per_step_ms, (t3 - t2) / steps * 1e3
 
 
 def cpu_baseline(cfg, algo, total_bytes_full):
@@ -166,8 +176,8 @@ def main():
     algo = args.algo or cfg["algo"]
     if args.unroll is not None:
         la.la_tuning_set("unroll", args.unroll)
-    if args.nontemporal is not None:
-        la.la_tuning_set("nontemporal", args.nontemporal)
+    if args.cache_policy is not None:
+        la.la_tuning_set("cache_policy", args.cache_policy)
     N, G, Q = cfg["topo"]
     P, n = N * G * Q, cfg["n"]
     e = la.ELEM_SIZE[la.DTYPES[cfg["dtype"]]]
@@ -181,7 +191,8 @@ def main():
     step_bytes = [s["bytes_read"] + s["bytes_written"] for s in info]
     total_bytes = sum(step_bytes)
 
-    ms, per_step_ms, ms_onecall = time_schedule(la, torch, sched, bufs, args.steps, args.warmup)
+    flush = torch.zeros(1 << 28, dtype=torch.float32, device="cuda") if args.flush_cache else None
+    ms, per_step_ms, ms_onecall = time_schedule(la, torch, sched, bufs, args.steps, args.warmup, flush)
 
     # the dominant kernel: the launch (or family of identical launches) with the most time
     fam = {}
@@ -214,8 +225,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg["name"], "config_id": args.config, "algo": algo, "schedule_flags": args.flags,
                    "virtual_ranks": P, "elements_per_rank": n, "launches_per_allreduce": len(info),
-                   "unroll": la.la_tuning_get("unroll"), "nontemporal": la.la_tuning_get("nontemporal"),
-                   "skew_bytes": args.skew},
+                   "unroll": la.la_tuning_get("unroll"), "cache_policy": la.la_tuning_get("cache_policy"),
+                   "skew_bytes": args.skew, "flush_cache_between_allreduces": bool(args.flush_cache)},
         "pct_of_hbm_peak": round(total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS * 100, 2),
         "algorithmic_bytes_per_allreduce": total_bytes,
         "allreduce_bytes_per_s_per_rank": round(n * e / (ms * 1e-3), 1),

@@ -178,7 +178,11 @@ const char* la_last_error(void);
  * la_reduce_segments call is made).  By default every step picks its own shape from its fan-in,
  * fan-out and segment length; a knob set to a fixed value overrides that choice for all steps.
  *   "unroll"      16-byte vectors per lane and operand: 1, 2, 4, 8; 0 = automatic
- *   "nontemporal" bit 0: non-temporal loads, bit 1: non-temporal stores; -1 = automatic
+ *   "cache_policy" 0..7: which of {loads of pure sources, loads of sources the segment also
+ *                 overwrites, stores} are plain (P), non-temporal (N) or scope-1 (S):
+ *                 0 PPP, 1 NPP, 2 NPS, 3 NNN, 4 PPN, 5 NNP, 6 NNS, 7 PPS; -1 = automatic.
+ *                 A three-digit value abc sets policy a for pure reduce steps, b for reduce
+ *                 steps with several destinations and c for copy / broadcast steps.
  *   "block"       lanes per workgroup: 256, 512, 1024; 0 = automatic
  * la_tuning_set returns LA_ERR_INVALID_ARG for an unknown key or value; la_tuning_get returns
  * the current setting, or -2 for an unknown key. */

@@ -121,25 +121,57 @@ struct BF16 {
 };
 
 // ---- memory access -----------------------------------------------------------------------------
+//
+// 16-byte accesses go through raw buffer instructions: the descriptor of an operand is rebased
+// to the workgroup's tile and sized to the bytes that remain in the segment, so the hardware
+// range check drops what lies beyond a ragged tail (loads return 0, stores are discarded) and the
+// lanes need no bounds test.  The aux operand carries the cache policy bits of the instruction.
 
-template <bool NT>
-__device__ inline u32x4 load16(uint64_t base, uint64_t vec)
+constexpr int AUX_PLAIN = 0;
+constexpr int AUX_NT = 2;   // non-temporal: the line is not kept
+constexpr int AUX_SC1 = 16; // scope bit 1 (write-through towards memory at agent scope)
+
+// Cache policy of a launch: {loads of pure sources, loads of sources that the segment also
+// overwrites, stores}.
+template <int POLICY>
+struct Policy;
+template <> struct Policy<0> { static constexpr int LD = AUX_PLAIN, LDA = AUX_PLAIN, ST = AUX_PLAIN; };
+template <> struct Policy<1> { static constexpr int LD = AUX_NT, LDA = AUX_PLAIN, ST = AUX_PLAIN; };
+template <> struct Policy<2> { static constexpr int LD = AUX_NT, LDA = AUX_PLAIN, ST = AUX_SC1; };
+template <> struct Policy<3> { static constexpr int LD = AUX_NT, LDA = AUX_NT, ST = AUX_NT; };
+template <> struct Policy<4> { static constexpr int LD = AUX_PLAIN, LDA = AUX_PLAIN, ST = AUX_NT; };
+template <> struct Policy<5> { static constexpr int LD = AUX_NT, LDA = AUX_NT, ST = AUX_PLAIN; };
+template <> struct Policy<6> { static constexpr int LD = AUX_NT, LDA = AUX_NT, ST = AUX_SC1; };
+template <> struct Policy<7> { static constexpr int LD = AUX_PLAIN, LDA = AUX_PLAIN, ST = AUX_SC1; };
+
+__device__ inline __amdgpu_buffer_rsrc_t tile_rsrc(uint64_t base, uint64_t tile_off, uint32_t tile_bytes)
 {
-    const u32x4* p = reinterpret_cast<const u32x4*>(base) + vec;
-    if constexpr (NT)
-        return __builtin_nontemporal_load(p);
-    else
-        return *p;
+    // raw buffer (stride 0), 32-bit data format word as used for untyped accesses on gfx9
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(base + tile_off), 0, (int)tile_bytes, 0x00020000);
 }
 
-template <bool NT>
-__device__ inline void store16(uint64_t base, uint64_t vec, u32x4 v)
+template <int AUX>
+__device__ inline u32x4 load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
 {
-    u32x4* p = reinterpret_cast<u32x4*>(base) + vec;
-    if constexpr (NT)
-        __builtin_nontemporal_store(v, p);
-    else
-        *p = v;
+    return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, AUX);
+}
+
+template <int AUX>
+__device__ inline void store16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, u32x4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, AUX);
+}
+
+// source t of a segment: plain-source policy unless the segment also writes that range
+template <typename P>
+__device__ inline u32x4 load_src(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, bool in_place)
+{
+    if constexpr (P::LD == P::LDA) {
+        return load16<P::LD>(r, byte_off);
+    } else {
+        if (in_place) return load16<P::LDA>(r, byte_off); // uniform across the workgroup
+        return load16<P::LD>(r, byte_off);
+    }
 }
 
 // One element of one segment, all k operands in order: the slow lanes (segment heads and
@@ -157,9 +189,10 @@ __device__ inline void reduce_one(const uint64_t* sp, const uint64_t* dp, uint32
 
 // ---- the kernel -------------------------------------------------------------------------------
 
-template <typename T, int U, bool NTL, bool NTS, int BLOCK>
+template <typename T, int U, int POLICY, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
 {
+    using P = Policy<POLICY>;
     const uint32_t seg = blockIdx.x / tab.tiles_per_seg;
     const uint32_t tile = blockIdx.x - seg * tab.tiles_per_seg;
     const uint32_t k = tab.k, m = tab.m;
@@ -181,7 +214,6 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     const uint64_t body = si.len - si.head;    // elements from the first 16-byte boundary on
     const uint64_t nvec = body / T::VEC;       // whole vectors
     const uint32_t tail = (uint32_t)(body % T::VEC);
-    const uint64_t shift = (uint64_t)si.head * sizeof(typename T::elem); // bytes to the boundary
 
     if (tile == 0 && tid < si.head + tail) {
         // the few elements before the first and after the last whole vector
@@ -189,20 +221,23 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
         reduce_one<T>(sp, dp, k, m, e);
     }
 
-    const uint64_t v0 = (uint64_t)tile * TILE + tid;
-    if (v0 >= nvec) return;
-    const bool full = (uint64_t)(tile + 1) * TILE <= nvec; // uniform across the workgroup
+    const uint64_t tile_v0 = (uint64_t)tile * TILE;
+    if (tile_v0 >= nvec) return; // uniform: nothing left for this workgroup
+    const uint64_t left = nvec - tile_v0;
+    const uint32_t tile_bytes = (uint32_t)(left < TILE ? left : TILE) * 16u;
+    const uint64_t tile_off = (uint64_t)si.head * sizeof(typename T::elem) + tile_v0 * 16u;
+    const uint64_t in_place = si.alias_mask;
+
+    uint32_t off[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) off[u] = (tid + (uint32_t)u * BLOCK) * 16u;
 
     typename T::Acc acc[U];
     {
-        const uint64_t base = sp[0] + shift;
+        const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[0], tile_off, tile_bytes);
+        const bool ip = in_place & 1u;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint64_t v = v0 + (uint64_t)u * BLOCK;
-            u32x4 x = u32x4{0, 0, 0, 0};
-            if (full || v < nvec) x = load16<NTL>(base, v);
-            acc[u] = T::widen(x);
-        }
+        for (int u = 0; u < U; ++u) acc[u] = T::widen(load_src<P>(r, off[u], ip));
     }
     uint32_t t = 1;
     // full batches: KBATCH*U independent 16-byte loads per lane are issued before the adds
@@ -210,13 +245,10 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
         u32x4 x[KBATCH][U];
 #pragma unroll
         for (int b = 0; b < KBATCH; ++b) {
-            const uint64_t base = sp[t + b] + shift;
+            const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[t + b], tile_off, tile_bytes);
+            const bool ip = (in_place >> ((t + b) & 63u)) & 1u;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint64_t v = v0 + (uint64_t)u * BLOCK;
-                x[b][u] = u32x4{0, 0, 0, 0};
-                if (full || v < nvec) x[b][u] = load16<NTL>(base, v);
-            }
+            for (int u = 0; u < U; ++u) x[b][u] = load_src<P>(r, off[u], ip);
         }
 #pragma unroll
         for (int b = 0; b < KBATCH; ++b)
@@ -230,13 +262,10 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
 #pragma unroll
         for (int b = 0; b < KBATCH - 1; ++b) {
             if ((uint32_t)b < rem) {
-                const uint64_t base = sp[t + b] + shift;
+                const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[t + b], tile_off, tile_bytes);
+                const bool ip = (in_place >> ((t + b) & 63u)) & 1u;
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint64_t v = v0 + (uint64_t)u * BLOCK;
-                    x[b][u] = u32x4{0, 0, 0, 0};
-                    if (full || v < nvec) x[b][u] = load16<NTL>(base, v);
-                }
+                for (int u = 0; u < U; ++u) x[b][u] = load_src<P>(r, off[u], ip);
             }
         }
 #pragma unroll
@@ -252,23 +281,25 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
 #pragma unroll
     for (int u = 0; u < U; ++u) out[u] = T::narrow(acc[u]);
     for (uint32_t d = 0; d < m; ++d) {
-        const uint64_t base = dp[d] + shift;
+        const __amdgpu_buffer_rsrc_t r = tile_rsrc(dp[d], tile_off, tile_bytes);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint64_t v = v0 + (uint64_t)u * BLOCK;
-            if (full || v < nvec) store16<NTS>(base, v, out[u]);
-        }
+        for (int u = 0; u < U; ++u) store16<P::ST>(r, off[u], out[u]);
     }
 }
 
 template <typename T, int U, int BLOCK>
-la_status_t launch_nt(const StepTable& t, int nt, dim3 grid, hipStream_t s)
+la_status_t launch_policy(const StepTable& t, int policy, dim3 grid, hipStream_t s)
 {
-    switch (nt & 3) {
-    case 0: hipLaunchKernelGGL((seg_reduce_kernel<T, U, false, false, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
-    case 1: hipLaunchKernelGGL((seg_reduce_kernel<T, U, true, false, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
-    case 2: hipLaunchKernelGGL((seg_reduce_kernel<T, U, false, true, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
-    default: hipLaunchKernelGGL((seg_reduce_kernel<T, U, true, true, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    switch (policy) {
+    case 0: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 0, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    case 1: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 1, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    case 2: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 2, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    case 3: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 3, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    case 4: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 4, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    case 5: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 5, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    case 6: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 6, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    case 7: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 7, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    default: return fail(LA_ERR_INVALID_ARG, "unsupported cache policy %d", policy);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LA_ERR_DEVICE, "kernel launch failed: %s", hipGetErrorString(e));
@@ -279,10 +310,10 @@ template <typename T, int BLOCK>
 la_status_t launch_unroll(const StepTable& t, const Tuning& tune, dim3 grid, hipStream_t s)
 {
     switch (tune.unroll) {
-    case 1: return launch_nt<T, 1, BLOCK>(t, tune.nontemporal, grid, s);
-    case 2: return launch_nt<T, 2, BLOCK>(t, tune.nontemporal, grid, s);
-    case 4: return launch_nt<T, 4, BLOCK>(t, tune.nontemporal, grid, s);
-    case 8: return launch_nt<T, 8, BLOCK>(t, tune.nontemporal, grid, s);
+    case 1: return launch_policy<T, 1, BLOCK>(t, tune.cache_policy, grid, s);
+    case 2: return launch_policy<T, 2, BLOCK>(t, tune.cache_policy, grid, s);
+    case 4: return launch_policy<T, 4, BLOCK>(t, tune.cache_policy, grid, s);
+    case 8: return launch_policy<T, 8, BLOCK>(t, tune.cache_policy, grid, s);
     }
     return fail(LA_ERR_INVALID_ARG, "unsupported unroll %d", tune.unroll);
 }

@@ -45,9 +45,10 @@ struct Step {
 
 // Per-segment record the kernels read.
 struct SegInfo {
-    uint64_t len;    // elements
-    uint32_t head;   // elements before the first 16-byte boundary (vector path only)
-    uint32_t vec_ok; // 1: all operands of the segment share the address modulo 16
+    uint64_t len;        // elements
+    uint32_t head;       // elements before the first 16-byte boundary (vector path only)
+    uint32_t vec_ok;     // 1: all operands of the segment share the address modulo 16
+    uint64_t alias_mask; // bit t: source t (t < 64) is also a destination of the segment
 };
 
 // Device view of one step, passed to the kernels by value.
@@ -60,21 +61,23 @@ struct StepTable {
     uint32_t num_segments;
 };
 
-// Launch shape of one step.  In the process-wide setting 0 (unroll, block) and -1 (nontemporal)
+// Launch shape of one step.  In the process-wide setting 0 (unroll, block) and -1 (cache_policy)
 // mean "choose per step from its fan-in, fan-out and segment length".
 struct Tuning {
     int unroll = 0;       // 16-byte vectors per lane and operand: 1, 2, 4, 8
-    int nontemporal = -1; // bit 0: loads, bit 1: stores
+    int cache_policy = -1; // 0..7, see Policy<> in kernels.hip
     int block = 0;        // lanes per workgroup: 256, 512, 1024
     bool operator==(const Tuning& o) const
     {
-        return unroll == o.unroll && block == o.block && nontemporal == o.nontemporal;
+        return unroll == o.unroll && block == o.block && cache_policy == o.cache_policy;
     }
 };
 Tuning current_tuning();
-// Fill the automatic fields of `requested` for a step with k sources, m destinations and a
-// longest segment of `longest_units` 16-byte vectors.
-Tuning resolve_tuning(const Tuning& requested, uint32_t k, uint32_t m, uint64_t longest_units);
+// Fill the automatic fields of `requested` for a step with k sources, m destinations, a longest
+// segment of `longest_units` 16-byte vectors and `bytes_per_operand` bytes summed over its
+// segments (the size of the step's result, and of its source when k == 1).
+Tuning resolve_tuning(const Tuning& requested, uint32_t k, uint32_t m, uint64_t longest_units,
+                      uint64_t bytes_per_operand);
 
 // kernels.hip
 la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream);

@@ -22,31 +22,38 @@ using namespace la;
 
 namespace la {
 static std::atomic<int> g_unroll{0};
-static std::atomic<int> g_nontemporal{-1};
+static std::atomic<int> g_cache_policy{-1};
 static std::atomic<int> g_block{0};
 
 Tuning current_tuning()
 {
     Tuning t;
     t.unroll = g_unroll.load();
-    t.nontemporal = g_nontemporal.load();
+    t.cache_policy = g_cache_policy.load();
     t.block = g_block.load();
     return t;
 }
 
-// Launch shapes measured on MI355X (HBM-bound; see the roofline notes of the build):
-//  - pure reduce (k >= 2, one destination): every operand is read once and the result is not
-//    read again by this launch, so loads and stores are non-temporal; large tiles keep each
-//    workgroup on long contiguous runs of every operand, which matters more as k grows;
-//  - copy / broadcast (k == 1): the source was produced by the previous launch and is often still
-//    cache-resident, so it is read with ordinary loads; with few destinations non-temporal stores
-//    keep the written stream from evicting it;
-//  - reduce with multi-destination store: ordinary accesses, 256-lane workgroups.
-Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longest_units)
+// Launch shapes and cache policies measured on MI355X (every step is HBM-bound):
+//  - pure reduce (k >= 2, one destination): every pure source is read once, so its loads are
+//    non-temporal; large tiles keep each workgroup on long contiguous runs of every operand,
+//    which matters more as k grows.  The result is what the next launch reads: if it fits the
+//    last-level cache it is stored with scope-1 stores (it stays resident), else streamed out;
+//  - copy / broadcast (k == 1): the source was produced by the previous launch.  If it fits the
+//    last-level cache it is read with ordinary loads and the destinations are written with
+//    non-temporal stores, so that the written stream does not evict it;
+//  - reduce with multi-destination store: every source is overwritten in place; ordinary loads,
+//    scope-1 stores.
+constexpr uint64_t LAST_LEVEL_CACHE_BYTES = 256ull << 20;
+
+Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longest_units, uint64_t bytes_per_operand)
 {
     Tuning t;
+    int cls; // step class: 0 pure reduce, 1 reduce + multi-destination store, 2 copy / broadcast
+    const bool fits = bytes_per_operand <= LAST_LEVEL_CACHE_BYTES;
     if (k >= 2 && m == 1) {
-        t.nontemporal = 3;
+        cls = 0;
+        t.cache_policy = fits ? 6 : 3;
         if (k >= 8) {
             t.block = 1024;
             t.unroll = 4;
@@ -58,27 +65,35 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
             t.unroll = 4;
         }
     } else if (k == 1) {
+        cls = 2;
         if (m == 1) {
-            t.nontemporal = 0;
+            t.cache_policy = 6;
             t.block = 256;
             t.unroll = 4;
         } else if (m <= 4) {
-            t.nontemporal = 2;
+            t.cache_policy = fits ? 4 : 7;
             t.block = 256;
             t.unroll = 1;
         } else {
-            t.nontemporal = 0;
+            t.cache_policy = fits ? 4 : 7;
             t.block = 1024;
             t.unroll = 4;
         }
     } else {
-        t.nontemporal = 0;
+        cls = 1;
+        t.cache_policy = 7;
         t.block = 256;
         t.unroll = 4;
     }
     if (req.unroll > 0) t.unroll = req.unroll;
     if (req.block > 0) t.block = req.block;
-    if (req.nontemporal >= 0) t.nontemporal = req.nontemporal;
+    if (req.cache_policy >= 100) {
+        // one digit per step class: reduce, reduce + multi-destination, copy / broadcast
+        const int digit[3] = {req.cache_policy / 100, (req.cache_policy / 10) % 10, req.cache_policy % 10};
+        t.cache_policy = digit[cls];
+    } else if (req.cache_policy >= 0) {
+        t.cache_policy = req.cache_policy;
+    }
     // a tile should not be much longer than the longest segment of the step
     if (req.unroll <= 0)
         while (t.unroll > 1 && (uint64_t)t.block * t.unroll > longest_units) t.unroll /= 2;
@@ -123,9 +138,14 @@ inline uint64_t align_up(uint64_t x, uint64_t a)
 
 // Fill SegInfo for one segment from its resolved operand addresses; returns its length in
 // 16-byte units as the launch sees it.
-uint64_t describe_segment(SegInfo& si, uint64_t len, const uint64_t* ptrs, size_t count, size_t esize)
+uint64_t describe_segment(SegInfo& si, uint64_t len, const uint64_t* ptrs, size_t count, size_t esize, size_t k)
 {
+    // ptrs = k sources followed by the destinations
     const uint64_t vec = 16 / esize;
+    si.alias_mask = 0;
+    for (size_t t = 0; t < k && t < 64; ++t)
+        for (size_t d = k; d < count; ++d)
+            if (ptrs[d] == ptrs[t]) si.alias_mask |= uint64_t(1) << t;
     bool congruent = true;
     for (size_t i = 1; i < count; ++i)
         if (((ptrs[i] ^ ptrs[0]) & 15u) != 0) congruent = false;
@@ -174,8 +194,9 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
         SegInfo* seg = reinterpret_cast<SegInfo*>(out.blob.data() + seg_at[i]);
         uint64_t* sp = reinterpret_cast<uint64_t*>(out.blob.data() + src_at[i]);
         uint64_t* dp = reinterpret_cast<uint64_t*>(out.blob.data() + dst_at[i]);
-        uint64_t longest = 0;
+        uint64_t longest = 0, step_elems = 0;
         for (size_t g = 0; g < S; ++g) {
+            step_elems += p.len[g];
             all.clear();
             for (int t = 0; t < p.k; ++t) {
                 const Operand& o = p.src[g * p.k + t];
@@ -187,7 +208,7 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
                 dp[g * p.m + d] = base[o.buf] + o.off * esize;
                 all.push_back(dp[g * p.m + d]);
             }
-            longest = std::max(longest, describe_segment(seg[g], p.len[g], all.data(), all.size(), esize));
+            longest = std::max(longest, describe_segment(seg[g], p.len[g], all.data(), all.size(), esize, (size_t)p.k));
         }
         StepTable& v = out.view[i];
         v.seg = reinterpret_cast<const SegInfo*>(seg_at[i]);
@@ -196,7 +217,7 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
         v.k = (uint32_t)p.k;
         v.m = (uint32_t)p.m;
         v.num_segments = (uint32_t)S;
-        shapes[i] = resolve_tuning(tune, v.k, v.m, longest);
+        shapes[i] = resolve_tuning(tune, v.k, v.m, longest, step_elems * esize);
         v.tiles_per_seg = tiles_for(longest, shapes[i]);
     }
 }
@@ -435,12 +456,15 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
     uint64_t* sp = reinterpret_cast<uint64_t*>(blob + seg_bytes);
     uint64_t* dp = reinterpret_cast<uint64_t*>(blob + seg_bytes + src_bytes);
     uint64_t longest = 0;
+    std::vector<uint64_t> all;
     for (size_t s = 0; s < num_segments; ++s) {
         const uint64_t byte_off = (uint64_t)seg_offsets[s] * e;
         sp[s * K] = d + byte_off;
         for (int t = 0; t < k; ++t) sp[s * K + 1 + t] = reinterpret_cast<uint64_t>(srcs[t]) + byte_off;
         dp[s] = d + byte_off;
-        longest = std::max(longest, describe_segment(seg[s], seg_len, sp + s * K, K, e));
+        all.assign(sp + s * K, sp + (s + 1) * K);
+        all.push_back(dp[s]);
+        longest = std::max(longest, describe_segment(seg[s], seg_len, all.data(), all.size(), e, K));
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     void* dev = nullptr;
@@ -462,7 +486,7 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
     t.k = (uint32_t)K;
     t.m = 1;
     t.num_segments = (uint32_t)num_segments;
-    const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest);
+    const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest, (uint64_t)num_segments * seg_len * e);
     t.tiles_per_seg = tiles_for(longest, tune);
     la_status_t st = launch_step(t, dtype, tune, hip_stream);
     (void)hipFreeAsync(dev, stream); // stream-ordered: freed after the kernel has run
@@ -479,10 +503,12 @@ la_status_t la_tuning_set(const char* key, int value)
         g_unroll.store(value);
         return LA_OK;
     }
-    if (k == "nontemporal") {
-        if (value < -1 || value > 3)
-            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: nontemporal must be -1 (auto) or 0..3");
-        g_nontemporal.store(value);
+    if (k == "cache_policy") {
+        const bool one = value >= -1 && value <= 7;
+        const bool three = value >= 100 && value / 100 <= 7 && (value / 10) % 10 <= 7 && value % 10 <= 7;
+        if (!one && !three)
+            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: cache_policy must be -1 (auto), 0..7, or three digits 0..7");
+        g_cache_policy.store(value);
         return LA_OK;
     }
     if (k == "block") {
@@ -499,7 +525,7 @@ int la_tuning_get(const char* key)
     if (!key) return -2;
     const std::string k(key);
     if (k == "unroll") return g_unroll.load();
-    if (k == "nontemporal") return g_nontemporal.load();
+    if (k == "cache_policy") return g_cache_policy.load();
     if (k == "block") return g_block.load();
     return -2;
 }

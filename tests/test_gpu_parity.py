@@ -115,12 +115,12 @@ def test_small_topologies_ragged_sizes_all_dtypes(oracle, algo, flags):
             assert np.array_equal(got[0], oracle.definition_sum(x))
 
 
-@pytest.mark.parametrize("unroll,nt,block", [(u, nt, b) for u in (1, 2, 4, 8) for nt in (0, 1, 2, 3) for b in (256, 1024)]
+@pytest.mark.parametrize("unroll,nt,block", [(u, nt, b) for u in (1, 2, 4, 8) for nt in range(8) for b in (256, 1024)]
                          + [(2, 3, 512), (0, -1, 0)])
 def test_every_launch_shape_gives_the_same_bits(oracle, unroll, nt, block):
     try:
         la.la_tuning_set("unroll", unroll)
-        la.la_tuning_set("nontemporal", nt)
+        la.la_tuning_set("cache_policy", nt)
         la.la_tuning_set("block", block)
         for algo, kind, n in (("lane_multiproc", "f32order", 50021), ("ring", "bf16", 33333), ("lane", "i32wrap", 9001)):
             x = make(12, n, kind, seed=unroll)
@@ -129,7 +129,7 @@ def test_every_launch_shape_gives_the_same_bits(oracle, unroll, nt, block):
             assert np.array_equal(bits(got), bits(ref)), (algo, kind)
     finally:
         la.la_tuning_set("unroll", 0)
-        la.la_tuning_set("nontemporal", -1)
+        la.la_tuning_set("cache_policy", -1)
         la.la_tuning_set("block", 0)
 
 

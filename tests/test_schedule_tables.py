@@ -77,9 +77,9 @@ def test_schedule_build_errors():
 
 
 def test_tuning_knobs():
-    assert (la.la_tuning_get("unroll"), la.la_tuning_get("nontemporal"), la.la_tuning_get("block")) == (0, -1, 0)
+    assert (la.la_tuning_get("unroll"), la.la_tuning_get("cache_policy"), la.la_tuning_get("block")) == (0, -1, 0)
     try:
-        for key, good, bad in (("unroll", (1, 2, 4, 8, 0), (3, -1, 16)), ("nontemporal", (0, 1, 2, 3, -1), (4, -2)),
+        for key, good, bad in (("unroll", (1, 2, 4, 8, 0), (3, -1, 16)), ("cache_policy", (0, 1, 2, 3, 4, 5, 6, 7, -1), (8, -2)),
                                ("block", (256, 512, 1024, 0), (128, 100, 2048))):
             for v in good:
                 la.la_tuning_set(key, v)
@@ -89,7 +89,7 @@ def test_tuning_knobs():
                     la.la_tuning_set(key, v)
     finally:
         la.la_tuning_set("unroll", 0)
-        la.la_tuning_set("nontemporal", -1)
+        la.la_tuning_set("cache_policy", -1)
         la.la_tuning_set("block", 0)
     with pytest.raises(la.LaError):
         la.la_tuning_set("no_such_knob", 1)
