@@ -19,11 +19,13 @@ _SRC = os.path.join(_HERE, "la_oracle.c")
 _LIB = os.path.join(_HERE, "libla_oracle.so")
 
 I32, F32, BF16 = 0, 1, 2
-RING, LANE, LANE_MULTIPROC = 0, 1, 2
-ALGOS = {"ring": RING, "lane": LANE, "lane_multiproc": LANE_MULTIPROC}
+RING, LANE, LANE_MULTIPROC, LANE_RING, LANE_MULTIPROC_RING = 0, 1, 2, 3, 4
+ALGOS = {"ring": RING, "lane": LANE, "lane_multiproc": LANE_MULTIPROC, "lane_ring": LANE_RING,
+         "lane_multiproc_ring": LANE_MULTIPROC_RING}
 
 # phases in the message trace
 PH_LANE_S1, PH_LANE_S2A, PH_LANE_S2B, PH_LANE_S3, PH_RING_RS, PH_RING_AG = 1, 2, 3, 4, 10, 11
+PH_LANE_S2_RING_RS, PH_LANE_S2_RING_AG = 5, 6
 
 MSG_DTYPE = np.dtype(
     [("phase", "<i4"), ("step", "<i4"), ("src", "<i4"), ("dst", "<i4"), ("off", "<u8"), ("cnt", "<u8")]
@@ -64,6 +66,7 @@ class Oracle:
     I32, F32, BF16 = I32, F32, BF16
     PH_LANE_S1, PH_LANE_S2A, PH_LANE_S2B, PH_LANE_S3 = PH_LANE_S1, PH_LANE_S2A, PH_LANE_S2B, PH_LANE_S3
     PH_RING_RS, PH_RING_AG = PH_RING_RS, PH_RING_AG
+    PH_LANE_S2_RING_RS, PH_LANE_S2_RING_AG = PH_LANE_S2_RING_RS, PH_LANE_S2_RING_AG
 
     def __init__(self, libpath: str):
         lib = ctypes.CDLL(libpath)

@@ -38,6 +38,9 @@
  *     part to the part's owner, who adds the operands in ascending
  *     communicator rank (its own copy taking its place in that order), and
  *     the all-reduce is that reduce-scatter followed by an all-gather;
+ *   - the "_ring" variants run Algorithm 1 as that inter-node all-reduce
+ *     instead: the owned part is cut into N pieces and member v of the lane
+ *     communicator plays rank v of a ring of N;
  *   - lanes first (one per GPU), then sub-chunks (one per process) inside a
  *     lane; "lane" without the multi-process split gives each lane to the
  *     GPU's leader process (local rank 0);
@@ -58,7 +61,15 @@
 #endif
 
 enum { ORACLE_I32 = 0, ORACLE_F32 = 1, ORACLE_BF16 = 2 };
-enum { ORACLE_RING = 0, ORACLE_LANE = 1, ORACLE_LANE_MULTIPROC = 2 };
+enum {
+    ORACLE_RING = 0,
+    ORACLE_LANE = 1,
+    ORACLE_LANE_MULTIPROC = 2,
+    /* Algorithm 2 with Algorithm 1 as the all-reduce on the lane communicator (the variant the
+     * Results section measures "where the ring algorithm is used in the inter-node stage") */
+    ORACLE_LANE_RING = 3,
+    ORACLE_LANE_MULTIPROC_RING = 4
+};
 
 /* phases recorded in the message trace */
 enum {
@@ -66,6 +77,8 @@ enum {
     PH_LANE_S2A = 2, /* inter-node reduce-scatter of parts */
     PH_LANE_S2B = 3, /* inter-node all-gather of pieces    */
     PH_LANE_S3 = 4,  /* intra-node all-gather              */
+    PH_LANE_S2_RING_RS = 5, /* inter-node stage as a ring: reduce loop */
+    PH_LANE_S2_RING_AG = 6, /* inter-node stage as a ring: gather loop */
     PH_RING_RS = 10, /* ring reduce-scatter loop           */
     PH_RING_AG = 11  /* ring all-gather loop               */
 };
@@ -376,6 +389,7 @@ static int run_ring(world_t* w, int max_rounds)
 typedef struct {
     int N, G, Q;
     int split_procs; /* 1: every process owns a sub-chunk; 0: the GPU's leader owns the lane */
+    int inner_ring;  /* 1: stage 2 is Algorithm 1 run on every lane communicator */
 } lane_cfg_t;
 
 static int rank_of(const lane_cfg_t* c, int node, int local)
@@ -448,9 +462,45 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
         end_round(w);
     }
 
+    /* stage 2, ring form: Algorithm 1 on every lane communicator at once.  The
+     * part is cut into N pieces; member v plays rank v of a ring of N. */
+    if (c->inner_ring) {
+        for (int loop = 0; loop < 2; ++loop) {
+            w->phase = loop == 0 ? PH_LANE_S2_RING_RS : PH_LANE_S2_RING_AG;
+            for (int i = 0; i < N - 1 && w->round < max_rounds; ++i) {
+                for (int j = 0; j < J; ++j) {
+                    uint64_t off, cnt, po, pc;
+                    part_of_buffer(c, w->n, j, &off, &cnt);
+                    int own = owner_local(c, j);
+                    for (int v = 0; v < N; ++v) {
+                        int sp = loop == 0 ? imod(v - i, N) : imod(v + 1 - i, N);
+                        part(cnt, (uint64_t)N, (uint64_t)sp, &po, &pc);
+                        post(w, rank_of(c, v, own), rank_of(c, (v + 1) % N, own), off + po, pc);
+                    }
+                }
+                for (int j = 0; j < J; ++j) {
+                    int own = owner_local(c, j);
+                    for (int v = 0; v < N; ++v) {
+                        int me = rank_of(c, v, own);
+                        const letter_t* le = letter_from(w, me, rank_of(c, imod(v - 1, N), own));
+                        if (!le) return 4;
+                        if (loop == 0) {
+                            char* mine = (char*)w->buf[me] + le->off * w->esz;
+                            const void* two[2] = {mine, le->data}; /* own = own + incoming */
+                            sum_operands(w->dtype, mine, two, 2, le->cnt);
+                        } else {
+                            overwrite(w, me, le);
+                        }
+                    }
+                }
+                end_round(w);
+            }
+        }
+    }
+
     /* stage 2: all-reduce of part j on the lane communicator (the owners of
      * part j on the N nodes), as reduce-scatter of N pieces + all-gather. */
-    if (w->round < max_rounds) {
+    if (!c->inner_ring && w->round < max_rounds) {
         w->phase = PH_LANE_S2A;
         for (int j = 0; j < J; ++j) {
             uint64_t off, cnt;
@@ -486,7 +536,7 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
         }
         end_round(w);
     }
-    if (w->round < max_rounds) {
+    if (!c->inner_ring && w->round < max_rounds) {
         w->phase = PH_LANE_S2B;
         for (int j = 0; j < J; ++j) {
             uint64_t off, cnt;
@@ -528,7 +578,8 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
  * Run a schedule over P = N*G*Q private buffers of n elements, in place.
  *   max_rounds < 0: run to the end; otherwise stop after that many rounds
  *   (ring: one round per loop iteration; lane: S1, S2a, S2b, S3 are one round
- *   each), so that tests can look at intermediate states.
+ *   each; lane with the ring inside: S1, then one round per ring iteration,
+ *   then S3), so that tests can look at intermediate states.
  *   trace / trace_cap: optional log of every message; *trace_len receives the
  *   number of messages sent (which may exceed trace_cap).
  * Returns 0 on success.
@@ -553,8 +604,10 @@ int oracle_allreduce(int algo, int N, int G, int Q, uint64_t n, int dtype, void*
     int rc;
     if (algo == ORACLE_RING) {
         rc = run_ring(&w, limit);
-    } else if (algo == ORACLE_LANE || algo == ORACLE_LANE_MULTIPROC) {
-        lane_cfg_t c = {N, G, Q, algo == ORACLE_LANE_MULTIPROC};
+    } else if (algo == ORACLE_LANE || algo == ORACLE_LANE_MULTIPROC || algo == ORACLE_LANE_RING ||
+               algo == ORACLE_LANE_MULTIPROC_RING) {
+        lane_cfg_t c = {N, G, Q, algo == ORACLE_LANE_MULTIPROC || algo == ORACLE_LANE_MULTIPROC_RING,
+                        algo == ORACLE_LANE_RING || algo == ORACLE_LANE_MULTIPROC_RING};
         rc = run_lane(&w, &c, limit);
     } else {
         rc = 2;

@@ -33,6 +33,12 @@ MUTATIONS = [
      "for (int l = 0; l < R - 1; ++l)\n                    if (l != own) post(w, rank_of(c, node, own), rank_of(c, node, l), off, cnt);"),
     ("proc_major_split", "*off = lo + so;", "*off = (uint64_t)q * (n / (uint64_t)c->Q) + so + lo / (uint64_t)c->Q;"),
     ("lane_owner_not_leader", "return c->split_procs ? j : j * c->Q;", "return c->split_procs ? j : j * c->Q + (c->Q - 1);"),
+    ("inner_ring_walks_forward", "int sp = loop == 0 ? imod(v - i, N) : imod(v + 1 - i, N);", "int sp = loop == 0 ? imod(v + i, N) : imod(v + 1 - i, N);"),
+    ("inner_ring_gather_starts_at_v", "int sp = loop == 0 ? imod(v - i, N) : imod(v + 1 - i, N);", "int sp = loop == 0 ? imod(v - i, N) : imod(v - i, N);"),
+    ("inner_ring_pieces_of_whole_buffer", "part(cnt, (uint64_t)N, (uint64_t)sp, &po, &pc);\n                        post(w, rank_of(c, v, own), rank_of(c, (v + 1) % N, own), off + po, pc);",
+     "part(w->n, (uint64_t)N, (uint64_t)sp, &po, &pc);\n                        post(w, rank_of(c, v, own), rank_of(c, (v + 1) % N, own), po, pc);"),
+    ("inner_ring_one_round_short", "for (int i = 0; i < N - 1 && w->round < max_rounds; ++i) {\n                for (int j = 0; j < J; ++j) {\n                    uint64_t off, cnt, po, pc;",
+     "for (int i = 0; i < N - 2 + loop && w->round < max_rounds; ++i) {\n                for (int j = 0; j < J; ++j) {\n                    uint64_t off, cnt, po, pc;"),
     ("rank_numbering_gpu_minor", "return node * c->G * c->Q + local;", "return local * c->N + node;"),
     ("bf16_truncates", "if (lost > 0x8000u)\n        kept += 1;", "if (lost > 0xffffu)\n        kept += 1;"),
     ("bf16_ties_away", "else if (lost == 0x8000u && (kept & 1u))", "else if (lost == 0x8000u)"),
@@ -71,6 +77,9 @@ def pin_calls(o):
         lambda: pins.test_lane_message_shapes(o),
         lambda: pins.test_reduce_segments_vs_numpy(o),
         lambda: pins.test_lane_equals_lane_multiproc_when_one_process_per_gpu(o),
+        lambda: pins.test_lane_ring_is_the_flat_ring_when_every_node_has_one_rank(o),
+        lambda: pins.test_lane_ring_order_node_sums_walk_the_ring(o),
+        lambda: pins.test_lane_ring_messages_and_boundaries(o),
     ]
     for algo in pins.ALGOS:
         for topo in ((2, 1, 1), (1, 2, 1), (1, 1, 2)):

@@ -13,7 +13,7 @@ import pytest
 from paper_2508_13397_amd import synth
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
-ALGOS = ("ring", "lane", "lane_multiproc")
+ALGOS = ("ring", "lane", "lane_multiproc", "lane_ring", "lane_multiproc_ring")
 TOL = {np.dtype(np.float32): 1e-5, np.dtype(np.uint16): 8e-3}
 
 
@@ -147,8 +147,8 @@ def test_bruteforce_floats_within_bound_and_all_ranks_identical(oracle, algo, di
             assert all(np.array_equal(out[0], out[r]) for r in range(P)), (algo, N, G, Q, n)
             if x.dtype == np.uint16:
                 xs, got = bf16_bits_to_f64(x), bf16_bits_to_f64(out[0])
-                if algo == "ring":
-                    continue  # P-1 roundings: only the bitwise parity is gated, not the tolerance
+                if "ring" in algo:
+                    continue  # a ring rounds once per hop: only the bitwise parity is gated there
             else:
                 xs, got = x.astype(np.float64), out[0].astype(np.float64)
             exact = np.array([math.fsum(xs[:, i]) for i in range(n)])
@@ -396,6 +396,71 @@ def test_lane_message_shapes(oracle):
     _, tl = oracle.allreduce("lane", N, G, Q, x, want_trace=True)
     t2 = tl[tl["phase"] == oracle.PH_LANE_S2A]
     assert np.all(t2["cnt"] == n // G // N) and np.all(t2["src"] % Q == 0)
+
+
+# --------------------------------------------------------------------------- ring inside the lane stage
+
+def test_lane_ring_is_the_flat_ring_when_every_node_has_one_rank(oracle):
+    x = synth.order_sensitive_f32(5, 37)
+    a, ta = oracle.allreduce("ring", 5, 1, 1, x, want_trace=True)
+    for algo in ("lane_ring", "lane_multiproc_ring"):
+        b, tb = oracle.allreduce(algo, 5, 1, 1, x, want_trace=True)
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+        for key in ("src", "dst", "off", "cnt"):
+            assert np.array_equal(ta[key], tb[key])
+
+
+def test_lane_ring_order_node_sums_walk_the_ring(oracle):
+    N, G, Q = 4, 2, 1
+    R, P = G * Q, N * G * Q
+    per = 3
+    n = G * N * per  # every piece has `per` elements
+    x = synth.order_sensitive_f32(P, n)
+    out = oracle.allreduce("lane_ring", N, G, Q, x)
+    node_sums = [f32_sum_in_order(x, [v * R + l for l in range(R)]) for v in range(N)]
+    for j in range(G):
+        for c in range(N):  # piece c of part j starts at member c and walks to c+1, c+2, ...
+            sl = slice(j * N * per + c * per, j * N * per + (c + 1) * per)
+            ref = node_sums[c][sl]
+            for t in range(1, N):
+                ref = ref + node_sums[(c + t) % N][sl]
+            assert np.array_equal(out[5, sl].view(np.uint32), ref.view(np.uint32)), (j, c)
+    direct = oracle.allreduce("lane", N, G, Q, x)
+    assert not np.array_equal(direct.view(np.uint32), out.view(np.uint32))  # the data tells them apart
+
+
+def test_lane_ring_messages_and_boundaries(oracle):
+    N, G, Q = 3, 2, 2
+    R, P = G * Q, N * G * Q
+    n = R * N * 4
+    c, piece = n // R, n // R // N
+    x = synth.make_inputs(P, n, "int_pm1000")
+    total = exact_int_sum(x)
+    out, tr = oracle.allreduce("lane_multiproc_ring", N, G, Q, x, want_trace=True)
+    assert np.array_equal(out, np.broadcast_to(total, out.shape))
+    for ph in (oracle.PH_LANE_S2_RING_RS, oracle.PH_LANE_S2_RING_AG):
+        t = tr[tr["phase"] == ph]
+        assert len(t) == (N - 1) * P and np.all(t["cnt"] == piece)
+        assert np.all(t["src"] % R == t["dst"] % R)                    # same local index
+        assert np.all(t["dst"] // R == (t["src"] // R + 1) % N)        # only to the next node
+        for r in range(P):
+            assert np.sum(t["src"] == r) == N - 1
+    assert not np.any((tr["phase"] == oracle.PH_LANE_S2A) | (tr["phase"] == oracle.PH_LANE_S2B))
+    # rounds: S1, N-1 reduce rounds, N-1 gather rounds, S3
+    mid = oracle.allreduce("lane_multiproc_ring", N, G, Q, x, max_rounds=1 + (N - 1))
+    for v in range(N):
+        for l in range(R):
+            r = v * R + l
+            own_piece = (v + 1) % N  # after the reduce loop member v holds the finished piece v+1
+            sl = slice(l * c + own_piece * piece, l * c + (own_piece + 1) * piece)
+            assert np.array_equal(mid[r, sl], total[sl])
+    before_s3 = oracle.allreduce("lane_multiproc_ring", N, G, Q, x, max_rounds=1 + 2 * (N - 1))
+    for v in range(N):
+        for l in range(R):
+            r = v * R + l
+            assert np.array_equal(before_s3[r, l * c:(l + 1) * c], total[l * c:(l + 1) * c])
+            other = (l + 1) % R
+            assert np.array_equal(before_s3[r, other * c:(other + 1) * c], x[r, other * c:(other + 1) * c])
 
 
 # --------------------------------------------------------------------------- reduce_segments
