@@ -65,7 +65,12 @@ enum {
      * from there and stores into the rank buffer.  This is the copy to and from a private
      * device buffer that the GPUDirect runs needed (Results, "GPUDirect RDMA Analysis").
      * Without it the reduce reads the peers' segments in place (fused pack + reduce). */
-    LA_SCHED_STAGED = 2u
+    LA_SCHED_STAGED = 2u,
+    /* Lane schedules only: the inter-node all-reduce of every part is Algorithm 1 run on the lane
+     * communicator (the variant of the Results section "where the ring algorithm is used in the
+     * inter-node stage of the multi-lane all-reduce"): 2(N-1) launches, each one ring iteration
+     * of all lane communicators, instead of the direct N-way exchange.  Ignored by LA_ALGO_RING. */
+    LA_SCHED_INNER_RING = 4u
 };
 
 /* Step kinds and stage labels reported by la_schedule_step_info. */
@@ -76,6 +81,8 @@ enum {
     LA_STAGE_S2B = 3,      /* inter-node all-gather of the pieces */
     LA_STAGE_S3 = 4,       /* intra-node all-gather (MPI_Allgatherv of Algorithm 2) */
     LA_STAGE_S2 = 5,       /* S2A and S2B in one launch (multi-destination store) */
+    LA_STAGE_S2_RING_RS = 6, /* LA_SCHED_INNER_RING: one reduce iteration of the inter-node rings */
+    LA_STAGE_S2_RING_AG = 7, /* LA_SCHED_INNER_RING: one gather iteration of the inter-node rings */
     LA_STAGE_RING_RS = 10, /* one iteration of the first loop of Algorithm 1 */
     LA_STAGE_RING_AG = 11, /* one iteration of the second loop of Algorithm 1 */
     LA_STAGE_PACK = 20     /* staged exchange: copy of incoming segments into the staging area */
@@ -141,7 +148,8 @@ la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_
  *   hip_stream  a hipStream_t (NULL = the default stream).  The call enqueues one kernel per
  *               step and returns without synchronising.
  * A schedule caches the device addresses it was last run with; a call with other buffers waits
- * for the schedule's previous work before rebinding.  Calls on one schedule must come from one
+ * for the schedule's previous work before rebinding.  Schedules with many launches (the ring
+ * forms) are recorded once per binding into a HIP graph of kernel nodes and replayed.  Calls on one schedule must come from one
  * thread at a time.
  * int32 wraps; fp32 adds are IEEE, in the fixed operand order of the tables; bf16 operands are
  * widened to fp32, summed in fp32 and rounded to nearest-even once per reduce step.
@@ -184,6 +192,8 @@ const char* la_last_error(void);
  *                 A three-digit value abc sets policy a for pure reduce steps, b for reduce
  *                 steps with several destinations and c for copy / broadcast steps.
  *   "block"       lanes per workgroup: 256, 512, 1024; 0 = automatic
+ *   "graph"       1: la_allreduce_emulated replays the schedule as one HIP graph of kernel nodes,
+ *                 0: it launches step by step, -1 (default): graph for schedules of 8+ launches
  * la_tuning_set returns LA_ERR_INVALID_ARG for an unknown key or value; la_tuning_get returns
  * the current setting, or -2 for an unknown key. */
 la_status_t la_tuning_set(const char* key, int value);

@@ -16,15 +16,17 @@ LA_OK, LA_ERR_INVALID_ARG, LA_ERR_UNSUPPORTED, LA_ERR_OUT_OF_MEMORY, LA_ERR_DEVI
 LA_ALGO_RING, LA_ALGO_LANE, LA_ALGO_LANE_MULTIPROC = 0, 1, 2
 LA_I32, LA_F32, LA_BF16 = 0, 1, 2
 LA_SUM = 0
-LA_SCHED_DEFAULT, LA_SCHED_P2P_GATHER, LA_SCHED_STAGED = 0, 1, 2
+LA_SCHED_DEFAULT, LA_SCHED_P2P_GATHER, LA_SCHED_STAGED, LA_SCHED_INNER_RING = 0, 1, 2, 4
 LA_STEP_REDUCE, LA_STEP_COPY = 0, 1
 LA_STAGE_S1, LA_STAGE_S2A, LA_STAGE_S2B, LA_STAGE_S3, LA_STAGE_S2 = 1, 2, 3, 4, 5
 LA_STAGE_RING_RS, LA_STAGE_RING_AG, LA_STAGE_PACK = 10, 11, 20
+LA_STAGE_S2_RING_RS, LA_STAGE_S2_RING_AG = 6, 7
 
 ALGOS = {"ring": LA_ALGO_RING, "lane": LA_ALGO_LANE, "lane_multiproc": LA_ALGO_LANE_MULTIPROC}
 DTYPES = {"int32": LA_I32, "float32": LA_F32, "bfloat16": LA_BF16}
 ELEM_SIZE = {LA_I32: 4, LA_F32: 4, LA_BF16: 2}
-STAGE_NAMES = {1: "S1", 2: "S2a", 3: "S2b", 4: "S3", 5: "S2", 10: "ring-RS", 11: "ring-AG", 20: "pack"}
+STAGE_NAMES = {1: "S1", 2: "S2a", 3: "S2b", 4: "S3", 5: "S2", 6: "S2-ring-RS", 7: "S2-ring-AG", 10: "ring-RS",
+               11: "ring-AG", 20: "pack"}
 
 # every symbol include/lane_allreduce.h declares
 EXPORTS = (

@@ -24,6 +24,8 @@ namespace la {
 static std::atomic<int> g_unroll{0};
 static std::atomic<int> g_cache_policy{-1};
 static std::atomic<int> g_block{0};
+static std::atomic<int> g_graph{-1}; // -1: graphs for schedules of GRAPH_MIN_STEPS launches or more
+constexpr int GRAPH_MIN_STEPS = 8;
 
 Tuning current_tuning()
 {
@@ -115,14 +117,30 @@ struct la_binding {
     hipEvent_t last_use = nullptr;
     bool used = false;
     std::vector<StepTable> step; // device views
+    // the whole schedule as one executable graph of kernel nodes (launch-bound schedules)
+    hipStream_t capture_stream = nullptr;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t graph_exec = nullptr;
+    bool graph_failed = false;
 };
 
 namespace la {
+
+static void drop_graph(la_binding* b)
+{
+    if (b->graph_exec) (void)hipGraphExecDestroy(b->graph_exec);
+    if (b->graph) (void)hipGraphDestroy(b->graph);
+    b->graph_exec = nullptr;
+    b->graph = nullptr;
+    b->graph_failed = false;
+}
 
 void release_binding(la_binding* b)
 {
     if (!b) return;
     if (b->used && b->last_use) (void)hipEventSynchronize(b->last_use);
+    drop_graph(b);
+    if (b->capture_stream) (void)hipStreamDestroy(b->capture_stream);
     if (b->tables) (void)hipFree(b->tables);
     if (b->staging) (void)hipFree(b->staging);
     if (b->last_use) (void)hipEventDestroy(b->last_use);
@@ -302,9 +320,35 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     relocate(ht.view, b->tables);
     b->step = std::move(ht.view);
     b->bufs.assign(addr.begin(), addr.begin() + P);
+    drop_graph(b); // recorded launches point at the old tables
     b->requested = tune;
     b->shape = std::move(shapes);
     b->used = false;
+    return LA_OK;
+}
+
+// Record every launch of the schedule into a graph of kernel nodes.  Only kernel launches are
+// captured (no memset or copy nodes).  On failure the binding falls back to stream launches.
+la_status_t capture_graph(const la_schedule_t* sched, la_binding* b)
+{
+    if (!b->capture_stream) LA_HIP(hipStreamCreateWithFlags(&b->capture_stream, hipStreamNonBlocking));
+    LA_HIP(hipStreamBeginCapture(b->capture_stream, hipStreamCaptureModeThreadLocal));
+    la_status_t st = LA_OK;
+    for (size_t i = 0; i < b->step.size() && st == LA_OK; ++i)
+        st = launch_step(b->step[i], sched->dtype, b->shape[i], b->capture_stream);
+    hipGraph_t g = nullptr;
+    const hipError_t e = hipStreamEndCapture(b->capture_stream, &g);
+    if (st != LA_OK || e != hipSuccess || !g) {
+        if (g) (void)hipGraphDestroy(g);
+        return st != LA_OK ? st : fail(LA_ERR_DEVICE, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+    }
+    hipGraphExec_t x = nullptr;
+    if (hipGraphInstantiate(&x, g, nullptr, nullptr, 0) != hipSuccess) {
+        (void)hipGraphDestroy(g);
+        return fail(LA_ERR_DEVICE, "hipGraphInstantiate failed");
+    }
+    b->graph = g;
+    b->graph_exec = x;
     return LA_OK;
 }
 
@@ -318,11 +362,25 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, int first, 
     st = bind(*sched, addr, tune);
     if (st != LA_OK) return st;
     la_binding* b = sched->bound;
-    for (int i = first; i < last; ++i) {
-        st = launch_step(b->step[i], sched->dtype, b->shape[i], hip_stream);
-        if (st != LA_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int mode = g_graph.load();
+    const bool whole = first == 0 && last == (int)sched->steps.size();
+    const bool want_graph = whole && last > 0 && (mode == 1 || (mode < 0 && last >= GRAPH_MIN_STEPS));
+    bool launched = false;
+    if (want_graph && !b->graph_failed) {
+        if (!b->graph_exec && capture_graph(sched, b) != LA_OK) b->graph_failed = true;
+        if (b->graph_exec) {
+            LA_HIP(hipGraphLaunch(b->graph_exec, stream));
+            launched = true;
+        }
     }
-    LA_HIP(hipEventRecord(b->last_use, static_cast<hipStream_t>(hip_stream)));
+    if (!launched) {
+        for (int i = first; i < last; ++i) {
+            st = launch_step(b->step[i], sched->dtype, b->shape[i], hip_stream);
+            if (st != LA_OK) return st;
+        }
+    }
+    LA_HIP(hipEventRecord(b->last_use, stream));
     b->used = true;
     return LA_OK;
 }
@@ -511,6 +569,11 @@ la_status_t la_tuning_set(const char* key, int value)
         g_cache_policy.store(value);
         return LA_OK;
     }
+    if (k == "graph") {
+        if (value < -1 || value > 1) return fail(LA_ERR_INVALID_ARG, "la_tuning_set: graph must be -1 (auto), 0 or 1");
+        g_graph.store(value);
+        return LA_OK;
+    }
     if (k == "block") {
         if (value != 0 && value != 256 && value != 512 && value != 1024)
             return fail(LA_ERR_INVALID_ARG, "la_tuning_set: block must be 0 (auto), 256, 512 or 1024");
@@ -527,6 +590,7 @@ int la_tuning_get(const char* key)
     if (k == "unroll") return g_unroll.load();
     if (k == "cache_policy") return g_cache_policy.load();
     if (k == "block") return g_block.load();
+    if (k == "graph") return g_graph.load();
     return -2;
 }
 

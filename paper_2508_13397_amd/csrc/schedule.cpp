@@ -165,10 +165,42 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
         rb.emit(s.steps);
     }
 
+    // S2, ring form (LA_SCHED_INNER_RING): Algorithm 1 on every lane communicator at once.  The
+    // part is cut into N pieces and member v plays rank v of a ring of N; one launch holds one
+    // ring iteration of all J lane communicators.
+    const bool inner_ring = (s.flags & LA_SCHED_INNER_RING) != 0;
+    if (N > 1 && inner_ring) {
+        for (int i = 0; i < N - 1; ++i) {
+            ReduceBuilder rb(s, st, LA_STAGE_S2_RING_RS, 2, 1);
+            for (int j = 0; j < J; ++j)
+                for (int v = 0; v < N; ++v) {
+                    const Part piece = split_part(part[j].cnt, N, imod(v - 1 - i, N));
+                    const uint64_t off = part[j].off + piece.off;
+                    const int me = t.rank_of(v, owner(j)), prev = t.rank_of(imod(v - 1, N), owner(j));
+                    rb.add(piece.cnt, {Operand{me, off}, Operand{prev, off}}, {Operand{me, off}}, me);
+                }
+            rb.emit(s.steps);
+        }
+        for (int i = 0; i < N - 1; ++i) {
+            Step cp;
+            cp.kind = LA_STEP_COPY;
+            cp.stage = LA_STAGE_S2_RING_AG;
+            cp.k = cp.m = 1;
+            for (int j = 0; j < J; ++j)
+                for (int v = 0; v < N; ++v) {
+                    const Part piece = split_part(part[j].cnt, N, imod(v - i, N));
+                    const uint64_t off = part[j].off + piece.off;
+                    push_copy(cp, piece.cnt, Operand{t.rank_of(imod(v - 1, N), owner(j)), off},
+                              Operand{t.rank_of(v, owner(j)), off});
+                }
+            if (!cp.len.empty()) s.steps.push_back(std::move(cp));
+        }
+    }
+
     // S2: all-reduce of part j among its N owners (the lane communicator): member v reduces
     // piece v of the part over the N members in ascending node order, then every member gets
     // every piece.
-    if (N > 1) {
+    if (N > 1 && !inner_ring) {
         ReduceBuilder rb(s, st, p2p ? LA_STAGE_S2A : LA_STAGE_S2, N, p2p ? 1 : N);
         Step ag;
         ag.kind = LA_STEP_COPY;
@@ -335,13 +367,14 @@ la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size
     if (!out) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: out is NULL");
     *out = nullptr;
     if (!topo) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: topology is NULL");
+    if (algo == LA_ALGO_RING) flags &= ~(unsigned)LA_SCHED_INNER_RING; // the flat ring has no inner stage
     if (n == 0) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: n is 0");
     if (n > (uint64_t(1) << 40)) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: n exceeds 2^40");
     if (dtype != LA_I32 && dtype != LA_F32 && dtype != LA_BF16)
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown dtype %d", (int)dtype);
     if (algo != LA_ALGO_RING && algo != LA_ALGO_LANE && algo != LA_ALGO_LANE_MULTIPROC)
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown algorithm %d", (int)algo);
-    if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED))
+    if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED | LA_SCHED_INNER_RING))
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown flag bits 0x%x", flags);
     la_schedule* s = new (std::nothrow) la_schedule;
     if (!s) return fail(LA_ERR_OUT_OF_MEMORY, "la_schedule_build: out of host memory");

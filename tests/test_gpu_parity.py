@@ -16,7 +16,13 @@ torch = pytest.importorskip("torch")
 
 TOL_F32, TOL_BF16 = 1e-5, 8e-3  # max |got - exact| / sum_p |in_p|, stated by the benchmark spec
 FLAG_SETS = (la.LA_SCHED_DEFAULT, la.LA_SCHED_P2P_GATHER, la.LA_SCHED_STAGED,
-             la.LA_SCHED_P2P_GATHER | la.LA_SCHED_STAGED)
+             la.LA_SCHED_P2P_GATHER | la.LA_SCHED_STAGED, la.LA_SCHED_INNER_RING,
+             la.LA_SCHED_INNER_RING | la.LA_SCHED_STAGED)
+
+
+def oracle_name(algo, flags):
+    """the oracle's name of what a schedule built with these flags computes"""
+    return algo + "_ring" if (flags & la.LA_SCHED_INNER_RING) and algo != "ring" else algo
 ALGOS = ("ring", "lane", "lane_multiproc")
 NAME = {np.dtype(np.int32): "int32", np.dtype(np.float32): "float32", np.dtype(np.uint16): "bfloat16"}
 
@@ -109,7 +115,7 @@ def test_small_topologies_ragged_sizes_all_dtypes(oracle, algo, flags):
         x = make(P, n, kind, seed=n)
         print("case", algo, flags, topo, n, kind, flush=True)
         got = gpu_allreduce(topo, algo, x, flags)
-        ref = oracle.allreduce(algo, *topo, x)
+        ref = oracle.allreduce(oracle_name(algo, flags), *topo, x)
         assert np.array_equal(bits(got), bits(ref)), (algo, flags, topo, n, kind)
         if kind == "i32wrap":
             assert np.array_equal(got[0], oracle.definition_sum(x))
@@ -258,6 +264,46 @@ def test_side_stream_rebinding_and_repeated_calls(oracle):
     assert np.array_equal(bits(np.stack([to_host(v) for v in b])), bits(oracle.allreduce("lane_multiproc", *topo, rolled)))
 
 
+@pytest.mark.parametrize("algo,flags,topo", [("ring", 0, (4, 2, 2)), ("lane_multiproc", la.LA_SCHED_INNER_RING, (6, 2, 2))])
+def test_graph_replays_match_step_by_step_launches(oracle, algo, flags, topo):
+    """Schedules with many launches are replayed as one HIP graph.  Replay it several times, with
+    other GPU work and synchronisations in between, and check every replay against the oracle and
+    against the step-by-step path."""
+    N, G, Q = topo
+    P, n = N * G * Q, 60013
+    x = make(P, n, "f32order", seed=5)
+    t = la.la_topology_create(N, G, Q)
+    sched = la.la_schedule_build(t, algo, n, "float32", flags)
+    assert sched.num_steps >= 8  # so that the automatic mode takes the graph path
+    bufs = [to_dev(x[r]) for r in range(P)]
+    eager = [to_dev(x[r]) for r in range(P)]
+    esched = la.la_schedule_build(t, algo, n, "float32", flags)
+    ref = x
+    scratch = torch.zeros(1 << 20, device="cuda")
+    try:
+        for replay in range(4):
+            la.la_tuning_set("graph", -1)
+            la.allreduce_tensors(sched, bufs)              # graph replay
+            scratch.add_(1.0)                               # unrelated eager work in between
+            torch.cuda.synchronize()
+            la.la_tuning_set("graph", 0)
+            la.allreduce_tensors(esched, eager)            # launch by launch
+            torch.cuda.synchronize()
+            ref = oracle.allreduce(oracle_name(algo, flags), N, G, Q, ref)
+            got = np.stack([to_host(b) for b in bufs])
+            assert np.array_equal(bits(got), bits(ref)), replay
+            assert np.array_equal(bits(np.stack([to_host(b) for b in eager])), bits(ref)), replay
+            assert float(scratch[0]) == replay + 1
+        # rebinding to other buffers drops the recorded graph and records a new one
+        la.la_tuning_set("graph", 1)
+        other = [to_dev(x[r]) for r in range(P)]
+        la.allreduce_tensors(sched, other)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(np.stack([to_host(b) for b in other])), bits(oracle.allreduce(oracle_name(algo, flags), N, G, Q, x)))
+    finally:
+        la.la_tuning_set("graph", -1)
+
+
 # ------------------------------------------------------------------------------ la_reduce_segments
 
 @pytest.mark.parametrize("kind", ["i32wrap", "f32order", "bf16"])
@@ -313,7 +359,7 @@ def full_size_case(oracle, topo, algo, n, dist, flags=la.LA_SCHED_DEFAULT, tol=T
                                         np.random.default_rng(1).integers(0, n, 200000)]))
         check_tolerance(oracle, np.ascontiguousarray(x[:, idx]), got0[idx])
     oracle.set_threads(min(16, oracle.max_threads()))
-    ref = oracle.allreduce(algo, N, G, Q, x, in_place=True)
+    ref = oracle.allreduce(oracle_name(algo, flags), N, G, Q, x, in_place=True)
     assert np.array_equal(bits(got0), bits(ref[0]))
     assert np.array_equal(bits(ref[P - 1]), bits(ref[0]))
 
@@ -344,6 +390,14 @@ def test_config5_scale_out_1024_ranks_1Mi_fp32(oracle):
     shape = [(s["stage_name"], s["num_segments"], s["fan_in"], s["fan_out"]) for s in sched.steps()]
     assert shape == [("S1", 1024, 32, 1), ("S2", 1024, 32, 32), ("S3", 1024, 1, 31)]
     full_size_case(oracle, topo, "lane_multiproc", 1 << 20, "uniform_pm1")
+
+
+def test_config3_inner_ring(oracle):
+    full_size_case(oracle, (8, 4, 4), "lane_multiproc", 1 << 22, "uniform_pm1", flags=la.LA_SCHED_INNER_RING)
+
+
+def test_config5_scale_out_inner_ring(oracle):
+    full_size_case(oracle, (32, 4, 8), "lane_multiproc", 1 << 20, "uniform_pm1", flags=la.LA_SCHED_INNER_RING)
 
 
 def test_config5_scale_out_point_to_point_gather(oracle):

@@ -15,7 +15,13 @@ from paper_2508_13397_amd import synth
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 ALGOS = ("ring", "lane", "lane_multiproc")
 FLAG_SETS = (la.LA_SCHED_DEFAULT, la.LA_SCHED_P2P_GATHER, la.LA_SCHED_STAGED,
-             la.LA_SCHED_P2P_GATHER | la.LA_SCHED_STAGED)
+             la.LA_SCHED_P2P_GATHER | la.LA_SCHED_STAGED, la.LA_SCHED_INNER_RING,
+             la.LA_SCHED_INNER_RING | la.LA_SCHED_STAGED | la.LA_SCHED_P2P_GATHER)
+
+
+def oracle_name(algo, flags):
+    """the oracle's name of what a schedule built with these flags computes"""
+    return algo + "_ring" if (flags & la.LA_SCHED_INNER_RING) and algo != "ring" else algo
 
 
 # ----------------------------------------------------------------------------- ABI surface
@@ -62,6 +68,7 @@ def test_schedule_build_errors():
         (dict(algo=7, n=16, dtype="float32"), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype=9), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype="float32", flags=64), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=8), la.LA_ERR_UNSUPPORTED),
     ):
         with pytest.raises(la.LaError) as e:
             la.la_schedule_build(t, **kwargs)
@@ -80,7 +87,7 @@ def test_tuning_knobs():
     assert (la.la_tuning_get("unroll"), la.la_tuning_get("cache_policy"), la.la_tuning_get("block")) == (0, -1, 0)
     try:
         for key, good, bad in (("unroll", (1, 2, 4, 8, 0), (3, -1, 16)), ("cache_policy", (0, 1, 2, 3, 4, 5, 6, 7, -1), (8, -2)),
-                               ("block", (256, 512, 1024, 0), (128, 100, 2048))):
+                               ("block", (256, 512, 1024, 0), (128, 100, 2048)), ("graph", (0, 1, -1), (2, -2))):
             for v in good:
                 la.la_tuning_set(key, v)
                 assert la.la_tuning_get(key) == v
@@ -196,7 +203,7 @@ def test_tables_reproduce_oracle_bitwise_small_topologies(oracle, algo, flags):
                 dt = {"i32": "int32", "f32": "float32", "bf16": "bfloat16"}[kind]
                 sched = la.la_schedule_build(topo, algo, n, dt, flags)
                 got = run_tables(sched, x)
-                ref = oracle.allreduce(algo, N, G, Q, x)
+                ref = oracle.allreduce(oracle_name(algo, flags), N, G, Q, x)
                 assert np.array_equal(got.view(np.uint8), ref.view(np.uint8)), (algo, flags, N, G, Q, n, kind)
                 if n == 17:
                     seq = run_tables(sched, x, snapshot=False)
@@ -281,6 +288,27 @@ def test_scale_out_shape_segment_counts_and_fan_in():
     by = {x["stage"]: x for x in d.steps()}
     assert (by[la.LA_STAGE_S2]["num_segments"], by[la.LA_STAGE_S2]["fan_in"], by[la.LA_STAGE_S2]["fan_out"]) == (1024, 32, 32)
     assert (by[la.LA_STAGE_S3]["num_segments"], by[la.LA_STAGE_S3]["fan_in"], by[la.LA_STAGE_S3]["fan_out"]) == (1024, 1, 31)
+
+
+def test_inner_ring_shape_and_bytes():
+    N, G, Q, n, e = 8, 4, 4, 1 << 22, 4
+    P = N * G * Q
+    s = la.la_schedule_build(la.la_topology_create(N, G, Q), "lane_multiproc", n, "float32", la.LA_SCHED_INNER_RING)
+    stages = [x["stage"] for x in s.steps()]
+    assert stages == [la.LA_STAGE_S1] + [la.LA_STAGE_S2_RING_RS] * (N - 1) + [la.LA_STAGE_S2_RING_AG] * (N - 1) + [la.LA_STAGE_S3]
+    piece = n // (G * Q) // N
+    for x in s.steps()[1:-1]:
+        assert (x["num_segments"], x["seg_len_max"]) == (P, piece)   # every rank moves one piece per iteration
+    # inter-node stage: 2 reads + 1 write per reduce iteration, 1 + 1 per gather iteration, of N*n/N each
+    inner = sum(x["bytes_read"] + x["bytes_written"] for x in s.steps()[1:-1])
+    assert inner == 5 * (N - 1) * n * e
+    # the flat ring ignores the flag
+    a = la.la_schedule_build(la.la_topology_create(2, 2, 1), "ring", 64, "float32", la.LA_SCHED_INNER_RING)
+    b = la.la_schedule_build(la.la_topology_create(2, 2, 1), "ring", 64, "float32")
+    assert a.num_steps == b.num_steps
+    for i in range(a.num_steps):
+        ta, tb = a.step_table(i), b.step_table(i)
+        assert all(np.array_equal(ta[key], tb[key]) for key in ta)
 
 
 def test_lane_tables_equal_lane_multiproc_tables_with_one_process_per_gpu():
