@@ -74,6 +74,8 @@ class Oracle:
         lib.oracle_allreduce.argtypes = [i32, i32, i32, i32, u64, i32, ctypes.POINTER(vp), i32,
                                          vp, u64, ctypes.POINTER(u64)]
         lib.oracle_allreduce.restype = i32
+        lib.oracle_allreduce_shared.argtypes = lib.oracle_allreduce.argtypes
+        lib.oracle_allreduce_shared.restype = i32
         lib.oracle_definition_sum.argtypes = [i32, i32, u64, ctypes.POINTER(vp), vp]
         lib.oracle_definition_sum.restype = i32
         lib.oracle_reduce_segments.argtypes = [i32, vp, ctypes.POINTER(vp), i32, vp, u64, u64]
@@ -92,11 +94,12 @@ class Oracle:
         return int(self.lib.oracle_max_threads())
 
     def allreduce(self, algo, N: int, G: int, Q: int, inputs, max_rounds: int = -1,
-                  want_trace: bool = False, in_place: bool = False):
-        """Simulate a schedule over the P = N*G*Q rank buffers `inputs` (a [P, n] array or a
-        list of P 1-D arrays).  Returns the result (and the message trace when asked)."""
+                  want_trace: bool = False, in_place: bool = False, shared: bool = False):
+        """Simulate a schedule over the rank buffers `inputs` (a 2-D array or a list of 1-D
+        arrays): P = N*G*Q private buffers, or with shared=True the N*G per-GPU buffers that the
+        Q processes of a GPU share.  Returns the result (and the message trace when asked)."""
         algo = ALGOS[algo] if isinstance(algo, str) else int(algo)
-        P = N * G * Q
+        P = N * G * (1 if shared else Q)
         if isinstance(inputs, np.ndarray):
             assert inputs.ndim == 2 and inputs.shape[0] == P
             work = inputs if in_place else inputs.copy()
@@ -112,9 +115,10 @@ class Oracle:
         trace, cap = None, 0
         if want_trace:
             # generous bound: ring sends 2(P-1)P messages, lane fewer than 4 P max(R, N)
-            cap = 4 * P * max(P, 2) + 16
+            cap = 4 * (N * G * Q) * max(N * G * Q, 2) + 16
             trace = np.zeros(cap, dtype=MSG_DTYPE)
-        rc = self.lib.oracle_allreduce(algo, N, G, Q, n, dtype_code(rows[0]), ptrs, int(max_rounds),
+        fn = self.lib.oracle_allreduce_shared if shared else self.lib.oracle_allreduce
+        rc = fn(algo, N, G, Q, n, dtype_code(rows[0]), ptrs, int(max_rounds),
                                        trace.ctypes.data if want_trace else None, cap,
                                        ctypes.byref(tlen))
         if rc != 0:

@@ -265,13 +265,20 @@ typedef struct {
     int dtype;
     size_t esz;
     uint64_t n;
-    void** buf;     /* buf[r]: rank r's buffer (caller's memory, updated in place) */
+    void** buf;     /* the buffers (caller's memory, updated in place) */
+    int share;      /* processes per buffer: 1 = every rank owns buf[r]; Q = the Q processes of a
+                       GPU work on the one buffer of their GPU, buf[r / Q] */
     inbox_t* inbox; /* inbox[r]: letters addressed to rank r in this round */
     oracle_msg_t* trace;
     uint64_t trace_cap, trace_len;
     int phase, round;
     int failed;
 } world_t;
+
+static char* mem(const world_t* w, int rank)
+{
+    return (char*)w->buf[rank / w->share];
+}
 
 static void post(world_t* w, int src, int dst, uint64_t off, uint64_t cnt)
 {
@@ -306,7 +313,7 @@ static void post(world_t* w, int src, int dst, uint64_t off, uint64_t cnt)
         l->cnt = 0;
         return;
     }
-    memcpy(l->data, (const char*)w->buf[src] + off * w->esz, cnt * w->esz);
+    memcpy(l->data, mem(w, src) + off * w->esz, cnt * w->esz);
 }
 
 static const letter_t* letter_from(const world_t* w, int at, int src)
@@ -329,7 +336,7 @@ static void end_round(world_t* w)
 
 static void overwrite(world_t* w, int at, const letter_t* l)
 {
-    memcpy((char*)w->buf[at] + l->off * w->esz, l->data, l->cnt * w->esz);
+    memcpy(mem(w, at) + l->off * w->esz, l->data, l->cnt * w->esz);
 }
 
 /* ---- Algorithm 1: ring_allreduce ---------------------------------------- */
@@ -359,7 +366,7 @@ static int run_ring(world_t* w, int max_rounds)
         for (int r = 0; r < P; ++r) {
             const letter_t* l = letter_from(w, r, imod(r - 1, P));
             if (!l) return 4;
-            char* own = (char*)w->buf[r] + l->off * w->esz;
+            char* own = mem(w, r) + l->off * w->esz;
             const void* ops[2] = {own, l->data}; /* own = own + incoming */
             sum_operands(w->dtype, own, ops, 2, l->cnt);
         }
@@ -447,7 +454,7 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
                 uint64_t off, cnt;
                 part_of_buffer(c, w->n, j, &off, &cnt);
                 int own = owner_local(c, j), me = rank_of(c, node, own);
-                char* mine = (char*)w->buf[me] + off * w->esz;
+                char* mine = mem(w, me) + off * w->esz;
                 for (int l = 0; l < R; ++l) {
                     if (l == own) {
                         ops[l] = mine;
@@ -485,7 +492,7 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
                         const letter_t* le = letter_from(w, me, rank_of(c, imod(v - 1, N), own));
                         if (!le) return 4;
                         if (loop == 0) {
-                            char* mine = (char*)w->buf[me] + le->off * w->esz;
+                            char* mine = mem(w, me) + le->off * w->esz;
                             const void* two[2] = {mine, le->data}; /* own = own + incoming */
                             sum_operands(w->dtype, mine, two, 2, le->cnt);
                         } else {
@@ -521,7 +528,7 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
                 uint64_t po, pc;
                 part(cnt, (uint64_t)N, (uint64_t)node, &po, &pc);
                 int me = rank_of(c, node, own);
-                char* mine = (char*)w->buf[me] + (off + po) * w->esz;
+                char* mine = mem(w, me) + (off + po) * w->esz;
                 for (int from = 0; from < N; ++from) {
                     if (from == node) {
                         ops[from] = mine;
@@ -574,6 +581,164 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
     return w->failed ? 3 : 0;
 }
 
+/* ---- the shared-buffer model ("Multiple Processes Per GPU" subsection) --------
+ * One buffer per GPU, N*G in all; the Q processes of a GPU all work on it, process q on the
+ * slice that starts at (s / PPG) * l_r: here part q of a balanced split of n into Q.  Processes
+ * with equal local rank q on all GPUs form new_comm (N*G members, member u = node*G + gpu). */
+
+static int proc_rank(int G, int Q, int node, int gpu, int q)
+{
+    return (node * G + gpu) * Q + q;
+}
+
+/* "Standard Approach": every process calls the library all-reduce on its slice over new_comm;
+ * the Q all-reduces run concurrently.  The library algorithm is a black box; it is taken to be
+ * Algorithm 1, the standard choice for large buffers (Background section). */
+static int run_shared_standard(world_t* w, int N, int G, int Q, int max_rounds)
+{
+    const int M = N * G; /* members of new_comm */
+    for (int loop = 0; loop < 2; ++loop) {
+        w->phase = loop == 0 ? PH_RING_RS : PH_RING_AG;
+        for (int i = 0; i < M - 1 && w->round < max_rounds; ++i) {
+            for (int q = 0; q < Q; ++q) {
+                uint64_t so, sc, co, cc;
+                part(w->n, (uint64_t)Q, (uint64_t)q, &so, &sc);
+                for (int u = 0; u < M; ++u) {
+                    int sp = loop == 0 ? imod(u - i, M) : imod(u + 1 - i, M);
+                    part(sc, (uint64_t)M, (uint64_t)sp, &co, &cc);
+                    post(w, u * Q + q, ((u + 1) % M) * Q + q, so + co, cc);
+                }
+            }
+            for (int q = 0; q < Q; ++q)
+                for (int u = 0; u < M; ++u) {
+                    int me = u * Q + q;
+                    const letter_t* le = letter_from(w, me, imod(u - 1, M) * Q + q);
+                    if (!le) return 4;
+                    if (loop == 0) {
+                        char* mine = mem(w, me) + le->off * w->esz;
+                        const void* two[2] = {mine, le->data};
+                        sum_operands(w->dtype, mine, two, 2, le->cnt);
+                    } else {
+                        overwrite(w, me, le);
+                    }
+                }
+            end_round(w);
+        }
+    }
+    return w->failed ? 3 : 0;
+}
+
+/* "Multi-lane Approach": every process runs Algorithm 2 on its slice.  comm_group = the G
+ * processes with local rank q on the node's GPUs, comm_lane = the N processes (node', gpu, q). */
+static int run_shared_lane(world_t* w, int N, int G, int Q, int max_rounds)
+{
+    const void** ops = (const void**)malloc(sizeof(void*) * (size_t)(G > N ? G : N));
+    if (!ops) return 3;
+    /* stage 1: reduce-scatter of slice q on comm_group: GPU g's process receives chunk g */
+    if (w->round < max_rounds) {
+        w->phase = PH_LANE_S1;
+        for (int node = 0; node < N; ++node)
+            for (int q = 0; q < Q; ++q) {
+                uint64_t so, sc, co, cc;
+                part(w->n, (uint64_t)Q, (uint64_t)q, &so, &sc);
+                for (int g = 0; g < G; ++g) {
+                    part(sc, (uint64_t)G, (uint64_t)g, &co, &cc);
+                    for (int from = 0; from < G; ++from)
+                        if (from != g) post(w, proc_rank(G, Q, node, from, q), proc_rank(G, Q, node, g, q), so + co, cc);
+                }
+            }
+        for (int node = 0; node < N; ++node)
+            for (int q = 0; q < Q; ++q) {
+                uint64_t so, sc, co, cc;
+                part(w->n, (uint64_t)Q, (uint64_t)q, &so, &sc);
+                for (int g = 0; g < G; ++g) {
+                    part(sc, (uint64_t)G, (uint64_t)g, &co, &cc);
+                    int me = proc_rank(G, Q, node, g, q);
+                    char* mine = mem(w, me) + (so + co) * w->esz;
+                    for (int from = 0; from < G; ++from) {
+                        if (from == g) {
+                            ops[from] = mine;
+                        } else {
+                            const letter_t* le = letter_from(w, me, proc_rank(G, Q, node, from, q));
+                            if (!le) return 4;
+                            ops[from] = le->data;
+                        }
+                    }
+                    sum_operands(w->dtype, mine, ops, G, cc);
+                }
+            }
+        end_round(w);
+    }
+    /* stage 2: all-reduce of the owned chunk on comm_lane (reduce-scatter of N pieces, then
+     * all-gather), operands in ascending node order */
+    for (int half = 0; half < 2; ++half) {
+        if (w->round >= max_rounds) break;
+        w->phase = half == 0 ? PH_LANE_S2A : PH_LANE_S2B;
+        for (int q = 0; q < Q; ++q) {
+            uint64_t so, sc, co, cc, po, pc;
+            part(w->n, (uint64_t)Q, (uint64_t)q, &so, &sc);
+            for (int g = 0; g < G; ++g) {
+                part(sc, (uint64_t)G, (uint64_t)g, &co, &cc);
+                for (int from = 0; from < N; ++from)
+                    for (int to = 0; to < N; ++to) {
+                        if (to == from) continue;
+                        /* first half: piece `to` goes to its reducer; second half: the reduced
+                         * piece `from` goes to everybody else */
+                        part(cc, (uint64_t)N, (uint64_t)(half == 0 ? to : from), &po, &pc);
+                        post(w, proc_rank(G, Q, from, g, q), proc_rank(G, Q, to, g, q), so + co + po, pc);
+                    }
+            }
+        }
+        if (half == 0) {
+            for (int q = 0; q < Q; ++q) {
+                uint64_t so, sc, co, cc, po, pc;
+                part(w->n, (uint64_t)Q, (uint64_t)q, &so, &sc);
+                for (int g = 0; g < G; ++g) {
+                    part(sc, (uint64_t)G, (uint64_t)g, &co, &cc);
+                    for (int node = 0; node < N; ++node) {
+                        part(cc, (uint64_t)N, (uint64_t)node, &po, &pc);
+                        int me = proc_rank(G, Q, node, g, q);
+                        char* mine = mem(w, me) + (so + co + po) * w->esz;
+                        for (int from = 0; from < N; ++from) {
+                            if (from == node) {
+                                ops[from] = mine;
+                            } else {
+                                const letter_t* le = letter_from(w, me, proc_rank(G, Q, from, g, q));
+                                if (!le) return 4;
+                                ops[from] = le->data;
+                            }
+                        }
+                        sum_operands(w->dtype, mine, ops, N, pc);
+                    }
+                }
+            }
+        } else {
+            for (int r = 0; r < w->P; ++r)
+                for (size_t i = 0; i < w->inbox[r].len; ++i) overwrite(w, r, &w->inbox[r].v[i]);
+        }
+        end_round(w);
+    }
+    /* stage 3: all-gatherv of slice q on comm_group */
+    if (w->round < max_rounds) {
+        w->phase = PH_LANE_S3;
+        for (int node = 0; node < N; ++node)
+            for (int q = 0; q < Q; ++q) {
+                uint64_t so, sc, co, cc;
+                part(w->n, (uint64_t)Q, (uint64_t)q, &so, &sc);
+                for (int g = 0; g < G; ++g) {
+                    part(sc, (uint64_t)G, (uint64_t)g, &co, &cc);
+                    for (int to = 0; to < G; ++to)
+                        if (to != g) post(w, proc_rank(G, Q, node, g, q), proc_rank(G, Q, node, to, q), so + co, cc);
+                }
+            }
+        for (int r = 0; r < w->P; ++r)
+            for (size_t i = 0; i < w->inbox[r].len; ++i) overwrite(w, r, &w->inbox[r].v[i]);
+        end_round(w);
+    }
+    free(ops);
+    return w->failed ? 3 : 0;
+}
+
 /*
  * Run a schedule over P = N*G*Q private buffers of n elements, in place.
  *   max_rounds < 0: run to the end; otherwise stop after that many rounds
@@ -584,7 +749,26 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
  *   number of messages sent (which may exceed trace_cap).
  * Returns 0 on success.
  */
+static int run_world(int shared, int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
+                     int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len);
+
 int oracle_allreduce(int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
+                     int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
+{
+    return run_world(0, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
+}
+
+/* The shared-buffer model: bufs holds N*G buffers (index node*G + gpu) of n elements; P = N*G*Q
+ * processes.  algo: ORACLE_RING = the "standard" multi-process all-reduce (Q concurrent rings
+ * over new_comm); ORACLE_LANE_MULTIPROC = Algorithm 2 per process on its slice.  Every buffer
+ * ends with the sum of the N*G buffers. */
+int oracle_allreduce_shared(int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
+                            int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
+{
+    return run_world(1, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
+}
+
+static int run_world(int shared, int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
                      int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
 {
     if (N < 1 || G < 1 || Q < 1 || !bufs) return 1;
@@ -596,13 +780,21 @@ int oracle_allreduce(int algo, int N, int G, int Q, uint64_t n, int dtype, void*
     w.esz = elem_size(dtype);
     w.n = n;
     w.buf = bufs;
+    w.share = shared ? Q : 1;
     w.inbox = (inbox_t*)calloc((size_t)w.P, sizeof(inbox_t));
     if (!w.inbox) return 3;
     w.trace = trace;
     w.trace_cap = trace ? trace_cap : 0;
     int limit = max_rounds < 0 ? 0x7fffffff : max_rounds;
     int rc;
-    if (algo == ORACLE_RING) {
+    if (shared) {
+        if (algo == ORACLE_RING)
+            rc = run_shared_standard(&w, N, G, Q, limit);
+        else if (algo == ORACLE_LANE_MULTIPROC)
+            rc = run_shared_lane(&w, N, G, Q, limit);
+        else
+            rc = 2;
+    } else if (algo == ORACLE_RING) {
         rc = run_ring(&w, limit);
     } else if (algo == ORACLE_LANE || algo == ORACLE_LANE_MULTIPROC || algo == ORACLE_LANE_RING ||
                algo == ORACLE_LANE_MULTIPROC_RING) {

@@ -39,6 +39,14 @@ MUTATIONS = [
      "part(w->n, (uint64_t)N, (uint64_t)sp, &po, &pc);\n                        post(w, rank_of(c, v, own), rank_of(c, (v + 1) % N, own), po, pc);"),
     ("inner_ring_one_round_short", "for (int i = 0; i < N - 1 && w->round < max_rounds; ++i) {\n                for (int j = 0; j < J; ++j) {\n                    uint64_t off, cnt, po, pc;",
      "for (int i = 0; i < N - 2 + loop && w->round < max_rounds; ++i) {\n                for (int j = 0; j < J; ++j) {\n                    uint64_t off, cnt, po, pc;"),
+    ("shared_standard_gpu_major_slices", "part(sc, (uint64_t)M, (uint64_t)sp, &co, &cc);\n                    post(w, u * Q + q, ((u + 1) % M) * Q + q, so + co, cc);",
+     "part(w->n, (uint64_t)M, (uint64_t)sp, &co, &cc); part(cc, (uint64_t)Q, (uint64_t)q, &so, &sc);\n                    post(w, u * Q + q, ((u + 1) % M) * Q + q, so + co, sc);"),
+    ("shared_standard_crosses_local_ranks", "post(w, u * Q + q, ((u + 1) % M) * Q + q, so + co, cc);", "post(w, u * Q + q, ((u + 1) % M) * Q + (q + 1) % Q, so + co, cc);"),
+    ("shared_lane_s1_descending", "                            ops[from] = le->data;\n                        }\n                    }\n                    sum_operands(w->dtype, mine, ops, G, cc);",
+     "                            ops[from] = le->data;\n                        }\n                    }\n                    if (G > 1) { const void* t0 = ops[0]; ops[0] = ops[G - 1]; ops[G - 1] = t0; }\n                    sum_operands(w->dtype, mine, ops, G, cc);"),
+    ("shared_lane_gather_skips_last_gpu", "for (int to = 0; to < G; ++to)\n                        if (to != g) post(w, proc_rank(G, Q, node, g, q), proc_rank(G, Q, node, to, q), so + co, cc);",
+     "for (int to = 0; to < G - 1; ++to)\n                        if (to != g) post(w, proc_rank(G, Q, node, g, q), proc_rank(G, Q, node, to, q), so + co, cc);"),
+    ("shared_lane_piece_of_wrong_member", "part(cc, (uint64_t)N, (uint64_t)(half == 0 ? to : from), &po, &pc);", "part(cc, (uint64_t)N, (uint64_t)(half == 0 ? from : to), &po, &pc);"),
     ("rank_numbering_gpu_minor", "return node * c->G * c->Q + local;", "return local * c->N + node;"),
     ("bf16_truncates", "if (lost > 0x8000u)\n        kept += 1;", "if (lost > 0xffffu)\n        kept += 1;"),
     ("bf16_ties_away", "else if (lost == 0x8000u && (kept & 1u))", "else if (lost == 0x8000u)"),
@@ -52,7 +60,8 @@ MUTATIONS = [
     ("definition_float_in_single", "double s = 0.0;\n            for (int p = 0; p < P; ++p) s += (double)((const float*)in[p])[i];",
      "float s = 0.0f;\n            for (int p = 0; p < P; ++p) s += ((const float*)in[p])[i];"),
     ("reduce_segments_ignores_dst", "sum_operands(dtype, (char*)dst + o * e, ops, k + 1, seg_len);", "sum_operands(dtype, (char*)dst + o * e, ops + (k > 0), k > 0 ? k : 1, seg_len);"),
-    ("overwrite_wrong_offset", "memcpy((char*)w->buf[at] + l->off * w->esz, l->data, l->cnt * w->esz);", "memcpy((char*)w->buf[at] + (l->off ? l->off - 1 : 0) * w->esz, l->data, l->cnt * w->esz);"),
+    ("overwrite_wrong_offset", "memcpy(mem(w, at) + l->off * w->esz, l->data, l->cnt * w->esz);", "memcpy(mem(w, at) + (l->off ? l->off - 1 : 0) * w->esz, l->data, l->cnt * w->esz);"),
+    ("shared_buffer_of_wrong_gpu", "return (char*)w->buf[rank / w->share];", "return (char*)w->buf[w->share > 1 ? rank % (w->P / w->share) : rank];"),
 ]
 
 
@@ -80,6 +89,11 @@ def pin_calls(o):
         lambda: pins.test_lane_ring_is_the_flat_ring_when_every_node_has_one_rank(o),
         lambda: pins.test_lane_ring_order_node_sums_walk_the_ring(o),
         lambda: pins.test_lane_ring_messages_and_boundaries(o),
+        lambda: pins.test_shared_model_with_one_process_per_gpu_is_the_private_model(o),
+        lambda: pins.test_shared_standard_messages_scale_with_processes_per_gpu(o),
+        lambda: pins.test_shared_lane_stages_and_order(o),
+        lambda: pins.test_shared_bruteforce_every_small_topology(o, "ring"),
+        lambda: pins.test_shared_bruteforce_every_small_topology(o, "lane_multiproc"),
     ]
     for algo in pins.ALGOS:
         for topo in ((2, 1, 1), (1, 2, 1), (1, 1, 2)):

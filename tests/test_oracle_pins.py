@@ -463,6 +463,95 @@ def test_lane_ring_messages_and_boundaries(oracle):
             assert np.array_equal(before_s3[r, other * c:(other + 1) * c], x[r, other * c:(other + 1) * c])
 
 
+# --------------------------------------------------------------------------- shared-buffer model
+
+SHARED_ALGOS = ("ring", "lane_multiproc")
+
+
+@pytest.mark.parametrize("algo", SHARED_ALGOS)
+def test_shared_bruteforce_every_small_topology(oracle, algo):
+    rng = np.random.default_rng(17)
+    for (N, G, Q) in TOPOS:
+        B = N * G
+        for n in (1, 2, 3, 5, 8, 12, 13, 27, 36, 40):
+            x = rng.integers(-(1 << 31), 1 << 31, size=(B, n), dtype=np.int64).astype(np.int32)
+            out = oracle.allreduce(algo, N, G, Q, x, shared=True)
+            assert np.array_equal(out, np.broadcast_to(exact_int_sum(x), out.shape)), (algo, N, G, Q, n)
+            f = synth.make_inputs(B, n, "uniform_pm1", seed=n)
+            got = oracle.allreduce(algo, N, G, Q, f, shared=True)
+            assert all(np.array_equal(got[0], got[b]) for b in range(B))
+            exact = np.array([math.fsum(f[:, i].astype(np.float64)) for i in range(n)])
+            assert np.all(np.abs(got[0] - exact) <= 1e-5 * np.abs(f).sum(axis=0))
+
+
+def test_shared_model_with_one_process_per_gpu_is_the_private_model(oracle):
+    x = synth.order_sensitive_f32(6, 41)
+    for shared_algo, private_algo in (("ring", "ring"), ("lane_multiproc", "lane")):
+        a, ta = oracle.allreduce(shared_algo, 3, 2, 1, x, shared=True, want_trace=True)
+        b, tb = oracle.allreduce(private_algo, 3, 2, 1, x, want_trace=True)
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+        for key in ("src", "dst", "off", "cnt"):
+            assert np.array_equal(ta[key], tb[key])
+
+
+def test_shared_standard_messages_scale_with_processes_per_gpu(oracle):
+    N, G, n = 2, 3, 6 * 4 * 5  # divisible by N*G*Q for Q = 1, 2, 4
+    M = N * G
+    x = synth.make_inputs(M, n, "int_pm1000")
+    counts = {}
+    for Q in (1, 2, 4):
+        out, tr = oracle.allreduce("ring", N, G, Q, x, shared=True, want_trace=True)
+        assert np.array_equal(out[0], exact_int_sum(x))
+        counts[Q] = len(tr)
+        assert np.all(tr["cnt"] == n // Q // M)                  # each message 1/PPG of the size
+        q = tr["src"] % Q
+        assert np.all(tr["dst"] % Q == q)                         # only inside new_comm (equal local rank)
+        assert np.all(tr["dst"] // Q == (tr["src"] // Q + 1) % M)  # to the next GPU's process
+        lo = q.astype(np.uint64) * (n // Q)
+        assert np.all((tr["off"] >= lo) & (tr["off"] + tr["cnt"] <= lo + n // Q))  # own slice only
+        for r in range(M * Q):
+            assert np.sum(tr["src"] == r) == 2 * (M - 1)
+    assert counts[2] == 2 * counts[1] and counts[4] == 4 * counts[1]  # message count grows by PPG
+
+
+def test_shared_lane_stages_and_order(oracle):
+    N, G, Q = 3, 3, 2
+    M = N * G
+    per = 2
+    n = Q * G * N * per
+    slice_len, c = n // Q, n // Q // G
+    x = synth.order_sensitive_f32(M, n)
+    out, tr = oracle.allreduce("lane_multiproc", N, G, Q, x, shared=True, want_trace=True)
+    # order: GPUs of a node in ascending order, then nodes in ascending order
+    node = [f32_sum_in_order(x, [v * G + g for g in range(G)]) for v in range(N)]
+    ref = node[0]
+    for v in range(1, N):
+        ref = ref + node[v]
+    assert np.array_equal(out[4].view(np.uint32), ref.view(np.uint32))
+    # message shapes: on-node stages move n/(Q*G), inter-node stages n/(Q*G*N)
+    gpu_of = lambda r: r // Q
+    for ph, cnt, same_node in ((oracle.PH_LANE_S1, c, True), (oracle.PH_LANE_S2A, c // N, False),
+                               (oracle.PH_LANE_S2B, c // N, False), (oracle.PH_LANE_S3, c, True)):
+        t = tr[tr["phase"] == ph]
+        assert len(t) and np.all(t["cnt"] == cnt)
+        assert np.all((gpu_of(t["src"]) // G == gpu_of(t["dst"]) // G) == same_node)
+        assert np.all(t["src"] % Q == t["dst"] % Q)
+        if not same_node:
+            assert np.all(gpu_of(t["src"]) % G == gpu_of(t["dst"]) % G)   # corresponding GPU on the other node
+    # after stage 1 the process (node, g, q) holds the node sum of chunk g of slice q, at q*(n/Q) + g*c
+    xi = synth.make_inputs(M, n, "int_pm1000")
+    s1 = oracle.allreduce("lane_multiproc", N, G, Q, xi, shared=True, max_rounds=1)
+    for v in range(N):
+        nsum = xi[v * G:(v + 1) * G].astype(np.int64).sum(axis=0).astype(np.int32)
+        for g in range(G):
+            for q in range(Q):
+                sl = slice(q * slice_len + g * c, q * slice_len + (g + 1) * c)
+                assert np.array_equal(s1[v * G + g, sl], nsum[sl])
+                o = (g + 1) % G
+                other = slice(q * slice_len + o * c, q * slice_len + (o + 1) * c)
+                assert np.array_equal(s1[v * G + g, other], xi[v * G + g, other])
+
+
 # --------------------------------------------------------------------------- reduce_segments
 
 def test_reduce_segments_vs_numpy(oracle):
