@@ -70,7 +70,22 @@ enum {
      * communicator (the variant of the Results section "where the ring algorithm is used in the
      * inter-node stage of the multi-lane all-reduce"): 2(N-1) launches, each one ring iteration
      * of all lane communicators, instead of the direct N-way exchange.  Ignored by LA_ALGO_RING. */
-    LA_SCHED_INNER_RING = 4u
+    LA_SCHED_INNER_RING = 4u,
+    /* The shared-buffer model of "Multiple Processes Per GPU": one buffer per GPU (bufs holds
+     * nodes * gpus_per_node pointers, index node * gpus_per_node + gpu); the procs_per_gpu
+     * processes of a GPU work on it, process q on part q of a balanced split of n.  The result in
+     * every buffer is the sum of the nodes * gpus_per_node buffers.
+     *   LA_ALGO_RING            the "Standard Approach": one all-reduce per local rank over the
+     *                           processes with that local rank (new_comm), all running at once;
+     *                           each is Algorithm 1 over nodes * gpus_per_node members.
+     *   LA_ALGO_LANE_MULTIPROC  the "Multi-lane Approach": Algorithm 2 per process on its slice
+     *                           (S1 fan-in = gpus_per_node).  LA_ALGO_LANE: the same with one
+     *                           process per GPU.
+     * With LA_SCHED_STAGED every process first copies its slice into a private staging slot, the
+     * all-reduce runs on the private copies, and the result is copied back (the copy to and from
+     * a buffer allocated by the calling process of the GPUDirect runs).  LA_SCHED_INNER_RING is
+     * not available in this model. */
+    LA_SCHED_SHARED_BUFFERS = 8u
 };
 
 /* Step kinds and stage labels reported by la_schedule_step_info. */
@@ -120,6 +135,8 @@ la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size
 la_status_t la_schedule_destroy(la_schedule_t* sched);
 
 int la_schedule_num_steps(const la_schedule_t* sched);       /* -1 for NULL */
+int la_schedule_num_buffers(const la_schedule_t* sched);     /* entries of bufs: P, or nodes * gpus_per_node
+                                                                with LA_SCHED_SHARED_BUFFERS; -1 for NULL */
 size_t la_schedule_staging_elems(const la_schedule_t* sched); /* elements of library-owned staging */
 
 /* Shape of one step.  Any out pointer may be NULL.  bytes_* are the algorithmic bytes of the
@@ -129,8 +146,9 @@ la_status_t la_schedule_step_info(const la_schedule_t* sched, int step, int* kin
                                   size_t* bytes_read, size_t* bytes_written);
 
 /* Copy out the table of one step [host arrays sized from la_schedule_step_info]:
- * seg_len[S]; src_buf/src_off[S*fan_in]; dst_buf/dst_off[S*fan_out].  A buffer index in [0,P)
- * is a rank; index P is the staging area.  Offsets are in elements. */
+ * seg_len[S]; src_buf/src_off[S*fan_in]; dst_buf/dst_off[S*fan_out].  A buffer index below
+ * la_schedule_num_buffers() is a caller buffer; that number itself is the staging area.  Offsets
+ * are in elements. */
 la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_t* seg_len, int32_t* src_buf,
                                    uint64_t* src_off, int32_t* dst_buf, uint64_t* dst_off);
 
@@ -140,7 +158,8 @@ la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_
  * In-place all-reduce: on return of the enqueued work every bufs[r] holds the element-wise SUM
  * of the P input buffers (the MPI_Allreduce(..., MPI_SUM, ...) of the "Standard Approach"
  * listing, with send and receive buffer the same).
- *   bufs        [host] array of P [device] pointers, each to n elements of dtype, aligned to
+ *   bufs        [host] array of la_schedule_num_buffers() [device] pointers (P unless the schedule
+ *               was built with LA_SCHED_SHARED_BUFFERS), each to n elements of dtype, aligned to
  *               the element size, pairwise disjoint.  128-bit accesses are used when all
  *               buffers share the same address modulo 16 bytes; otherwise a slower
  *               element-wise path runs.

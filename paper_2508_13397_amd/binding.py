@@ -17,6 +17,7 @@ LA_ALGO_RING, LA_ALGO_LANE, LA_ALGO_LANE_MULTIPROC = 0, 1, 2
 LA_I32, LA_F32, LA_BF16 = 0, 1, 2
 LA_SUM = 0
 LA_SCHED_DEFAULT, LA_SCHED_P2P_GATHER, LA_SCHED_STAGED, LA_SCHED_INNER_RING = 0, 1, 2, 4
+LA_SCHED_SHARED_BUFFERS = 8
 LA_STEP_REDUCE, LA_STEP_COPY = 0, 1
 LA_STAGE_S1, LA_STAGE_S2A, LA_STAGE_S2B, LA_STAGE_S3, LA_STAGE_S2 = 1, 2, 3, 4, 5
 LA_STAGE_RING_RS, LA_STAGE_RING_AG, LA_STAGE_PACK = 10, 11, 20
@@ -32,6 +33,7 @@ STAGE_NAMES = {1: "S1", 2: "S2a", 3: "S2b", 4: "S3", 5: "S2", 6: "S2-ring-RS", 7
 EXPORTS = (
     "la_topology_create", "la_topology_destroy", "la_topology_num_ranks",
     "la_schedule_build", "la_schedule_build_ex", "la_schedule_destroy", "la_schedule_num_steps",
+    "la_schedule_num_buffers",
     "la_schedule_staging_elems", "la_schedule_step_info", "la_schedule_step_table",
     "la_allreduce_emulated", "la_schedule_run_step", "la_reduce_segments",
     "la_status_string", "la_last_error", "la_tuning_set", "la_tuning_get",
@@ -66,6 +68,7 @@ def lib() -> ctypes.CDLL:
     L.la_schedule_build_ex.argtypes = [vp, i32, sz, i32, u32, pp(vp)]
     L.la_schedule_destroy.argtypes = [vp]
     L.la_schedule_num_steps.argtypes = [vp]
+    L.la_schedule_num_buffers.argtypes = [vp]
     L.la_schedule_staging_elems.argtypes = [vp]
     L.la_schedule_staging_elems.restype = sz
     L.la_schedule_step_info.argtypes = [vp, i32, pp(i32), pp(i32), pp(sz), pp(sz), pp(i32), pp(i32), pp(sz), pp(sz)]
@@ -161,6 +164,10 @@ class Schedule:
     @property
     def num_steps(self) -> int:
         return int(lib().la_schedule_num_steps(self.handle))
+
+    @property
+    def num_buffers(self) -> int:
+        return int(lib().la_schedule_num_buffers(self.handle))
 
     @property
     def staging_elems(self) -> int:

@@ -103,6 +103,8 @@ struct la_schedule {
     la_dtype_t dtype;
     uint64_t n;
     unsigned flags;
+    int nbuf = 0; // caller buffers: one per rank, or one per GPU with LA_SCHED_SHARED_BUFFERS;
+                  // buffer index nbuf in the tables is the staging area
     uint64_t staging_elems = 0;
     std::vector<la::Step> steps;
     // device-side state, created by the first run

@@ -252,7 +252,7 @@ void relocate(std::vector<StepTable>& view, const void* device_base)
 
 la_status_t check_buffers(const la_schedule& s, void* const* bufs, std::vector<uint64_t>& addr)
 {
-    const int P = s.topo.ranks();
+    const int P = s.nbuf;
     const size_t e = dtype_size(s.dtype);
     addr.resize(P + 1);
     for (int r = 0; r < P; ++r) {
@@ -275,7 +275,7 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     int dev = -1;
     LA_HIP(hipGetDevice(&dev));
     la_binding* b = s.bound;
-    const int P = s.topo.ranks();
+    const int P = s.nbuf;
     if (b && b->device == dev && b->requested == tune && b->bufs.size() == (size_t)P &&
         std::equal(addr.begin(), addr.begin() + P, b->bufs.begin()))
         return LA_OK;

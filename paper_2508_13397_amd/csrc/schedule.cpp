@@ -53,7 +53,7 @@ struct ReduceBuilder {
     ReduceBuilder(const la_schedule& sc, Staging& stg, int stage, int k, int m) : s(sc), st(stg)
     {
         staged = (sc.flags & LA_SCHED_STAGED) != 0;
-        P = sc.topo.ranks();
+        P = sc.nbuf;
         pack.kind = LA_STEP_COPY;
         pack.stage = LA_STAGE_PACK;
         pack.k = 1;
@@ -255,16 +255,185 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
     }
 }
 
+// ---- the shared-buffer model -------------------------------------------------------------------
+// One buffer per GPU (index node*G + gpu); the Q processes of a GPU work on it, process q on part q
+// of a balanced split of n into Q ("Multiple Processes Per GPU": the slice at (s/PPG) * l_r).
+
+// "Standard Approach": Q concurrent all-reduces, one per local rank, each over the N*G processes
+// with that local rank (new_comm), each taken to be Algorithm 1.  One launch holds one iteration
+// of all Q rings: the message count grows by Q and the message size shrinks by Q.
+void gen_shared_standard(la_schedule& s, Staging& st)
+{
+    const int M = s.topo.nodes * s.topo.gpus, Q = s.topo.procs;
+    auto chunk = [&](int q, int c) {
+        const Part slice = split_part(s.n, Q, q);
+        const Part ch = split_part(slice.cnt, M, c);
+        return Part{slice.off + ch.off, ch.cnt};
+    };
+    for (int i = 0; i < M - 1; ++i) {
+        ReduceBuilder rb(s, st, LA_STAGE_RING_RS, 2, 1);
+        for (int q = 0; q < Q; ++q)
+            for (int u = 0; u < M; ++u) {
+                const Part c = chunk(q, imod(u - 1 - i, M));
+                rb.add(c.cnt, {Operand{u, c.off}, Operand{imod(u - 1, M), c.off}}, {Operand{u, c.off}}, u);
+            }
+        rb.emit(s.steps);
+    }
+    for (int i = 0; i < M - 1; ++i) {
+        Step cp;
+        cp.kind = LA_STEP_COPY;
+        cp.stage = LA_STAGE_RING_AG;
+        cp.k = cp.m = 1;
+        for (int q = 0; q < Q; ++q)
+            for (int u = 0; u < M; ++u) {
+                const Part c = chunk(q, imod(u - i, M));
+                push_copy(cp, c.cnt, Operand{imod(u - 1, M), c.off}, Operand{u, c.off});
+            }
+        if (!cp.len.empty()) s.steps.push_back(std::move(cp));
+    }
+}
+
+// "Multi-lane Approach": every process runs Algorithm 2 on its slice; comm_group = the G
+// processes with local rank q on the node, comm_lane = the N processes (node', gpu, q).
+void gen_shared_lane(la_schedule& s, Staging& st, int Q)
+{
+    const la_topology& t = s.topo;
+    const int N = t.nodes, G = t.gpus;
+    const bool p2p = (s.flags & LA_SCHED_P2P_GATHER) != 0;
+    auto buf = [&](int node, int g) { return node * G + g; };
+    auto chunk = [&](int q, int g) {
+        const Part slice = split_part(s.n, Q, q);
+        const Part ch = split_part(slice.cnt, G, g);
+        return Part{slice.off + ch.off, ch.cnt};
+    };
+    if (G > 1) {
+        ReduceBuilder rb(s, st, LA_STAGE_S1, G, 1);
+        for (int node = 0; node < N; ++node)
+            for (int q = 0; q < Q; ++q)
+                for (int g = 0; g < G; ++g) {
+                    const Part c = chunk(q, g);
+                    std::vector<Operand> ops(G);
+                    for (int h = 0; h < G; ++h) ops[h] = Operand{buf(node, h), c.off};
+                    rb.add(c.cnt, ops, {Operand{buf(node, g), c.off}}, buf(node, g));
+                }
+        rb.emit(s.steps);
+    }
+    if (N > 1) {
+        ReduceBuilder rb(s, st, p2p ? LA_STAGE_S2A : LA_STAGE_S2, N, p2p ? 1 : N);
+        Step ag;
+        ag.kind = LA_STEP_COPY;
+        ag.stage = LA_STAGE_S2B;
+        ag.k = ag.m = 1;
+        for (int q = 0; q < Q; ++q)
+            for (int g = 0; g < G; ++g)
+                for (int v = 0; v < N; ++v) {
+                    const Part c = chunk(q, g);
+                    const Part piece = split_part(c.cnt, N, v);
+                    const uint64_t off = c.off + piece.off;
+                    std::vector<Operand> ops(N), dsts;
+                    for (int w = 0; w < N; ++w) ops[w] = Operand{buf(w, g), off};
+                    dsts.push_back(Operand{buf(v, g), off});
+                    for (int w = 0; w < N; ++w) {
+                        if (w == v) continue;
+                        if (p2p)
+                            push_copy(ag, piece.cnt, Operand{buf(v, g), off}, Operand{buf(w, g), off});
+                        else
+                            dsts.push_back(Operand{buf(w, g), off});
+                    }
+                    rb.add(piece.cnt, ops, dsts, buf(v, g));
+                }
+        rb.emit(s.steps);
+        if (p2p && !ag.len.empty()) s.steps.push_back(std::move(ag));
+    }
+    if (G > 1) {
+        Step ag;
+        ag.kind = LA_STEP_COPY;
+        ag.stage = LA_STAGE_S3;
+        ag.k = 1;
+        ag.m = p2p ? 1 : G - 1;
+        for (int node = 0; node < N; ++node)
+            for (int q = 0; q < Q; ++q)
+                for (int g = 0; g < G; ++g) {
+                    const Part c = chunk(q, g);
+                    if (c.cnt == 0) continue;
+                    const Operand from{buf(node, g), c.off};
+                    if (!p2p) {
+                        ag.len.push_back(c.cnt);
+                        ag.src.push_back(from);
+                    }
+                    for (int h = 0; h < G; ++h) {
+                        if (h == g) continue;
+                        if (p2p)
+                            push_copy(ag, c.cnt, from, Operand{buf(node, h), c.off});
+                        else
+                            ag.dst.push_back(Operand{buf(node, h), c.off});
+                    }
+                }
+        if (!ag.len.empty()) s.steps.push_back(std::move(ag));
+    }
+}
+
+// LA_SCHED_STAGED in the shared model: every process first copies its slice of the shared buffer
+// into a private staging slot, the all-reduce then runs on those private copies, and the result
+// is copied back: the copy to and from a device buffer allocated by the calling process that the
+// GPUDirect runs needed because the MPI library refused buffers shared through IPC.
+void wrap_copy_in_out(la_schedule& s, Staging& st, int Q)
+{
+    const int M = s.nbuf;
+    std::vector<Part> slice(Q);
+    std::vector<uint64_t> slot((size_t)M * Q);
+    for (int q = 0; q < Q; ++q) slice[q] = split_part(s.n, Q, q);
+    Step in, out;
+    in.kind = out.kind = LA_STEP_COPY;
+    in.stage = out.stage = LA_STAGE_PACK;
+    in.k = in.m = out.k = out.m = 1;
+    for (int b = 0; b < M; ++b)
+        for (int q = 0; q < Q; ++q) {
+            slot[(size_t)b * Q + q] = st.take(slice[q].cnt);
+            push_copy(in, slice[q].cnt, Operand{b, slice[q].off}, Operand{M, slot[(size_t)b * Q + q]});
+            push_copy(out, slice[q].cnt, Operand{M, slot[(size_t)b * Q + q]}, Operand{b, slice[q].off});
+        }
+    auto to_private = [&](Operand& o) {
+        int q = 0;
+        while (q + 1 < Q && o.off >= slice[q].off + slice[q].cnt) ++q;
+        o = Operand{M, slot[(size_t)o.buf * Q + q] + (o.off - slice[q].off)};
+    };
+    for (Step& p : s.steps) {
+        for (Operand& o : p.src) to_private(o);
+        for (Operand& o : p.dst) to_private(o);
+    }
+    if (!in.len.empty()) {
+        s.steps.insert(s.steps.begin(), std::move(in));
+        s.steps.push_back(std::move(out));
+    }
+}
+
 } // namespace
 
 la_status_t generate_steps(la_schedule& s)
 {
     Staging st;
-    switch (s.algo) {
-    case LA_ALGO_RING: gen_ring(s, st); break;
-    case LA_ALGO_LANE: gen_lane(s, st, false); break;
-    case LA_ALGO_LANE_MULTIPROC: gen_lane(s, st, true); break;
-    default: return fail(LA_ERR_UNSUPPORTED, "unknown algorithm %d", (int)s.algo);
+    if (s.flags & LA_SCHED_SHARED_BUFFERS) {
+        if (s.flags & LA_SCHED_INNER_RING)
+            return fail(LA_ERR_UNSUPPORTED, "LA_SCHED_INNER_RING is not available with LA_SCHED_SHARED_BUFFERS");
+        const unsigned staged = s.flags & LA_SCHED_STAGED;
+        s.flags &= ~(unsigned)LA_SCHED_STAGED; // here staging means copy-in / copy-out, not per-message packs
+        const int Q = s.algo == LA_ALGO_LANE ? 1 : s.topo.procs; // "lane": the leader handles the whole buffer
+        switch (s.algo) {
+        case LA_ALGO_RING: gen_shared_standard(s, st); break;
+        case LA_ALGO_LANE:
+        case LA_ALGO_LANE_MULTIPROC: gen_shared_lane(s, st, Q); break;
+        default: return fail(LA_ERR_UNSUPPORTED, "unknown algorithm %d", (int)s.algo);
+        }
+        s.flags |= staged;
+        if (staged) wrap_copy_in_out(s, st, s.algo == LA_ALGO_RING ? s.topo.procs : Q);
+    } else {
+        switch (s.algo) {
+        case LA_ALGO_RING: gen_ring(s, st); break;
+        case LA_ALGO_LANE: gen_lane(s, st, false); break;
+        case LA_ALGO_LANE_MULTIPROC: gen_lane(s, st, true); break;
+        default: return fail(LA_ERR_UNSUPPORTED, "unknown algorithm %d", (int)s.algo);
+        }
     }
     s.staging_elems = st.peak;
     for (const Step& p : s.steps) {
@@ -287,7 +456,7 @@ la_status_t validate_hazards(const la_schedule& s)
         bool write;
     };
     const uint64_t limit_stage = s.staging_elems;
-    const int P = s.topo.ranks();
+    const int P = s.nbuf;
     std::vector<Iv> iv;
     for (size_t si = 0; si < s.steps.size(); ++si) {
         const Step& p = s.steps[si];
@@ -374,7 +543,7 @@ la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown dtype %d", (int)dtype);
     if (algo != LA_ALGO_RING && algo != LA_ALGO_LANE && algo != LA_ALGO_LANE_MULTIPROC)
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown algorithm %d", (int)algo);
-    if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED | LA_SCHED_INNER_RING))
+    if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED | LA_SCHED_INNER_RING | LA_SCHED_SHARED_BUFFERS))
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown flag bits 0x%x", flags);
     la_schedule* s = new (std::nothrow) la_schedule;
     if (!s) return fail(LA_ERR_OUT_OF_MEMORY, "la_schedule_build: out of host memory");
@@ -383,6 +552,7 @@ la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size
     s->dtype = dtype;
     s->n = n;
     s->flags = flags;
+    s->nbuf = (flags & LA_SCHED_SHARED_BUFFERS) ? topo->nodes * topo->gpus : topo->ranks();
     la_status_t st;
     try {
         st = generate_steps(*s);
@@ -415,6 +585,11 @@ la_status_t la_schedule_destroy(la_schedule_t* sched)
 int la_schedule_num_steps(const la_schedule_t* sched)
 {
     return sched ? (int)sched->steps.size() : -1;
+}
+
+int la_schedule_num_buffers(const la_schedule_t* sched)
+{
+    return sched ? sched->nbuf : -1;
 }
 
 size_t la_schedule_staging_elems(const la_schedule_t* sched)

@@ -304,6 +304,54 @@ def test_graph_replays_match_step_by_step_launches(oracle, algo, flags, topo):
         la.la_tuning_set("graph", -1)
 
 
+# ------------------------------------------------------------------------------ shared-buffer model
+
+SHARED = la.LA_SCHED_SHARED_BUFFERS
+
+
+@pytest.mark.parametrize("algo", ["ring", "lane_multiproc", "lane"])
+@pytest.mark.parametrize("extra", [0, la.LA_SCHED_P2P_GATHER, la.LA_SCHED_STAGED])
+def test_shared_buffers_small_topologies(oracle, algo, extra):
+    for (topo, n), kind in itertools.product([((2, 2, 2), 100003), ((3, 2, 4), 40961), ((1, 3, 2), 7), ((2, 1, 3), 12289),
+                                              ((2, 4, 3), 262147)], ("i32wrap", "f32order", "bf16")):
+        N, G, Q = topo
+        B = N * G
+        x = make(B, n, kind, seed=n)
+        print("shared case", algo, extra, topo, n, kind, flush=True)
+        t = la.la_topology_create(N, G, Q)
+        sched = la.la_schedule_build(t, algo, n, NAME[x.dtype], SHARED | extra)
+        assert sched.num_buffers == B
+        bufs = [to_dev(x[b]) for b in range(B)]
+        la.allreduce_tensors(sched, bufs)
+        torch.cuda.synchronize()
+        got = np.stack([to_host(b) for b in bufs])
+        if algo == "lane":
+            ref = oracle.allreduce("lane_multiproc", N, G, 1, x, shared=True)
+        else:
+            ref = oracle.allreduce(algo, N, G, Q, x, shared=True)
+        assert np.array_equal(bits(got), bits(ref)), (algo, extra, topo, n, kind)
+
+
+@pytest.mark.parametrize("algo,extra", [("ring", 0), ("lane_multiproc", 0), ("lane_multiproc", la.LA_SCHED_STAGED)])
+def test_shared_buffers_full_size_16_gpus_4_procs_64Mi_fp32(oracle, algo, extra):
+    # the paper's regime: a large fp32 buffer per GPU, several processes per GPU each on a slice
+    N, G, Q, n = 4, 4, 4, 1 << 26
+    B = N * G
+    x = synth.make_inputs(B, n, "normal", workers=16)
+    sched = la.la_schedule_build(la.la_topology_create(N, G, Q), algo, n, "float32", SHARED | extra)
+    bufs = [to_dev(x[b]) for b in range(B)]
+    la.allreduce_tensors(sched, bufs)
+    torch.cuda.synchronize()
+    got0 = to_host(bufs[0])
+    for b in range(1, B):
+        assert torch.equal(bufs[b].view(torch.int32), bufs[0].view(torch.int32)), b
+    del bufs
+    torch.cuda.empty_cache()
+    oracle.set_threads(min(16, oracle.max_threads()))
+    ref = oracle.allreduce(algo, N, G, Q, x, in_place=True, shared=True)
+    assert np.array_equal(bits(got0), bits(ref[0]))
+
+
 # ------------------------------------------------------------------------------ la_reduce_segments
 
 @pytest.mark.parametrize("kind", ["i32wrap", "f32order", "bf16"])

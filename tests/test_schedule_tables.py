@@ -68,7 +68,7 @@ def test_schedule_build_errors():
         (dict(algo=7, n=16, dtype="float32"), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype=9), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype="float32", flags=64), la.LA_ERR_UNSUPPORTED),
-        (dict(algo="lane", n=16, dtype="float32", flags=8), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=16), la.LA_ERR_UNSUPPORTED),
     ):
         with pytest.raises(la.LaError) as e:
             la.la_schedule_build(t, **kwargs)
@@ -208,6 +208,70 @@ def test_tables_reproduce_oracle_bitwise_small_topologies(oracle, algo, flags):
                 if n == 17:
                     seq = run_tables(sched, x, snapshot=False)
                     assert np.array_equal(seq.view(np.uint8), got.view(np.uint8))
+
+
+SHARED = la.LA_SCHED_SHARED_BUFFERS
+
+
+@pytest.mark.parametrize("algo", ["ring", "lane_multiproc", "lane"])
+@pytest.mark.parametrize("extra", [0, la.LA_SCHED_P2P_GATHER, la.LA_SCHED_STAGED, la.LA_SCHED_P2P_GATHER | la.LA_SCHED_STAGED])
+def test_shared_buffer_tables_reproduce_oracle_bitwise(oracle, algo, extra):
+    for (N, G, Q) in TOPOS:
+        B = N * G
+        topo = la.la_topology_create(N, G, Q)
+        for n in (1, 3, 10, 17, 36, 40):
+            for kind in ("i32", "f32", "bf16"):
+                if kind == "i32":
+                    x = np.random.default_rng(n).integers(-(1 << 31), 1 << 31, size=(B, n), dtype=np.int64).astype(np.int32)
+                elif kind == "f32":
+                    x = synth.order_sensitive_f32(B, n)
+                else:
+                    x = synth.to_bf16_bits(synth.order_sensitive_f32(B, n) * np.float32(2.0 ** -20))
+                dt = {"i32": "int32", "f32": "float32", "bf16": "bfloat16"}[kind]
+                sched = la.la_schedule_build(topo, algo, n, dt, SHARED | extra)
+                assert sched.num_buffers == B
+                got = run_tables(sched, x)
+                if algo == "lane":  # one process per GPU does the whole buffer
+                    ref = oracle.allreduce("lane_multiproc", N, G, 1, x, shared=True)
+                else:
+                    ref = oracle.allreduce(algo, N, G, Q, x, shared=True)
+                assert np.array_equal(got.view(np.uint8), ref.view(np.uint8)), (algo, extra, N, G, Q, n, kind)
+                if n == 17:
+                    seq = run_tables(sched, x, snapshot=False)
+                    assert np.array_equal(seq.view(np.uint8), got.view(np.uint8))
+
+
+def test_shared_buffer_shapes_and_bytes():
+    N, G, Q, n, e = 4, 4, 4, 1 << 22, 4
+    M = N * G
+    t = la.la_topology_create(N, G, Q)
+    std = la.la_schedule_build(t, "ring", n, "float32", SHARED)
+    one = la.la_schedule_build(la.la_topology_create(N, G, 1), "ring", n, "float32", SHARED)
+    assert std.num_buffers == M and std.num_steps == one.num_steps == 2 * (M - 1)
+    for a, b in zip(std.steps(), one.steps()):
+        # Q times the messages, each 1/Q of the size, same bytes
+        assert a["num_segments"] == Q * b["num_segments"] and a["seg_len_max"] * Q == b["seg_len_max"]
+        assert (a["bytes_read"], a["bytes_written"]) == (b["bytes_read"], b["bytes_written"])
+    assert sum(totals(std)) == 5 * (M - 1) * n * e
+    lane = la.la_schedule_build(t, "lane_multiproc", n, "float32", SHARED)
+    st = {x["stage"]: x for x in lane.steps()}
+    assert (st[la.LA_STAGE_S1]["fan_in"], st[la.LA_STAGE_S1]["num_segments"], st[la.LA_STAGE_S1]["seg_len_max"]) == (G, M * Q, n // (Q * G))
+    assert (st[la.LA_STAGE_S1]["bytes_read"], st[la.LA_STAGE_S1]["bytes_written"]) == (M * n * e, N * n * e)
+    assert (st[la.LA_STAGE_S2]["fan_in"], st[la.LA_STAGE_S2]["seg_len_max"]) == (N, n // (Q * G * N))   # inter-node piece / procs per node
+    assert (st[la.LA_STAGE_S3]["bytes_read"], st[la.LA_STAGE_S3]["bytes_written"]) == (N * n * e, (M - N) * n * e)
+    # copy-in / copy-out: one private slot per process, the all-reduce touches staging only
+    staged = la.la_schedule_build(t, "lane_multiproc", n, "float32", SHARED | la.LA_SCHED_STAGED)
+    assert staged.staging_elems >= M * n
+    steps = staged.steps()
+    assert steps[0]["stage"] == steps[-1]["stage"] == la.LA_STAGE_PACK
+    assert steps[0]["num_segments"] == steps[-1]["num_segments"] == M * Q
+    for i in range(1, staged.num_steps - 1):
+        tb = staged.step_table(i)
+        assert np.all(tb["src_buf"] == M) and np.all(tb["dst_buf"] == M)
+    assert np.all(staged.step_table(0)["dst_buf"] == M) and np.all(staged.step_table(0)["src_buf"] < M)
+    with pytest.raises(la.LaError) as err:
+        la.la_schedule_build(t, "lane_multiproc", n, "float32", SHARED | la.LA_SCHED_INNER_RING)
+    assert err.value.status == la.LA_ERR_UNSUPPORTED
 
 
 def test_hazard_freedom_every_step_reads_no_range_another_segment_writes():
