@@ -18,7 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "la_oracle.c")
 _LIB = os.path.join(_HERE, "libla_oracle.so")
 
-I32, F32, BF16 = 0, 1, 2
+I32, F32, BF16, F16, F64 = 0, 1, 2, 3, 4
+OPS = {"sum": 0, "prod": 1, "max": 2, "min": 3}
 RING, LANE, LANE_MULTIPROC, LANE_RING, LANE_MULTIPROC_RING = 0, 1, 2, 3, 4
 ALGOS = {"ring": RING, "lane": LANE, "lane_multiproc": LANE_MULTIPROC, "lane_ring": LANE_RING,
          "lane_multiproc_ring": LANE_MULTIPROC_RING}
@@ -42,13 +43,12 @@ def build(force: bool = True, src: str = _SRC, lib: str = _LIB) -> str:
 
 
 def dtype_code(arr: np.ndarray) -> int:
-    if arr.dtype == np.int32:
-        return I32
-    if arr.dtype == np.float32:
-        return F32
-    if arr.dtype == np.uint16:
-        return BF16
-    raise TypeError(f"oracle buffers must be int32, float32 or uint16 (bf16 bits), not {arr.dtype}")
+    table = {np.dtype(np.int32): I32, np.dtype(np.float32): F32, np.dtype(np.uint16): BF16,
+             np.dtype(np.float16): F16, np.dtype(np.float64): F64}
+    if arr.dtype not in table:
+        raise TypeError("oracle buffers must be int32, float32, float16, float64 or uint16 (bf16 bits), "
+                        f"not {arr.dtype}")
+    return table[arr.dtype]
 
 
 def _row_ptrs(rows):
@@ -76,10 +76,14 @@ class Oracle:
         lib.oracle_allreduce.restype = i32
         lib.oracle_allreduce_shared.argtypes = lib.oracle_allreduce.argtypes
         lib.oracle_allreduce_shared.restype = i32
-        lib.oracle_definition_sum.argtypes = [i32, i32, u64, ctypes.POINTER(vp), vp]
-        lib.oracle_definition_sum.restype = i32
-        lib.oracle_reduce_segments.argtypes = [i32, vp, ctypes.POINTER(vp), i32, vp, u64, u64]
-        lib.oracle_reduce_segments.restype = i32
+        lib.oracle_allreduce_op.argtypes = [i32, i32] + list(lib.oracle_allreduce.argtypes)
+        lib.oracle_allreduce_op.restype = i32
+        lib.oracle_definition_reduce.argtypes = [i32, i32, i32, u64, ctypes.POINTER(vp), vp]
+        lib.oracle_definition_reduce.restype = i32
+        lib.oracle_reduce_segments_op.argtypes = [i32, i32, vp, ctypes.POINTER(vp), i32, vp, u64, u64]
+        lib.oracle_reduce_segments_op.restype = i32
+        lib.oracle_f16_round.argtypes = [vp, vp, u64]
+        lib.oracle_f16_widen.argtypes = [vp, vp, u64]
         lib.oracle_bf16_round.argtypes = [vp, vp, u64]
         lib.oracle_bf16_widen.argtypes = [vp, vp, u64]
         lib.oracle_part.argtypes = [u64, u64, u64, ctypes.POINTER(u64), ctypes.POINTER(u64)]
@@ -94,7 +98,7 @@ class Oracle:
         return int(self.lib.oracle_max_threads())
 
     def allreduce(self, algo, N: int, G: int, Q: int, inputs, max_rounds: int = -1,
-                  want_trace: bool = False, in_place: bool = False, shared: bool = False):
+                  want_trace: bool = False, in_place: bool = False, shared: bool = False, op="sum"):
         """Simulate a schedule over the rank buffers `inputs` (a 2-D array or a list of 1-D
         arrays): P = N*G*Q private buffers, or with shared=True the N*G per-GPU buffers that the
         Q processes of a GPU share.  Returns the result (and the message trace when asked)."""
@@ -117,10 +121,10 @@ class Oracle:
             # generous bound: ring sends 2(P-1)P messages, lane fewer than 4 P max(R, N)
             cap = 4 * (N * G * Q) * max(N * G * Q, 2) + 16
             trace = np.zeros(cap, dtype=MSG_DTYPE)
-        fn = self.lib.oracle_allreduce_shared if shared else self.lib.oracle_allreduce
-        rc = fn(algo, N, G, Q, n, dtype_code(rows[0]), ptrs, int(max_rounds),
-                                       trace.ctypes.data if want_trace else None, cap,
-                                       ctypes.byref(tlen))
+        opc = OPS[op] if isinstance(op, str) else int(op)
+        rc = self.lib.oracle_allreduce_op(1 if shared else 0, opc, algo, N, G, Q, n, dtype_code(rows[0]), ptrs,
+                                          int(max_rounds), trace.ctypes.data if want_trace else None, cap,
+                                          ctypes.byref(tlen))
         if rc != 0:
             raise RuntimeError(f"oracle_allreduce failed with code {rc}")
         if want_trace:
@@ -128,25 +132,30 @@ class Oracle:
             return work, trace[: tlen.value]
         return work
 
-    def definition_sum(self, inputs):
+    def definition_reduce(self, inputs, op="sum"):
         """The all-reduce by its definition: int32 -> int32 (exact, wrapped); floats -> float64."""
-        rows = [inputs[r] for r in range(len(inputs))]
+        rows = [np.ascontiguousarray(inputs[r]) for r in range(len(inputs))]
         n = rows[0].shape[0]
         code = dtype_code(rows[0])
         out = np.empty(n, dtype=np.int32 if code == I32 else np.float64)
-        rc = self.lib.oracle_definition_sum(code, len(rows), n, _row_ptrs(rows), out.ctypes.data)
+        opc = OPS[op] if isinstance(op, str) else int(op)
+        rc = self.lib.oracle_definition_reduce(code, opc, len(rows), n, _row_ptrs(rows), out.ctypes.data)
         if rc != 0:
-            raise RuntimeError(f"oracle_definition_sum failed with code {rc}")
+            raise RuntimeError(f"oracle_definition_reduce failed with code {rc}")
         return out
 
-    def reduce_segments(self, dst: np.ndarray, srcs, seg_offsets, seg_len: int) -> np.ndarray:
+    def definition_sum(self, inputs):
+        return self.definition_reduce(inputs, "sum")
+
+    def reduce_segments(self, dst: np.ndarray, srcs, seg_offsets, seg_len: int, op="sum") -> np.ndarray:
         """dst[o] = ((dst[o] + srcs[0][o]) + srcs[1][o]) + ... over every segment; a copy."""
         out = dst.copy()
         offs = np.ascontiguousarray(seg_offsets, dtype=np.uint64)
         srcs = [np.ascontiguousarray(s) for s in srcs]
         ptrs = _row_ptrs(srcs) if srcs else (ctypes.c_void_p * 1)()
-        rc = self.lib.oracle_reduce_segments(dtype_code(out), out.ctypes.data, ptrs, len(srcs),
-                                             offs.ctypes.data, len(offs), int(seg_len))
+        opc = OPS[op] if isinstance(op, str) else int(op)
+        rc = self.lib.oracle_reduce_segments_op(dtype_code(out), opc, out.ctypes.data, ptrs, len(srcs),
+                                                offs.ctypes.data, len(offs), int(seg_len))
         if rc != 0:
             raise RuntimeError(f"oracle_reduce_segments failed with code {rc}")
         return out
@@ -161,6 +170,18 @@ class Oracle:
         h = np.ascontiguousarray(h, dtype=np.uint16)
         out = np.empty(h.shape, dtype=np.float32)
         self.lib.oracle_bf16_widen(h.ctypes.data, out.ctypes.data, h.size)
+        return out
+
+    def f16_round(self, x: np.ndarray) -> np.ndarray:
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        out = np.empty(x.shape, dtype=np.uint16)
+        self.lib.oracle_f16_round(x.ctypes.data, out.ctypes.data, x.size)
+        return out
+
+    def f16_widen(self, h: np.ndarray) -> np.ndarray:
+        h = np.ascontiguousarray(h, dtype=np.uint16)
+        out = np.empty(h.shape, dtype=np.float32)
+        self.lib.oracle_f16_widen(h.ctypes.data, out.ctypes.data, h.size)
         return out
 
     def part(self, length: int, m: int, i: int):
@@ -196,8 +217,12 @@ def definition_sum(inputs):
     return default().definition_sum(inputs)
 
 
-def reduce_segments(dst, srcs, seg_offsets, seg_len):
-    return default().reduce_segments(dst, srcs, seg_offsets, seg_len)
+def reduce_segments(dst, srcs, seg_offsets, seg_len, op="sum"):
+    return default().reduce_segments(dst, srcs, seg_offsets, seg_len, op)
+
+
+def definition_reduce(inputs, op="sum"):
+    return default().definition_reduce(inputs, op)
 
 
 def bf16_round(x):

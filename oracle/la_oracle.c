@@ -45,8 +45,11 @@
  *     lane; "lane" without the multi-process split gives each lane to the
  *     GPU's leader process (local rank 0);
  *   - int32 wraps (two's complement); fp32 is IEEE binary32 add, left to
- *     right; bf16 operands are widened exactly to fp32, added in fp32 and
- *     rounded once (nearest, ties to even) when a step stores its result.
+ *     right; bf16 and fp16 operands are widened exactly to fp32, added in fp32
+ *     and rounded once (nearest, ties to even) when a step stores its result;
+ *     fp64 is IEEE binary64.  The operations other than the sum (product,
+ *     maximum, minimum) are not in the paper; they run on the same schedules
+ *     with the binary operations defined under "one binary operation".
  *
  * Parity pins: see tests/test_oracle_*.py (definition, closed forms, the
  * index walk of Algorithm 1, stage boundaries of Algorithm 2, brute force).
@@ -60,7 +63,9 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_I32 = 0, ORACLE_F32 = 1, ORACLE_BF16 = 2 };
+enum { ORACLE_I32 = 0, ORACLE_F32 = 1, ORACLE_BF16 = 2, ORACLE_F16 = 3, ORACLE_F64 = 4 };
+/* reduction operations (MPI_SUM is the paper's; the others follow the same schedules) */
+enum { OP_SUM = 0, OP_PROD = 1, OP_MAX = 2, OP_MIN = 3 };
 enum {
     ORACLE_RING = 0,
     ORACLE_LANE = 1,
@@ -110,7 +115,8 @@ int oracle_max_threads(void)
 
 static size_t elem_size(int dtype)
 {
-    return dtype == ORACLE_BF16 ? 2 : 4;
+    if (dtype == ORACLE_BF16 || dtype == ORACLE_F16) return 2;
+    return dtype == ORACLE_F64 ? 8 : 4;
 }
 
 /* ---- bf16 <-> fp32 ------------------------------------------------------ */
@@ -151,6 +157,63 @@ void oracle_bf16_widen(const uint16_t* in, float* out, uint64_t n)
     for (uint64_t i = 0; i < n; ++i) out[i] = bf16_widen(in[i]);
 }
 
+/* ---- IEEE binary16 <-> fp32 --------------------------------------------- */
+
+/* binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits.  Widening is exact. */
+static float f16_widen(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16, e = (h >> 10) & 0x1fu, m = h & 0x3ffu, u;
+    if (e == 0x1fu) {
+        u = sign | 0x7f800000u | (m << 13); /* infinity or NaN */
+    } else if (e != 0) {
+        u = sign | ((e + 112u) << 23) | (m << 13); /* normal: rebias 15 -> 127 */
+    } else {
+        /* zero or subnormal: m * 2^-24, exactly representable in binary32 */
+        float f = (float)m * 5.9604644775390625e-08f; /* 2^-24 */
+        memcpy(&u, &f, 4);
+        u |= sign;
+    }
+    float r;
+    memcpy(&r, &u, 4);
+    return r;
+}
+
+/* Round a binary32 to the nearest binary16, ties to even, from the definition. */
+static uint16_t f16_round(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    uint32_t a = u & 0x7fffffffu, e = a >> 23, m = a & 0x7fffffu;
+    if (a > 0x7f800000u) return (uint16_t)(sign | 0x7e00u); /* NaN */
+    if (e == 0xffu) return (uint16_t)(sign | 0x7c00u);      /* infinity */
+    if (e >= 113u) {
+        /* at least 2^-14: a normal binary16 unless it overflows; drop 13 fraction bits */
+        uint32_t kept = ((e - 112u) << 10) | (m >> 13), lost = m & 0x1fffu;
+        if (lost > 0x1000u || (lost == 0x1000u && (kept & 1u))) kept += 1; /* a carry moves to the exponent */
+        if (kept >= 0x7c00u) kept = 0x7c00u; /* beyond the largest finite value: infinity */
+        return (uint16_t)(sign | kept);
+    }
+    if (e == 0) return sign; /* binary32 subnormals are far below half of 2^-24 */
+    /* below 2^-14: the result is a multiple of 2^-24.  value = (2^23 + m) * 2^(e-150), so in
+     * units of 2^-24 it is (2^23 + m) >> (126 - e). */
+    uint32_t full = 0x800000u | m, shift = 126u - e;
+    if (shift > 24u) return sign; /* less than half a unit */
+    uint32_t kept = full >> shift, lost = full & ((1u << shift) - 1u), half = 1u << (shift - 1u);
+    if (lost > half || (lost == half && (kept & 1u))) kept += 1;
+    return (uint16_t)(sign | kept);
+}
+
+void oracle_f16_round(const float* in, uint16_t* out, uint64_t n)
+{
+    for (uint64_t i = 0; i < n; ++i) out[i] = f16_round(in[i]);
+}
+
+void oracle_f16_widen(const uint16_t* in, float* out, uint64_t n)
+{
+    for (uint64_t i = 0; i < n; ++i) out[i] = f16_widen(in[i]);
+}
+
 /* ---- balanced split ------------------------------------------------------ */
 
 /* part i of m of a length len: offset (relative) and count */
@@ -168,31 +231,112 @@ void oracle_part(uint64_t len, uint64_t m, uint64_t i, uint64_t* off, uint64_t* 
 
 /* ---- the definition ------------------------------------------------------ */
 
-/* out[i] = sum over p of in[p][i].  int32: exact in int64, then wrapped to
- * 32 bits, out is int32[n].  fp32 / bf16: summed in fp64 in ascending rank,
- * out is double[n] (the caller applies the tolerance). */
-int oracle_definition_sum(int dtype, int P, uint64_t n, const void* const* in, void* out)
+/* ---- one binary operation ------------------------------------------------- */
+
+/* Maximum of two floating-point numbers as the schedules use it: a NaN loses against a number,
+ * two NaNs give the first, and +0 is larger than -0.  a is the running value, b the next operand. */
+static double max_f64(double a, double b)
 {
-    if (P < 1 || !in || !out) return 1;
+    if (b != b) return a;
+    if (a != a) return b;
+    if (a < b) return b;
+    if (a == b && a == 0.0) { /* signed zeros: take +0 if either is +0 */
+        uint64_t ua, ub;
+        memcpy(&ua, &a, 8);
+        memcpy(&ub, &b, 8);
+        return (ua >> 63) ? b : a;
+    }
+    return a;
+}
+
+static double min_f64(double a, double b)
+{
+    if (b != b) return a;
+    if (a != a) return b;
+    if (b < a) return b;
+    if (a == b && a == 0.0) { /* take -0 if either is -0 */
+        uint64_t ua;
+        memcpy(&ua, &a, 8);
+        return (ua >> 63) ? a : b;
+    }
+    return a;
+}
+
+/* binary32 operands: max and min are exact, so going through binary64 changes nothing */
+static float op_f32(int op, float a, float b)
+{
+    switch (op) {
+    case OP_SUM: return a + b;
+    case OP_PROD: return a * b;
+    case OP_MAX: return (float)max_f64((double)a, (double)b);
+    default: return (float)min_f64((double)a, (double)b);
+    }
+}
+
+static double op_f64(int op, double a, double b)
+{
+    switch (op) {
+    case OP_SUM: return a + b;
+    case OP_PROD: return a * b;
+    case OP_MAX: return max_f64(a, b);
+    default: return min_f64(a, b);
+    }
+}
+
+/* int32: sum and product wrap (two's complement), max and min compare as signed */
+static uint32_t op_u32(int op, uint32_t a, uint32_t b)
+{
+    switch (op) {
+    case OP_SUM: return a + b;
+    case OP_PROD: return a * b;
+    case OP_MAX: return (int32_t)b > (int32_t)a ? b : a;
+    default: return (int32_t)b < (int32_t)a ? b : a;
+    }
+}
+
+/* ---- the definition ------------------------------------------------------ */
+
+static double as_double(int dtype, const void* p, uint64_t i)
+{
+    switch (dtype) {
+    case ORACLE_F32: return (double)((const float*)p)[i];
+    case ORACLE_BF16: return (double)bf16_widen(((const uint16_t*)p)[i]);
+    case ORACLE_F16: return (double)f16_widen(((const uint16_t*)p)[i]);
+    default: return ((const double*)p)[i];
+    }
+}
+
+/* out[i] = in[0][i] op in[1][i] op ... op in[P-1][i].  int32: exact (sum in int64 then wrapped
+ * to 32 bits, product modulo 2^32), out is int32[n].  Floating types: computed in fp64 in
+ * ascending rank, out is double[n] (the caller applies the tolerance; max and min are exact). */
+int oracle_definition_reduce(int dtype, int op, int P, uint64_t n, const void* const* in, void* out)
+{
+    if (P < 1 || !in || !out || op < OP_SUM || op > OP_MIN) return 1;
     if (dtype == ORACLE_I32) {
         int32_t* o = (int32_t*)out;
         for (uint64_t i = 0; i < n; ++i) {
-            int64_t s = 0;
-            for (int p = 0; p < P; ++p) s += ((const int32_t*)in[p])[i];
-            o[i] = (int32_t)(uint32_t)(uint64_t)s;
+            if (op == OP_SUM) {
+                int64_t s = 0;
+                for (int p = 0; p < P; ++p) s += ((const int32_t*)in[p])[i];
+                o[i] = (int32_t)(uint32_t)(uint64_t)s;
+            } else if (op == OP_PROD) {
+                uint64_t s = 1;
+                for (int p = 0; p < P; ++p) s = (s * (uint64_t)(uint32_t)((const int32_t*)in[p])[i]) & 0xffffffffull;
+                o[i] = (int32_t)(uint32_t)s;
+            } else {
+                int32_t s = ((const int32_t*)in[0])[i];
+                for (int p = 1; p < P; ++p) {
+                    int32_t v = ((const int32_t*)in[p])[i];
+                    if (op == OP_MAX ? v > s : v < s) s = v;
+                }
+                o[i] = s;
+            }
         }
-    } else if (dtype == ORACLE_F32) {
+    } else if (dtype == ORACLE_F32 || dtype == ORACLE_BF16 || dtype == ORACLE_F16 || dtype == ORACLE_F64) {
         double* o = (double*)out;
         for (uint64_t i = 0; i < n; ++i) {
-            double s = 0.0;
-            for (int p = 0; p < P; ++p) s += (double)((const float*)in[p])[i];
-            o[i] = s;
-        }
-    } else if (dtype == ORACLE_BF16) {
-        double* o = (double*)out;
-        for (uint64_t i = 0; i < n; ++i) {
-            double s = 0.0;
-            for (int p = 0; p < P; ++p) s += (double)bf16_widen(((const uint16_t*)in[p])[i]);
+            double s = as_double(dtype, in[0], i);
+            for (int p = 1; p < P; ++p) s = op_f64(op, s, as_double(dtype, in[p], i));
             o[i] = s;
         }
     } else {
@@ -201,30 +345,53 @@ int oracle_definition_sum(int dtype, int P, uint64_t n, const void* const* in, v
     return 0;
 }
 
+int oracle_definition_sum(int dtype, int P, uint64_t n, const void* const* in, void* out)
+{
+    return oracle_definition_reduce(dtype, OP_SUM, P, n, in, out);
+}
+
 /* ---- element-wise k-operand sum, operands in the order given -------------- */
+
+static int g_op = OP_SUM; /* the operation of the run in progress (set by the entry points) */
 
 static void sum_operands(int dtype, void* dst, const void* const* ops, int k, uint64_t cnt)
 {
     int64_t m = (int64_t)cnt;
+    const int op = g_op;
     if (dtype == ORACLE_I32) {
 #pragma omp parallel for num_threads(g_threads) schedule(static)
         for (int64_t i = 0; i < m; ++i) {
             uint32_t s = ((const uint32_t*)ops[0])[i];
-            for (int t = 1; t < k; ++t) s = s + ((const uint32_t*)ops[t])[i];
+            for (int t = 1; t < k; ++t) s = op_u32(op, s, ((const uint32_t*)ops[t])[i]);
             ((uint32_t*)dst)[i] = s;
         }
     } else if (dtype == ORACLE_F32) {
 #pragma omp parallel for num_threads(g_threads) schedule(static)
         for (int64_t i = 0; i < m; ++i) {
             float s = ((const float*)ops[0])[i];
-            for (int t = 1; t < k; ++t) s = s + ((const float*)ops[t])[i];
+            for (int t = 1; t < k; ++t) s = op_f32(op, s, ((const float*)ops[t])[i]);
             ((float*)dst)[i] = s;
+        }
+    } else if (dtype == ORACLE_F64) {
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+        for (int64_t i = 0; i < m; ++i) {
+            double s = ((const double*)ops[0])[i];
+            for (int t = 1; t < k; ++t) s = op_f64(op, s, ((const double*)ops[t])[i]);
+            ((double*)dst)[i] = s;
+        }
+    } else if (dtype == ORACLE_F16) {
+        /* widened exactly, combined in fp32, rounded once when the step stores */
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+        for (int64_t i = 0; i < m; ++i) {
+            float s = f16_widen(((const uint16_t*)ops[0])[i]);
+            for (int t = 1; t < k; ++t) s = op_f32(op, s, f16_widen(((const uint16_t*)ops[t])[i]));
+            ((uint16_t*)dst)[i] = f16_round(s);
         }
     } else {
 #pragma omp parallel for num_threads(g_threads) schedule(static)
         for (int64_t i = 0; i < m; ++i) {
             float s = bf16_widen(((const uint16_t*)ops[0])[i]);
-            for (int t = 1; t < k; ++t) s = s + bf16_widen(((const uint16_t*)ops[t])[i]);
+            for (int t = 1; t < k; ++t) s = op_f32(op, s, bf16_widen(((const uint16_t*)ops[t])[i]));
             ((uint16_t*)dst)[i] = bf16_round(s);
         }
     }
@@ -232,10 +399,20 @@ static void sum_operands(int dtype, void* dst, const void* const* ops, int k, ui
 
 /* dst[o] = ((dst[o] + srcs[0][o]) + srcs[1][o]) + ... for o in every segment:
  * "k incoming segments summed into the owned segment". */
+int oracle_reduce_segments_op(int dtype, int op, void* dst, const void* const* srcs, int k,
+                              const uint64_t* seg_offsets, uint64_t num_segments, uint64_t seg_len);
+
 int oracle_reduce_segments(int dtype, void* dst, const void* const* srcs, int k,
                            const uint64_t* seg_offsets, uint64_t num_segments, uint64_t seg_len)
 {
-    if (k < 0 || k > 4096) return 1;
+    return oracle_reduce_segments_op(dtype, OP_SUM, dst, srcs, k, seg_offsets, num_segments, seg_len);
+}
+
+int oracle_reduce_segments_op(int dtype, int op, void* dst, const void* const* srcs, int k,
+                              const uint64_t* seg_offsets, uint64_t num_segments, uint64_t seg_len)
+{
+    if (k < 0 || k > 4096 || op < OP_SUM || op > OP_MIN) return 1;
+    g_op = op;
     size_t e = elem_size(dtype);
     const void* ops[4097];
     for (uint64_t s = 0; s < num_segments; ++s) {
@@ -752,9 +929,21 @@ static int run_shared_lane(world_t* w, int N, int G, int Q, int max_rounds)
 static int run_world(int shared, int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
                      int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len);
 
+/* Same as oracle_allreduce / oracle_allreduce_shared with an operation other than the sum. */
+int oracle_allreduce_op(int shared, int op, int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
+                        int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
+{
+    if (op < OP_SUM || op > OP_MIN) return 2;
+    g_op = op;
+    int rc = run_world(shared, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
+    g_op = OP_SUM;
+    return rc;
+}
+
 int oracle_allreduce(int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
                      int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
 {
+    g_op = OP_SUM;
     return run_world(0, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
 }
 
@@ -765,6 +954,7 @@ int oracle_allreduce(int algo, int N, int G, int Q, uint64_t n, int dtype, void*
 int oracle_allreduce_shared(int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
                             int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
 {
+    g_op = OP_SUM;
     return run_world(1, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
 }
 
@@ -772,7 +962,7 @@ static int run_world(int shared, int algo, int N, int G, int Q, uint64_t n, int 
                      int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
 {
     if (N < 1 || G < 1 || Q < 1 || !bufs) return 1;
-    if (dtype != ORACLE_I32 && dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 2;
+    if (dtype < ORACLE_I32 || dtype > ORACLE_F64) return 2;
     world_t w;
     memset(&w, 0, sizeof w);
     w.P = N * G * Q;

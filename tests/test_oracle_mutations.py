@@ -47,18 +47,33 @@ MUTATIONS = [
     ("shared_lane_gather_skips_last_gpu", "for (int to = 0; to < G; ++to)\n                        if (to != g) post(w, proc_rank(G, Q, node, g, q), proc_rank(G, Q, node, to, q), so + co, cc);",
      "for (int to = 0; to < G - 1; ++to)\n                        if (to != g) post(w, proc_rank(G, Q, node, g, q), proc_rank(G, Q, node, to, q), so + co, cc);"),
     ("shared_lane_piece_of_wrong_member", "part(cc, (uint64_t)N, (uint64_t)(half == 0 ? to : from), &po, &pc);", "part(cc, (uint64_t)N, (uint64_t)(half == 0 ? from : to), &po, &pc);"),
+    ("f16_ties_away", "if (lost > 0x1000u || (lost == 0x1000u && (kept & 1u))) kept += 1; /* a carry", "if (lost >= 0x1000u) kept += 1; /* a carry"),
+    ("f16_overflow_saturates", "if (kept >= 0x7c00u) kept = 0x7c00u;", "if (kept >= 0x7c00u) kept = 0x7bffu;"),
+    ("f16_subnormal_shift_off_by_one", "uint32_t full = 0x800000u | m, shift = 126u - e;", "uint32_t full = 0x800000u | m, shift = 125u - e;"),
+    ("f16_subnormal_truncates", "if (lost > half || (lost == half && (kept & 1u))) kept += 1;", "if (lost > half + half) kept += 1;"),
+    ("f16_widen_wrong_bias", "u = sign | ((e + 112u) << 23) | (m << 13); /* normal", "u = sign | ((e + 111u) << 23) | (m << 13); /* normal"),
+    ("f16_rounds_every_add", "for (int t = 1; t < k; ++t) s = op_f32(op, s, f16_widen(((const uint16_t*)ops[t])[i]));",
+     "for (int t = 1; t < k; ++t) s = f16_widen(f16_round(op_f32(op, s, f16_widen(((const uint16_t*)ops[t])[i]))));"),
+    ("max_nan_wins", "if (b != b) return a;\n    if (a != a) return b;\n    if (a < b) return b;", "if (b != b) return b;\n    if (a != a) return a;\n    if (a < b) return b;"),
+    ("max_ignores_signed_zero", "return (ua >> 63) ? b : a;", "return a;"),
+    ("min_is_max", "if (b < a) return b;\n    if (a == b && a == 0.0) { /* take -0", "if (a < b) return b;\n    if (a == b && a == 0.0) { /* take -0"),
+    ("int_max_compares_unsigned", "case OP_MAX: return (int32_t)b > (int32_t)a ? b : a;", "case OP_MAX: return b > a ? b : a;"),
+    ("int_prod_not_wrapping", "case OP_PROD: return a * b;\n    case OP_MAX: return (int32_t)b > (int32_t)a ? b : a;\n    default: return (int32_t)b < (int32_t)a ? b : a;",
+     "case OP_PROD: { int64_t z = (int64_t)(int32_t)a * (int32_t)b; return (uint32_t)(z > 2147483647 ? 2147483647 : z < -2147483648LL ? -2147483648LL : z); }\n    case OP_MAX: return (int32_t)b > (int32_t)a ? b : a;\n    default: return (int32_t)b < (int32_t)a ? b : a;"),
+    ("f64_in_single", "double s = ((const double*)ops[0])[i];\n            for (int t = 1; t < k; ++t) s = op_f64(op, s, ((const double*)ops[t])[i]);",
+     "float s = (float)((const double*)ops[0])[i];\n            for (int t = 1; t < k; ++t) s = op_f32(op, s, (float)((const double*)ops[t])[i]);"),
     ("rank_numbering_gpu_minor", "return node * c->G * c->Q + local;", "return local * c->N + node;"),
     ("bf16_truncates", "if (lost > 0x8000u)\n        kept += 1;", "if (lost > 0xffffu)\n        kept += 1;"),
     ("bf16_ties_away", "else if (lost == 0x8000u && (kept & 1u))", "else if (lost == 0x8000u)"),
-    ("bf16_rounds_every_add", "for (int t = 1; t < k; ++t) s = s + bf16_widen(((const uint16_t*)ops[t])[i]);",
-     "for (int t = 1; t < k; ++t) s = bf16_widen(bf16_round(s + bf16_widen(((const uint16_t*)ops[t])[i])));"),
-    ("f32_accumulates_in_double", "float s = ((const float*)ops[0])[i];\n            for (int t = 1; t < k; ++t) s = s + ((const float*)ops[t])[i];",
-     "double s = ((const float*)ops[0])[i];\n            for (int t = 1; t < k; ++t) s = s + ((const float*)ops[t])[i];"),
-    ("int_saturates", "for (int t = 1; t < k; ++t) s = s + ((const uint32_t*)ops[t])[i];",
-     "for (int t = 1; t < k; ++t) { int64_t z = (int64_t)(int32_t)s + ((const int32_t*)ops[t])[i]; s = (uint32_t)(z > 2147483647 ? 2147483647 : z < -2147483648LL ? -2147483648LL : z); }"),
+    ("bf16_rounds_every_add", "for (int t = 1; t < k; ++t) s = op_f32(op, s, bf16_widen(((const uint16_t*)ops[t])[i]));",
+     "for (int t = 1; t < k; ++t) s = bf16_widen(bf16_round(op_f32(op, s, bf16_widen(((const uint16_t*)ops[t])[i]))));"),
+    ("f32_accumulates_in_double", "float s = ((const float*)ops[0])[i];\n            for (int t = 1; t < k; ++t) s = op_f32(op, s, ((const float*)ops[t])[i]);",
+     "double s = ((const float*)ops[0])[i];\n            for (int t = 1; t < k; ++t) s = op_f64(op, s, ((const float*)ops[t])[i]);"),
+    ("int_saturates", "case OP_SUM: return a + b;\n    case OP_PROD: return a * b;\n    case OP_MAX: return (int32_t)b > (int32_t)a ? b : a;",
+     "case OP_SUM: { int64_t z = (int64_t)(int32_t)a + (int32_t)b; return (uint32_t)(z > 2147483647 ? 2147483647 : z < -2147483648LL ? -2147483648LL : z); }\n    case OP_PROD: return a * b;\n    case OP_MAX: return (int32_t)b > (int32_t)a ? b : a;"),
     ("definition_skips_rank0", "for (int p = 0; p < P; ++p) s += ((const int32_t*)in[p])[i];", "for (int p = 1; p < P; ++p) s += ((const int32_t*)in[p])[i];"),
-    ("definition_float_in_single", "double s = 0.0;\n            for (int p = 0; p < P; ++p) s += (double)((const float*)in[p])[i];",
-     "float s = 0.0f;\n            for (int p = 0; p < P; ++p) s += ((const float*)in[p])[i];"),
+    ("definition_float_in_single", "double s = as_double(dtype, in[0], i);\n            for (int p = 1; p < P; ++p) s = op_f64(op, s, as_double(dtype, in[p], i));",
+     "float s = (float)as_double(dtype, in[0], i);\n            for (int p = 1; p < P; ++p) s = (float)op_f64(op, s, as_double(dtype, in[p], i));"),
     ("reduce_segments_ignores_dst", "sum_operands(dtype, (char*)dst + o * e, ops, k + 1, seg_len);", "sum_operands(dtype, (char*)dst + o * e, ops + (k > 0), k > 0 ? k : 1, seg_len);"),
     ("overwrite_wrong_offset", "memcpy(mem(w, at) + l->off * w->esz, l->data, l->cnt * w->esz);", "memcpy(mem(w, at) + (l->off ? l->off - 1 : 0) * w->esz, l->data, l->cnt * w->esz);"),
     ("shared_buffer_of_wrong_gpu", "return (char*)w->buf[rank / w->share];", "return (char*)w->buf[w->share > 1 ? rank % (w->P / w->share) : rank];"),
@@ -89,6 +104,13 @@ def pin_calls(o):
         lambda: pins.test_lane_ring_is_the_flat_ring_when_every_node_has_one_rank(o),
         lambda: pins.test_lane_ring_order_node_sums_walk_the_ring(o),
         lambda: pins.test_lane_ring_messages_and_boundaries(o),
+        lambda: pins.test_f16_round_matches_numpy(o),
+        lambda: pins.test_f16_widen_all_patterns(o),
+        lambda: pins.test_operations_closed_forms(o),
+        lambda: pins.test_definition_of_operations_vs_python(o),
+        lambda: pins.test_f16_rounds_once_per_reduce_step(o),
+        lambda: pins.test_schedules_with_operations_and_wide_types(o, "ring"),
+        lambda: pins.test_schedules_with_operations_and_wide_types(o, "lane_multiproc"),
         lambda: pins.test_shared_model_with_one_process_per_gpu_is_the_private_model(o),
         lambda: pins.test_shared_standard_messages_scale_with_processes_per_gpu(o),
         lambda: pins.test_shared_lane_stages_and_order(o),

@@ -95,6 +95,36 @@ def test_bf16_widen_all_patterns(oracle):
     assert np.array_equal(got, h.astype(np.uint32) << 16)
 
 
+def test_f16_round_matches_numpy(oracle):
+    rng = np.random.default_rng(9)
+    bits = rng.integers(0, 1 << 32, size=600000, dtype=np.uint64).astype(np.uint32)
+    # dense coverage of the binary16 range: normals, subnormals (below 2^-14), ties, overflow
+    mags = np.exp2(rng.uniform(-27, 17, size=400000)).astype(np.float32) * rng.choice([-1.0, 1.0], size=400000).astype(np.float32)
+    ties = (np.arange(0, 1 << 16, dtype=np.uint32).view(np.uint32))
+    halves = ties.astype(np.uint16).view(np.float16).astype(np.float32)
+    halves = halves[np.isfinite(halves)]
+    with np.errstate(over="ignore"):
+        mid = (halves + np.nextafter(halves.astype(np.float16), np.float16(np.inf)).astype(np.float32)) / np.float32(2)  # exact midpoints
+    special = np.array([65504.0, 65519.99, 65520.0, 65536.0, 1e9, 2.0 ** -24, 2.0 ** -25, 2.0 ** -25 * 1.0000001, 2.0 ** -26,
+                        2.0 ** -14, 2.0 ** -14 * (1 - 2.0 ** -12), 0.0, -0.0, np.inf, -np.inf], dtype=np.float32)
+    x = np.concatenate([bits.view(np.float32), mags, mid[np.isfinite(mid)], special])
+    got = oracle.f16_round(x)
+    with np.errstate(over="ignore"):
+        ref = x.astype(np.float16).view(np.uint16)
+    nan = np.isnan(x)
+    assert np.array_equal(got[~nan], ref[~nan])
+    assert np.all(np.isnan(got[nan].view(np.float16)))
+
+
+def test_f16_widen_all_patterns(oracle):
+    h = np.arange(1 << 16, dtype=np.uint16)
+    got = oracle.f16_widen(h)
+    ref = h.view(np.float16).astype(np.float32)
+    ok = ~np.isnan(ref)
+    assert np.array_equal(got.view(np.uint32)[ok], ref.view(np.uint32)[ok])
+    assert np.all(np.isnan(got[~ok]))
+
+
 # --------------------------------------------------------------------------- the definition
 
 def test_definition_int32_vs_python_integers_with_wrap(oracle):
@@ -115,6 +145,100 @@ def test_definition_float_vs_fsum(oracle):
     w = bf16_bits_to_f64(h)
     ref = np.array([math.fsum(w[:, i]) for i in range(w.shape[1])])
     assert np.allclose(got, ref, rtol=0, atol=1e-13)
+
+
+def py_int_reduce(x, op):
+    out = []
+    for i in range(x.shape[1]):
+        col = [int(v) for v in x[:, i]]
+        if op == "sum":
+            s = sum(col)
+        elif op == "prod":
+            s = 1
+            for v in col:
+                s *= v
+        else:
+            s = max(col) if op == "max" else min(col)
+        s &= 0xFFFFFFFF
+        out.append(s - (1 << 32) if s >= (1 << 31) else s)
+    return np.array(out, dtype=np.int32)
+
+
+def test_definition_of_operations_vs_python(oracle):
+    rng = np.random.default_rng(21)
+    x = rng.integers(-(1 << 31), 1 << 31, size=(6, 40), dtype=np.int64).astype(np.int32)
+    x[:, :10] = rng.integers(-9, 10, size=(6, 10))
+    for op in ("sum", "prod", "max", "min"):
+        assert np.array_equal(oracle.definition_reduce(x, op), py_int_reduce(x, op)), op
+    f = synth.make_inputs(7, 33, "normal")
+    assert np.allclose(oracle.definition_reduce(f, "prod"), [math.prod(float(v) for v in f[:, i]) for i in range(33)], rtol=1e-14)
+    assert np.array_equal(oracle.definition_reduce(f, "max"), f.astype(np.float64).max(axis=0))
+    assert np.array_equal(oracle.definition_reduce(f, "min"), f.astype(np.float64).min(axis=0))
+    d = np.random.default_rng(2).standard_normal((5, 20))
+    assert np.allclose(oracle.definition_reduce(d, "sum"), [math.fsum(d[:, i]) for i in range(20)], rtol=0, atol=1e-15 * 5)
+    h = np.random.default_rng(3).standard_normal((5, 20)).astype(np.float16)
+    assert np.allclose(oracle.definition_reduce(h, "sum"), [math.fsum(float(v) for v in h[:, i]) for i in range(20)], rtol=0, atol=1e-14)
+
+
+def test_operations_closed_forms(oracle):
+    nan, pz, nz = np.float32(np.nan), np.float32(0.0), np.float32(-0.0)
+    # columns: (+0,-0), (-0,+0), (nan,1), (1,nan), (nan,nan), (2,3), (-inf, 5)
+    a = np.array([pz, nz, nan, 1.0, nan, 2.0, -np.inf], dtype=np.float32)
+    b = np.array([nz, pz, 1.0, nan, nan, 3.0, 5.0], dtype=np.float32)
+    x = np.stack([a, b])
+    for algo in ("ring", "lane"):
+        mx = oracle.allreduce(algo, 2, 1, 1, x, op="max")[0]
+        mn = oracle.allreduce(algo, 2, 1, 1, x, op="min")[0]
+        assert [int(v) for v in mx[:2].view(np.uint32)] == [0x00000000, 0x00000000]      # +0 is the larger zero
+        assert [int(v) for v in mn[:2].view(np.uint32)] == [0x80000000, 0x80000000]      # -0 the smaller
+        assert mx[2] == 1.0 and mx[3] == 1.0 and mn[2] == 1.0 and mn[3] == 1.0          # a NaN loses against a number
+        assert np.isnan(mx[4]) and np.isnan(mn[4])
+        assert (mx[5], mn[5], mx[6], mn[6]) == (3.0, 2.0, 5.0, -np.inf)
+    i = np.array([[-5, 7, -2147483648, 65536], [3, -7, 2147483647, 65536]], dtype=np.int32)
+    assert list(oracle.allreduce("lane", 1, 2, 1, i, op="max")[0]) == [3, 7, 2147483647, 65536]
+    assert list(oracle.allreduce("lane", 1, 2, 1, i, op="min")[0]) == [-5, -7, -2147483648, 65536]
+    assert list(oracle.allreduce("lane", 1, 2, 1, i, op="prod")[0]) == [-15, -49, -2147483648, 0]  # 2^32 wraps to 0
+
+
+def test_f16_rounds_once_per_reduce_step(oracle):
+    # binary16 has 11 significant bits: ulp(1) = 2^-10, so 1 + 2^-11 is an exact tie
+    vals3 = np.array([1.0, 2.0 ** -11, 2.0 ** -11], dtype=np.float16)
+    x3 = np.repeat(vals3[:, None], 3, axis=1)
+    one = oracle.allreduce("lane", 1, 3, 1, x3)          # one 3-way step: fp32 sum 1 + 2^-10, exact
+    assert np.all(one.view(np.uint16) == 0x3C01)
+    ring = oracle.allreduce("ring", 3, 1, 1, x3)          # rounds after every hop
+    # chunk 0: rnd(rnd(1 + 2^-11) + 2^-11) = 1; chunk 1: rnd(rnd(2^-11 + 2^-11) + 1) = 1 + 2^-10; chunk 2: like chunk 0
+    assert [int(v) for v in ring[0].view(np.uint16)] == [0x3C00, 0x3C01, 0x3C00]
+
+
+@pytest.mark.parametrize("algo", ["ring", "lane_multiproc"])
+def test_schedules_with_operations_and_wide_types(oracle, algo):
+    rng = np.random.default_rng(33)
+    for (N, G, Q) in [(2, 2, 2), (3, 1, 2), (1, 3, 1), (2, 3, 1)]:
+        P = N * G * Q
+        for n in (1, 7, 24, 40):
+            xi = rng.integers(-(1 << 31), 1 << 31, size=(P, n), dtype=np.int64).astype(np.int32)
+            xi[:, : n // 2] = rng.integers(-6, 7, size=(P, n // 2))
+            for op in ("prod", "max", "min"):
+                out = oracle.allreduce(algo, N, G, Q, xi, op=op)
+                assert np.array_equal(out, np.broadcast_to(py_int_reduce(xi, op), out.shape)), (algo, op, N, G, Q, n)
+            f = synth.make_inputs(P, n, "uniform_pm1", seed=n) + np.float32(1.5)   # in [0.5, 2.5): products stay in range
+            for op in ("max", "min"):
+                out = oracle.allreduce(algo, N, G, Q, f, op=op)
+                assert np.array_equal(out[P - 1].astype(np.float64), oracle.definition_reduce(f, op))
+            pr = oracle.allreduce(algo, N, G, Q, f, op="prod")[0].astype(np.float64)
+            assert np.allclose(pr, oracle.definition_reduce(f, "prod"), rtol=1e-5, atol=0)
+            d = rng.standard_normal((P, n))
+            got = oracle.allreduce(algo, N, G, Q, d)
+            exact = np.array([math.fsum(d[:, i]) for i in range(n)])
+            assert np.all(np.abs(got[0] - exact) <= 1e-14 * np.abs(d).sum(axis=0))
+            h = rng.standard_normal((P, n)).astype(np.float16)
+            goth = oracle.allreduce(algo, N, G, Q, h)
+            assert all(np.array_equal(goth[0].view(np.uint16), goth[r].view(np.uint16)) for r in range(P))
+            if algo != "ring":  # two roundings of 2^-11 each
+                hx = h.astype(np.float64)
+                exact = np.array([math.fsum(hx[:, i]) for i in range(n)])
+                assert np.all(np.abs(goth[0].astype(np.float64) - exact) <= 2e-3 * np.abs(hx).sum(axis=0))
 
 
 # --------------------------------------------------------------------------- brute force
