@@ -36,7 +36,7 @@ typedef enum {
     LA_OK = 0,
     LA_ERR_INVALID_ARG = 1,   /* null pointer, dimension <= 0, n == 0, mismatch with the schedule,
                                  misaligned or overlapping buffers */
-    LA_ERR_UNSUPPORTED = 2,   /* unknown dtype / algorithm / flag, op other than SUM */
+    LA_ERR_UNSUPPORTED = 2,   /* unknown dtype / algorithm / flag / operation, or a combination that is not built */
     LA_ERR_OUT_OF_MEMORY = 3, /* host or device allocation failed */
     LA_ERR_DEVICE = 4         /* a HIP call failed (no GPU, launch error, ...) */
 } la_status_t;
@@ -49,8 +49,13 @@ typedef enum {
                                   is split again into one sub-chunk per process of the GPU */
 } la_algo_t;
 
-typedef enum { LA_I32 = 0, LA_F32 = 1, LA_BF16 = 2 } la_dtype_t;
-typedef enum { LA_SUM = 0 } la_op_t; /* MPI_SUM, the only operation the paper uses */
+/* Element types.  The paper reduces 32-bit floats; the others follow the same schedules.  The
+ * 16-bit types are widened exactly to fp32, combined in fp32 and rounded to nearest-even once
+ * per reduce step. */
+typedef enum { LA_I32 = 0, LA_F32 = 1, LA_BF16 = 2, LA_F16 = 3, LA_F64 = 4 } la_dtype_t;
+/* Operations.  LA_SUM is MPI_SUM, the one the paper uses.  Floating-point maximum / minimum: a
+ * NaN loses against a number, +0 is larger than -0; int32 sum and product wrap. */
+typedef enum { LA_SUM = 0, LA_PROD = 1, LA_MAX = 2, LA_MIN = 3 } la_op_t;
 
 /* Flags of la_schedule_build_ex (bit set). */
 enum {
@@ -204,13 +209,13 @@ const char* la_last_error(void);
 /* Launch-shape knobs for measurements (process-wide, read when a schedule is bound or a
  * la_reduce_segments call is made).  By default every step picks its own shape from its fan-in,
  * fan-out and segment length; a knob set to a fixed value overrides that choice for all steps.
- *   "unroll"      16-byte vectors per lane and operand: 1, 2, 4, 8; 0 = automatic
+ *   "unroll"      16-byte vectors per lane and operand: 1, 2, 4; 0 = automatic
  *   "cache_policy" 0..7: which of {loads of pure sources, loads of sources the segment also
  *                 overwrites, stores} are plain (P), non-temporal (N) or scope-1 (S):
  *                 0 PPP, 1 NPP, 2 NPS, 3 NNN, 4 PPN, 5 NNP, 6 NNS, 7 PPS; -1 = automatic.
  *                 A three-digit value abc sets policy a for pure reduce steps, b for reduce
  *                 steps with several destinations and c for copy / broadcast steps.
- *   "block"       lanes per workgroup: 256, 512, 1024; 0 = automatic
+ *   "block"       lanes per workgroup: 256, 1024; 0 = automatic
  *   "graph"       1: la_allreduce_emulated replays the schedule as one HIP graph of kernel nodes,
  *                 0: it launches step by step, -1 (default): graph for schedules of 8+ launches
  * la_tuning_set returns LA_ERR_INVALID_ARG for an unknown key or value; la_tuning_get returns

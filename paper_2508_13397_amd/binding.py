@@ -14,8 +14,9 @@ LIB_PATH = os.path.join(_HERE, "liblaneallreduce.so")
 
 LA_OK, LA_ERR_INVALID_ARG, LA_ERR_UNSUPPORTED, LA_ERR_OUT_OF_MEMORY, LA_ERR_DEVICE = range(5)
 LA_ALGO_RING, LA_ALGO_LANE, LA_ALGO_LANE_MULTIPROC = 0, 1, 2
-LA_I32, LA_F32, LA_BF16 = 0, 1, 2
-LA_SUM = 0
+LA_I32, LA_F32, LA_BF16, LA_F16, LA_F64 = 0, 1, 2, 3, 4
+LA_SUM, LA_PROD, LA_MAX, LA_MIN = 0, 1, 2, 3
+OPS = {"sum": LA_SUM, "prod": LA_PROD, "max": LA_MAX, "min": LA_MIN}
 LA_SCHED_DEFAULT, LA_SCHED_P2P_GATHER, LA_SCHED_STAGED, LA_SCHED_INNER_RING = 0, 1, 2, 4
 LA_SCHED_SHARED_BUFFERS = 8
 LA_STEP_REDUCE, LA_STEP_COPY = 0, 1
@@ -24,8 +25,8 @@ LA_STAGE_RING_RS, LA_STAGE_RING_AG, LA_STAGE_PACK = 10, 11, 20
 LA_STAGE_S2_RING_RS, LA_STAGE_S2_RING_AG = 6, 7
 
 ALGOS = {"ring": LA_ALGO_RING, "lane": LA_ALGO_LANE, "lane_multiproc": LA_ALGO_LANE_MULTIPROC}
-DTYPES = {"int32": LA_I32, "float32": LA_F32, "bfloat16": LA_BF16}
-ELEM_SIZE = {LA_I32: 4, LA_F32: 4, LA_BF16: 2}
+DTYPES = {"int32": LA_I32, "float32": LA_F32, "bfloat16": LA_BF16, "float16": LA_F16, "float64": LA_F64}
+ELEM_SIZE = {LA_I32: 4, LA_F32: 4, LA_BF16: 2, LA_F16: 2, LA_F64: 8}
 STAGE_NAMES = {1: "S1", 2: "S2a", 3: "S2b", 4: "S3", 5: "S2", 6: "S2-ring-RS", 7: "S2-ring-AG", 10: "ring-RS",
                11: "ring-AG", 20: "pack"}
 

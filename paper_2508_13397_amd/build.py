@@ -4,21 +4,25 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblaneallreduce.so")
-SOURCES = ["kernels.hip", "runtime.cpp", "schedule.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
-    "-Wall", "-Wextra", "-Wno-unused-parameter",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
+    "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wno-unused-const-variable",
     # keep hipcc from forming packed fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
+# (source, object name, extra flags): kernels.hip is built once per element type
+UNITS = [("kernels.hip", f"kernels_dtype{d}.o", [f"-DLA_KERNEL_DTYPE={d}"]) for d in range(5)] + [
+    ("dispatch.cpp", "dispatch.o", []), ("runtime.cpp", "runtime.o", []), ("schedule.cpp", "schedule.o", [])]
 
 
 def stale() -> bool:
@@ -29,16 +33,28 @@ def stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
+def build(force: bool = True, verbose: bool = False, jobs: int = 8) -> str:
     if not force and not stale():
         return LIB
-    cmd = [HIPCC] + FLAGS + ["-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    os.makedirs(OBJ, exist_ok=True)
+
+    def compile_unit(unit):
+        src, obj, extra = unit
+        cmd = [HIPCC] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", os.path.join(OBJ, obj)]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return os.path.join(OBJ, obj)
+
+    with ThreadPoolExecutor(max_workers=max(1, min(jobs, os.cpu_count() or 1, 16))) as ex:
+        objs = list(ex.map(compile_unit, UNITS))
+    link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return LIB
 
 
 if __name__ == "__main__":
-    build(force=True, verbose=True)
+    build(force=True, verbose="-q" not in sys.argv)
     print(LIB)

@@ -23,7 +23,68 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KBATCH = 4; // operands whose loads are issued together
 
+// ---- binary operations -----------------------------------------------------------------------
+// The paper reduces with MPI_SUM; product, maximum and minimum run on the same schedules.  The
+// operation is a launch argument (uniform across the grid): the kernels are memory-bound, a
+// scalar branch per combine costs nothing measurable.
+
+// Maximum / minimum of two floating-point numbers: a NaN loses against a number, two NaNs give
+// the running value, and +0 is larger than -0.  a is the running value, b the next operand.
+template <typename F>
+__device__ inline bool sign_of(F x)
+{
+    if constexpr (sizeof(F) == 4)
+        return (__float_as_uint((float)x) >> 31) != 0;
+    else
+        return (__double_as_longlong((double)x) < 0);
+}
+
+template <typename F>
+__device__ inline F fmax_ordered(F a, F b)
+{
+    if (b != b) return a;
+    if (a != a) return b;
+    if (a < b) return b;
+    if (a == b && a == F(0)) return sign_of(a) ? b : a;
+    return a;
+}
+
+template <typename F>
+__device__ inline F fmin_ordered(F a, F b)
+{
+    if (b != b) return a;
+    if (a != a) return b;
+    if (b < a) return b;
+    if (a == b && a == F(0)) return sign_of(a) ? a : b;
+    return a;
+}
+
+template <typename F>
+__device__ inline F combine_fp(uint32_t op, F a, F b)
+{
+    switch (op) {
+    case LA_SUM: return a + b;
+    case LA_PROD: return a * b;
+    case LA_MAX: return fmax_ordered(a, b);
+    default: return fmin_ordered(a, b);
+    }
+}
+
+// int32: sum and product wrap (two's complement), maximum and minimum compare as signed
+__device__ inline uint32_t combine_u32(uint32_t op, uint32_t a, uint32_t b)
+{
+    switch (op) {
+    case LA_SUM: return a + b;
+    case LA_PROD: return a * b;
+    case LA_MAX: return (int32_t)b > (int32_t)a ? b : a;
+    default: return (int32_t)b < (int32_t)a ? b : a;
+    }
+}
+
 // ---- element types ---------------------------------------------------------------------------
+// Each type says how a 16-byte vector is widened into accumulators, combined with the next
+// operand's vector, and narrowed for the store; and the same for a single element (heads, tails
+// and operands that are not congruent modulo 16 bytes).
 
 struct I32 {
     using elem = uint32_t;
@@ -32,17 +93,17 @@ struct I32 {
         uint32_t v[4];
     };
     __device__ static Acc widen(u32x4 x) { return Acc{{x.x, x.y, x.z, x.w}}; }
-    __device__ static void add(Acc& a, u32x4 x)
+    __device__ static void add(Acc& a, u32x4 x, uint32_t op)
     {
-        a.v[0] += x.x; // wraps (two's complement)
-        a.v[1] += x.y;
-        a.v[2] += x.z;
-        a.v[3] += x.w;
+        a.v[0] = combine_u32(op, a.v[0], x.x);
+        a.v[1] = combine_u32(op, a.v[1], x.y);
+        a.v[2] = combine_u32(op, a.v[2], x.z);
+        a.v[3] = combine_u32(op, a.v[3], x.w);
     }
     __device__ static u32x4 narrow(const Acc& a) { return u32x4{a.v[0], a.v[1], a.v[2], a.v[3]}; }
     using sacc = uint32_t;
     __device__ static sacc swiden(elem x) { return x; }
-    __device__ static sacc sadd(sacc a, elem x) { return a + x; }
+    __device__ static sacc sadd(sacc a, elem x, uint32_t op) { return combine_u32(op, a, x); }
     __device__ static elem snarrow(sacc a) { return a; }
 };
 
@@ -56,12 +117,12 @@ struct F32 {
     {
         return Acc{{__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)}};
     }
-    __device__ static void add(Acc& a, u32x4 x)
+    __device__ static void add(Acc& a, u32x4 x, uint32_t op)
     {
-        a.v[0] = a.v[0] + __uint_as_float(x.x);
-        a.v[1] = a.v[1] + __uint_as_float(x.y);
-        a.v[2] = a.v[2] + __uint_as_float(x.z);
-        a.v[3] = a.v[3] + __uint_as_float(x.w);
+        a.v[0] = combine_fp(op, a.v[0], __uint_as_float(x.x));
+        a.v[1] = combine_fp(op, a.v[1], __uint_as_float(x.y));
+        a.v[2] = combine_fp(op, a.v[2], __uint_as_float(x.z));
+        a.v[3] = combine_fp(op, a.v[3], __uint_as_float(x.w));
     }
     __device__ static u32x4 narrow(const Acc& a)
     {
@@ -70,55 +131,94 @@ struct F32 {
     }
     using sacc = float;
     __device__ static sacc swiden(elem x) { return x; }
-    __device__ static sacc sadd(sacc a, elem x) { return a + x; }
+    __device__ static sacc sadd(sacc a, elem x, uint32_t op) { return combine_fp(op, a, x); }
     __device__ static elem snarrow(sacc a) { return a; }
 };
 
-// bf16 is the upper half of a binary32.  Operands are widened exactly, summed in fp32 and
-// rounded to nearest, ties to even, once when the step stores its result.
-__device__ inline uint32_t f32_to_bf16_bits(float f)
-{
-    const uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u; // NaN: keep it quiet
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
+struct F64 {
+    using elem = double;
+    static constexpr int VEC = 2;
+    struct Acc {
+        double v[2];
+    };
+    __device__ static double join(uint32_t lo, uint32_t hi)
+    {
+        return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+    }
+    __device__ static Acc widen(u32x4 x) { return Acc{{join(x.x, x.y), join(x.z, x.w)}}; }
+    __device__ static void add(Acc& a, u32x4 x, uint32_t op)
+    {
+        a.v[0] = combine_fp(op, a.v[0], join(x.x, x.y));
+        a.v[1] = combine_fp(op, a.v[1], join(x.z, x.w));
+    }
+    __device__ static u32x4 narrow(const Acc& a)
+    {
+        const uint64_t p = (uint64_t)__double_as_longlong(a.v[0]), q = (uint64_t)__double_as_longlong(a.v[1]);
+        return u32x4{(uint32_t)p, (uint32_t)(p >> 32), (uint32_t)q, (uint32_t)(q >> 32)};
+    }
+    using sacc = double;
+    __device__ static sacc swiden(elem x) { return x; }
+    __device__ static sacc sadd(sacc a, elem x, uint32_t op) { return combine_fp(op, a, x); }
+    __device__ static elem snarrow(sacc a) { return a; }
+};
 
-struct BF16 {
+// 16-bit floating types: operands are widened exactly to fp32, combined in fp32 and rounded to
+// nearest, ties to even, once when the step stores its result.
+template <typename H>
+struct Half16 {
     using elem = uint16_t;
     static constexpr int VEC = 8;
     struct Acc {
         float v[8];
     };
-    __device__ static float lo(uint32_t w) { return __uint_as_float(w << 16); }
-    __device__ static float hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+    __device__ static float lo(uint32_t w) { return H::widen((uint16_t)(w & 0xffffu)); }
+    __device__ static float hi(uint32_t w) { return H::widen((uint16_t)(w >> 16)); }
     __device__ static Acc widen(u32x4 x)
     {
         return Acc{{lo(x.x), hi(x.x), lo(x.y), hi(x.y), lo(x.z), hi(x.z), lo(x.w), hi(x.w)}};
     }
-    __device__ static void add(Acc& a, u32x4 x)
+    __device__ static void add(Acc& a, u32x4 x, uint32_t op)
     {
-        a.v[0] = a.v[0] + lo(x.x);
-        a.v[1] = a.v[1] + hi(x.x);
-        a.v[2] = a.v[2] + lo(x.y);
-        a.v[3] = a.v[3] + hi(x.y);
-        a.v[4] = a.v[4] + lo(x.z);
-        a.v[5] = a.v[5] + hi(x.z);
-        a.v[6] = a.v[6] + lo(x.w);
-        a.v[7] = a.v[7] + hi(x.w);
+        a.v[0] = combine_fp(op, a.v[0], lo(x.x));
+        a.v[1] = combine_fp(op, a.v[1], hi(x.x));
+        a.v[2] = combine_fp(op, a.v[2], lo(x.y));
+        a.v[3] = combine_fp(op, a.v[3], hi(x.y));
+        a.v[4] = combine_fp(op, a.v[4], lo(x.z));
+        a.v[5] = combine_fp(op, a.v[5], hi(x.z));
+        a.v[6] = combine_fp(op, a.v[6], lo(x.w));
+        a.v[7] = combine_fp(op, a.v[7], hi(x.w));
     }
-    __device__ static uint32_t pack(float l, float h)
-    {
-        return f32_to_bf16_bits(l) | (f32_to_bf16_bits(h) << 16);
-    }
+    __device__ static uint32_t pack(float l, float h) { return (uint32_t)H::narrow(l) | ((uint32_t)H::narrow(h) << 16); }
     __device__ static u32x4 narrow(const Acc& a)
     {
         return u32x4{pack(a.v[0], a.v[1]), pack(a.v[2], a.v[3]), pack(a.v[4], a.v[5]), pack(a.v[6], a.v[7])};
     }
     using sacc = float;
-    __device__ static sacc swiden(elem x) { return __uint_as_float((uint32_t)x << 16); }
-    __device__ static sacc sadd(sacc a, elem x) { return a + __uint_as_float((uint32_t)x << 16); }
-    __device__ static elem snarrow(sacc a) { return (elem)f32_to_bf16_bits(a); }
+    __device__ static sacc swiden(elem x) { return H::widen(x); }
+    __device__ static sacc sadd(sacc a, elem x, uint32_t op) { return combine_fp(op, a, H::widen(x)); }
+    __device__ static elem snarrow(sacc a) { return H::narrow(a); }
 };
+
+// bf16 is the upper half of a binary32
+struct Bf16Conv {
+    __device__ static float widen(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+    __device__ static uint16_t narrow(float f)
+    {
+        const uint32_t u = __float_as_uint(f);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u); // NaN: keep it quiet
+        return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+    }
+};
+
+// IEEE binary16 through the hardware conversions (v_cvt_f32_f16 is exact, v_cvt_f16_f32 rounds
+// to nearest even in the default rounding mode, subnormals included)
+struct F16Conv {
+    __device__ static float widen(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+    __device__ static uint16_t narrow(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+};
+
+using BF16 = Half16<Bf16Conv>;
+using F16 = Half16<F16Conv>;
 
 // ---- memory access -----------------------------------------------------------------------------
 //
@@ -178,24 +278,25 @@ __device__ inline u32x4 load_src(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, bo
 // tails that do not fill a 16-byte vector, and segments whose operands are not congruent
 // modulo 16 bytes).
 template <typename T>
-__device__ inline void reduce_one(const uint64_t* sp, const uint64_t* dp, uint32_t k, uint32_t m, uint64_t e)
+__device__ inline void reduce_one(const uint64_t* sp, const uint64_t* dp, uint32_t k, uint32_t m, uint64_t e, uint32_t op)
 {
     using elem = typename T::elem;
     typename T::sacc a = T::swiden(reinterpret_cast<const elem*>(sp[0])[e]);
-    for (uint32_t t = 1; t < k; ++t) a = T::sadd(a, reinterpret_cast<const elem*>(sp[t])[e]);
+    for (uint32_t t = 1; t < k; ++t) a = T::sadd(a, reinterpret_cast<const elem*>(sp[t])[e], op);
     const elem r = T::snarrow(a);
     for (uint32_t d = 0; d < m; ++d) reinterpret_cast<elem*>(dp[d])[e] = r;
 }
 
 // ---- the kernel -------------------------------------------------------------------------------
 
-template <typename T, int U, int POLICY, int BLOCK>
+// SUM_ONLY instances have the paper's operation compiled in; the others take it from the launch.
+template <typename T, int U, int POLICY, int BLOCK, bool SUM_ONLY>
 __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
 {
     using P = Policy<POLICY>;
     const uint32_t seg = blockIdx.x / tab.tiles_per_seg;
     const uint32_t tile = blockIdx.x - seg * tab.tiles_per_seg;
-    const uint32_t k = tab.k, m = tab.m;
+    const uint32_t k = tab.k, m = tab.m, op = SUM_ONLY ? (uint32_t)LA_SUM : tab.op;
     const SegInfo si = tab.seg[seg];
     const uint64_t* sp = tab.src_ptr + (uint64_t)seg * k;
     const uint64_t* dp = tab.dst_ptr + (uint64_t)seg * m;
@@ -207,7 +308,7 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
         const uint64_t lo = (uint64_t)tile * TILE * T::VEC;
         uint64_t hi = lo + TILE * T::VEC;
         if (hi > si.len) hi = si.len;
-        for (uint64_t e = lo + tid; e < hi; e += BLOCK) reduce_one<T>(sp, dp, k, m, e);
+        for (uint64_t e = lo + tid; e < hi; e += BLOCK) reduce_one<T>(sp, dp, k, m, e, op);
         return;
     }
 
@@ -218,7 +319,7 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     if (tile == 0 && tid < si.head + tail) {
         // the few elements before the first and after the last whole vector
         const uint64_t e = tid < si.head ? tid : si.head + nvec * T::VEC + (tid - si.head);
-        reduce_one<T>(sp, dp, k, m, e);
+        reduce_one<T>(sp, dp, k, m, e, op);
     }
 
     const uint64_t tile_v0 = (uint64_t)tile * TILE;
@@ -253,7 +354,7 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
 #pragma unroll
         for (int b = 0; b < KBATCH; ++b)
 #pragma unroll
-            for (int u = 0; u < U; ++u) T::add(acc[u], x[b][u]);
+            for (int u = 0; u < U; ++u) T::add(acc[u], x[b][u], op);
     }
     // remaining 0..KBATCH-1 operands
     if (t < k) {
@@ -272,7 +373,7 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
         for (int b = 0; b < KBATCH - 1; ++b) {
             if ((uint32_t)b < rem) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) T::add(acc[u], x[b][u]);
+                for (int u = 0; u < U; ++u) T::add(acc[u], x[b][u], op);
             }
         }
     }
@@ -287,18 +388,27 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     }
 }
 
+template <typename T, int U, int POLICY, int BLOCK>
+void launch_op(const StepTable& t, dim3 grid, hipStream_t s)
+{
+    if (t.op == (uint32_t)LA_SUM)
+        hipLaunchKernelGGL((seg_reduce_kernel<T, U, POLICY, BLOCK, true>), grid, dim3(BLOCK), 0, s, t);
+    else
+        hipLaunchKernelGGL((seg_reduce_kernel<T, U, POLICY, BLOCK, false>), grid, dim3(BLOCK), 0, s, t);
+}
+
 template <typename T, int U, int BLOCK>
 la_status_t launch_policy(const StepTable& t, int policy, dim3 grid, hipStream_t s)
 {
     switch (policy) {
-    case 0: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 0, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
-    case 1: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 1, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
-    case 2: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 2, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
-    case 3: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 3, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
-    case 4: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 4, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
-    case 5: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 5, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
-    case 6: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 6, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
-    case 7: hipLaunchKernelGGL((seg_reduce_kernel<T, U, 7, BLOCK>), grid, dim3(BLOCK), 0, s, t); break;
+    case 0: launch_op<T, U, 0, BLOCK>(t, grid, s); break;
+    case 1: launch_op<T, U, 1, BLOCK>(t, grid, s); break;
+    case 2: launch_op<T, U, 2, BLOCK>(t, grid, s); break;
+    case 3: launch_op<T, U, 3, BLOCK>(t, grid, s); break;
+    case 4: launch_op<T, U, 4, BLOCK>(t, grid, s); break;
+    case 5: launch_op<T, U, 5, BLOCK>(t, grid, s); break;
+    case 6: launch_op<T, U, 6, BLOCK>(t, grid, s); break;
+    case 7: launch_op<T, U, 7, BLOCK>(t, grid, s); break;
     default: return fail(LA_ERR_INVALID_ARG, "unsupported cache policy %d", policy);
     }
     const hipError_t e = hipGetLastError();
@@ -313,7 +423,6 @@ la_status_t launch_unroll(const StepTable& t, const Tuning& tune, dim3 grid, hip
     case 1: return launch_policy<T, 1, BLOCK>(t, tune.cache_policy, grid, s);
     case 2: return launch_policy<T, 2, BLOCK>(t, tune.cache_policy, grid, s);
     case 4: return launch_policy<T, 4, BLOCK>(t, tune.cache_policy, grid, s);
-    case 8: return launch_policy<T, 8, BLOCK>(t, tune.cache_policy, grid, s);
     }
     return fail(LA_ERR_INVALID_ARG, "unsupported unroll %d", tune.unroll);
 }
@@ -323,7 +432,6 @@ la_status_t launch_block(const StepTable& t, const Tuning& tune, dim3 grid, hipS
 {
     switch (tune.block) {
     case 256: return launch_unroll<T, 256>(t, tune, grid, s);
-    case 512: return launch_unroll<T, 512>(t, tune, grid, s);
     case 1024: return launch_unroll<T, 1024>(t, tune, grid, s);
     }
     return fail(LA_ERR_INVALID_ARG, "unsupported block size %d", tune.block);
@@ -331,30 +439,35 @@ la_status_t launch_block(const StepTable& t, const Tuning& tune, dim3 grid, hipS
 
 } // namespace
 
-uint32_t tiles_for(uint64_t max_units, const Tuning& tune)
+// This file is compiled once per element type (-DLA_KERNEL_DTYPE=<la_dtype_t value>), so that
+// the instances of the five types build in parallel; launch_step in dispatch.cpp picks one.
+#if LA_KERNEL_DTYPE == 0
+la_status_t launch_step_i32(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream)
 {
-    const uint64_t tile = (uint64_t)tune.block * (uint64_t)tune.unroll;
-    const uint64_t tiles = (max_units + tile - 1) / tile;
-    return (uint32_t)(tiles ? tiles : 1);
+    return launch_block<I32>(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
 }
-
-// The caller guarantees: tables are device-resident and hold num_segments * k (resp. m)
-// pointers; every pointer range [ptr, ptr + len*esize) is valid device memory;
-// tiles_per_seg == tiles_for(longest segment in vectors, tune).
-la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream)
+#elif LA_KERNEL_DTYPE == 1
+la_status_t launch_step_f32(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream)
 {
-    if (t.num_segments == 0) return LA_OK;
-    if (t.k < 1 || t.m < 1) return fail(LA_ERR_INVALID_ARG, "internal: step with k=%u m=%u", t.k, t.m);
-    const uint64_t blocks = (uint64_t)t.num_segments * t.tiles_per_seg;
-    if (blocks > 0x7fffffffull) return fail(LA_ERR_INVALID_ARG, "step needs %llu workgroups", (unsigned long long)blocks);
-    const dim3 grid((uint32_t)blocks);
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    switch (dtype) {
-    case LA_I32: return launch_block<I32>(t, tune, grid, s);
-    case LA_F32: return launch_block<F32>(t, tune, grid, s);
-    case LA_BF16: return launch_block<BF16>(t, tune, grid, s);
-    }
-    return fail(LA_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+    return launch_block<F32>(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
 }
+#elif LA_KERNEL_DTYPE == 2
+la_status_t launch_step_bf16(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream)
+{
+    return launch_block<BF16>(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
+}
+#elif LA_KERNEL_DTYPE == 3
+la_status_t launch_step_f16(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream)
+{
+    return launch_block<F16>(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
+}
+#elif LA_KERNEL_DTYPE == 4
+la_status_t launch_step_f64(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream)
+{
+    return launch_block<F64>(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
+}
+#else
+#error "compile kernels.hip with -DLA_KERNEL_DTYPE=0..4"
+#endif
 
 } // namespace la

@@ -24,7 +24,16 @@ inline Part split_part(uint64_t len, uint64_t m, uint64_t i)
 
 inline size_t dtype_size(la_dtype_t d)
 {
-    return d == LA_BF16 ? 2 : 4;
+    if (d == LA_BF16 || d == LA_F16) return 2;
+    return d == LA_F64 ? 8 : 4;
+}
+inline bool known_dtype(int d)
+{
+    return d == LA_I32 || d == LA_F32 || d == LA_BF16 || d == LA_F16 || d == LA_F64;
+}
+inline bool known_op(int op)
+{
+    return op == LA_SUM || op == LA_PROD || op == LA_MAX || op == LA_MIN;
 }
 
 struct Operand {
@@ -59,6 +68,7 @@ struct StepTable {
     uint32_t k, m;
     uint32_t tiles_per_seg;  // grid = S * tiles_per_seg blocks
     uint32_t num_segments;
+    uint32_t op = 0;         // la_op_t of the launch
 };
 
 // Launch shape of one step.  In the process-wide setting 0 (unroll, block) and -1 (cache_policy)

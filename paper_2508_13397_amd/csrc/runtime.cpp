@@ -100,7 +100,7 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
     if (req.unroll <= 0)
         while (t.unroll > 1 && (uint64_t)t.block * t.unroll > longest_units) t.unroll /= 2;
     if (req.block <= 0)
-        while (t.block > 256 && (uint64_t)t.block * t.unroll > longest_units) t.block /= 2;
+        if (t.block > 256 && (uint64_t)t.block * t.unroll > longest_units) t.block = 256;
     return t;
 }
 } // namespace la
@@ -121,6 +121,7 @@ struct la_binding {
     hipStream_t capture_stream = nullptr;
     hipGraph_t graph = nullptr;
     hipGraphExec_t graph_exec = nullptr;
+    uint32_t graph_op = 0;       // the operation recorded in the graph's kernel arguments
     bool graph_failed = false;
 };
 
@@ -329,13 +330,16 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
 
 // Record every launch of the schedule into a graph of kernel nodes.  Only kernel launches are
 // captured (no memset or copy nodes).  On failure the binding falls back to stream launches.
-la_status_t capture_graph(const la_schedule_t* sched, la_binding* b)
+la_status_t capture_graph(const la_schedule_t* sched, la_binding* b, uint32_t op)
 {
     if (!b->capture_stream) LA_HIP(hipStreamCreateWithFlags(&b->capture_stream, hipStreamNonBlocking));
     LA_HIP(hipStreamBeginCapture(b->capture_stream, hipStreamCaptureModeThreadLocal));
     la_status_t st = LA_OK;
-    for (size_t i = 0; i < b->step.size() && st == LA_OK; ++i)
-        st = launch_step(b->step[i], sched->dtype, b->shape[i], b->capture_stream);
+    for (size_t i = 0; i < b->step.size() && st == LA_OK; ++i) {
+        StepTable t = b->step[i];
+        t.op = op;
+        st = launch_step(t, sched->dtype, b->shape[i], b->capture_stream);
+    }
     hipGraph_t g = nullptr;
     const hipError_t e = hipStreamEndCapture(b->capture_stream, &g);
     if (st != LA_OK || e != hipSuccess || !g) {
@@ -349,10 +353,11 @@ la_status_t capture_graph(const la_schedule_t* sched, la_binding* b)
     }
     b->graph = g;
     b->graph_exec = x;
+    b->graph_op = op;
     return LA_OK;
 }
 
-la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, int first, int last, void* hip_stream)
+la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, int first, int last, uint32_t op, void* hip_stream)
 {
     std::vector<uint64_t> addr;
     la_status_t st = check_buffers(*sched, bufs, addr);
@@ -368,7 +373,8 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, int first, 
     const bool want_graph = whole && last > 0 && (mode == 1 || (mode < 0 && last >= GRAPH_MIN_STEPS));
     bool launched = false;
     if (want_graph && !b->graph_failed) {
-        if (!b->graph_exec && capture_graph(sched, b) != LA_OK) b->graph_failed = true;
+        if (b->graph_exec && b->graph_op != op) drop_graph(b);
+        if (!b->graph_exec && capture_graph(sched, b, op) != LA_OK) b->graph_failed = true;
         if (b->graph_exec) {
             LA_HIP(hipGraphLaunch(b->graph_exec, stream));
             launched = true;
@@ -376,7 +382,9 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, int first, 
     }
     if (!launched) {
         for (int i = first; i < last; ++i) {
-            st = launch_step(b->step[i], sched->dtype, b->shape[i], hip_stream);
+            StepTable t = b->step[i];
+            t.op = op;
+            st = launch_step(t, sched->dtype, b->shape[i], hip_stream);
             if (st != LA_OK) return st;
         }
     }
@@ -451,13 +459,13 @@ la_status_t la_allreduce_emulated(const la_schedule_t* sched, void* const* bufs,
 {
     if (!sched) return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated: schedule is NULL");
     if (!bufs) return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated: bufs is NULL");
-    if (op != LA_SUM) return fail(LA_ERR_UNSUPPORTED, "la_allreduce_emulated: only LA_SUM is supported");
-    if (dtype != LA_I32 && dtype != LA_F32 && dtype != LA_BF16)
+    if (!known_op((int)op)) return fail(LA_ERR_UNSUPPORTED, "la_allreduce_emulated: unknown operation %d", (int)op);
+    if (!known_dtype((int)dtype))
         return fail(LA_ERR_UNSUPPORTED, "la_allreduce_emulated: unknown dtype %d", (int)dtype);
     if (n != sched->n || dtype != sched->dtype)
         return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated: n/dtype differ from the schedule's (%llu, %d)",
                     (unsigned long long)sched->n, (int)sched->dtype);
-    return run_steps(sched, bufs, 0, (int)sched->steps.size(), hip_stream);
+    return run_steps(sched, bufs, 0, (int)sched->steps.size(), (uint32_t)op, hip_stream);
 }
 
 la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* const* bufs, void* hip_stream)
@@ -466,15 +474,15 @@ la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* con
     if (!bufs) return fail(LA_ERR_INVALID_ARG, "la_schedule_run_step: bufs is NULL");
     if (step < 0 || step >= (int)sched->steps.size())
         return fail(LA_ERR_INVALID_ARG, "la_schedule_run_step: step %d out of range", step);
-    return run_steps(sched, bufs, step, step + 1, hip_stream);
+    return run_steps(sched, bufs, step, step + 1, (uint32_t)LA_SUM, hip_stream);
 }
 
 la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const size_t* seg_offsets,
                                size_t num_segments, size_t seg_len, la_dtype_t dtype, la_op_t op,
                                void* hip_stream)
 {
-    if (op != LA_SUM) return fail(LA_ERR_UNSUPPORTED, "la_reduce_segments: only LA_SUM is supported");
-    if (dtype != LA_I32 && dtype != LA_F32 && dtype != LA_BF16)
+    if (!known_op((int)op)) return fail(LA_ERR_UNSUPPORTED, "la_reduce_segments: unknown operation %d", (int)op);
+    if (!known_dtype((int)dtype))
         return fail(LA_ERR_UNSUPPORTED, "la_reduce_segments: unknown dtype %d", (int)dtype);
     if (k < 0) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: k is negative");
     if (!dst) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: dst is NULL");
@@ -543,6 +551,7 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
     t.dst_ptr = reinterpret_cast<const uint64_t*>(b + seg_bytes + src_bytes);
     t.k = (uint32_t)K;
     t.m = 1;
+    t.op = (uint32_t)op;
     t.num_segments = (uint32_t)num_segments;
     const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest, (uint64_t)num_segments * seg_len * e);
     t.tiles_per_seg = tiles_for(longest, tune);
@@ -556,8 +565,8 @@ la_status_t la_tuning_set(const char* key, int value)
     if (!key) return fail(LA_ERR_INVALID_ARG, "la_tuning_set: key is NULL");
     const std::string k(key);
     if (k == "unroll") {
-        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
-            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: unroll must be 0 (auto), 1, 2, 4 or 8");
+        if (value != 0 && value != 1 && value != 2 && value != 4)
+            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: unroll must be 0 (auto), 1, 2 or 4");
         g_unroll.store(value);
         return LA_OK;
     }
@@ -575,8 +584,8 @@ la_status_t la_tuning_set(const char* key, int value)
         return LA_OK;
     }
     if (k == "block") {
-        if (value != 0 && value != 256 && value != 512 && value != 1024)
-            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: block must be 0 (auto), 256, 512 or 1024");
+        if (value != 0 && value != 256 && value != 1024)
+            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: block must be 0 (auto), 256 or 1024");
         g_block.store(value);
         return LA_OK;
     }

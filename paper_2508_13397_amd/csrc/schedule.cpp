@@ -539,8 +539,7 @@ la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size
     if (algo == LA_ALGO_RING) flags &= ~(unsigned)LA_SCHED_INNER_RING; // the flat ring has no inner stage
     if (n == 0) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: n is 0");
     if (n > (uint64_t(1) << 40)) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: n exceeds 2^40");
-    if (dtype != LA_I32 && dtype != LA_F32 && dtype != LA_BF16)
-        return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown dtype %d", (int)dtype);
+    if (!known_dtype((int)dtype)) return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown dtype %d", (int)dtype);
     if (algo != LA_ALGO_RING && algo != LA_ALGO_LANE && algo != LA_ALGO_LANE_MULTIPROC)
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown algorithm %d", (int)algo);
     if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED | LA_SCHED_INNER_RING | LA_SCHED_SHARED_BUFFERS))

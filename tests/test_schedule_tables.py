@@ -86,8 +86,8 @@ def test_schedule_build_errors():
 def test_tuning_knobs():
     assert (la.la_tuning_get("unroll"), la.la_tuning_get("cache_policy"), la.la_tuning_get("block")) == (0, -1, 0)
     try:
-        for key, good, bad in (("unroll", (1, 2, 4, 8, 0), (3, -1, 16)), ("cache_policy", (0, 1, 2, 3, 4, 5, 6, 7, -1), (8, -2)),
-                               ("block", (256, 512, 1024, 0), (128, 100, 2048)), ("graph", (0, 1, -1), (2, -2))):
+        for key, good, bad in (("unroll", (1, 2, 4, 0), (3, -1, 8, 16)), ("cache_policy", (0, 1, 2, 3, 4, 5, 6, 7, -1), (8, -2)),
+                               ("block", (256, 1024, 0), (128, 512, 2048)), ("graph", (0, 1, -1), (2, -2))):
             for v in good:
                 la.la_tuning_set(key, v)
                 assert la.la_tuning_get(key) == v
@@ -114,7 +114,7 @@ def test_run_calls_reject_bad_arguments_before_touching_a_device():
     assert L.la_allreduce_emulated(s.handle, None, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
     assert L.la_allreduce_emulated(s.handle, bufs, 32, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
     assert L.la_allreduce_emulated(s.handle, bufs, 64, la.LA_I32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
-    assert L.la_allreduce_emulated(s.handle, bufs, 64, la.LA_F32, 3, None) == la.LA_ERR_UNSUPPORTED
+    assert L.la_allreduce_emulated(s.handle, bufs, 64, la.LA_F32, 4, None) == la.LA_ERR_UNSUPPORTED
     null_buf = (ctypes.c_void_p * 2)(0x1000, 0)
     assert L.la_allreduce_emulated(s.handle, null_buf, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
     odd = (ctypes.c_void_p * 2)(0x1001, 0x2000)
@@ -134,7 +134,7 @@ def test_run_calls_reject_bad_arguments_before_touching_a_device():
     assert rs(0x1002, srcs, 1, offs, 2, 8, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
     assert rs(0x1000, srcs, 1, offs, 2, 9, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG  # overlap
     assert rs(0x1000, srcs, 1, offs, 2, 8, 5, la.LA_SUM, None) == la.LA_ERR_UNSUPPORTED
-    assert rs(0x1000, srcs, 1, offs, 2, 8, la.LA_F32, 1, None) == la.LA_ERR_UNSUPPORTED
+    assert rs(0x1000, srcs, 1, offs, 2, 8, la.LA_F32, 7, None) == la.LA_ERR_UNSUPPORTED
     alias = (ctypes.c_void_p * 1)(0x1000)
     assert rs(0x1000, alias, 1, offs, 2, 8, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
     # nothing to do: accepted without any device work
