@@ -90,7 +90,11 @@ enum {
      * all-reduce runs on the private copies, and the result is copied back (the copy to and from
      * a buffer allocated by the calling process of the GPUDirect runs).  LA_SCHED_INNER_RING is
      * not available in this model. */
-    LA_SCHED_SHARED_BUFFERS = 8u
+    LA_SCHED_SHARED_BUFFERS = 8u,
+    /* Separate send and receive buffers, as Algorithm 1 is printed (buf_send, buf_recv): the
+     * schedule is run with la_allreduce_emulated_out_of_place; original inputs are read from the
+     * send buffers, which are never written, and every result lands in the receive buffers. */
+    LA_SCHED_OUT_OF_PLACE = 16u
 };
 
 /* Step kinds and stage labels reported by la_schedule_step_info. */
@@ -105,7 +109,8 @@ enum {
     LA_STAGE_S2_RING_AG = 7, /* LA_SCHED_INNER_RING: one gather iteration of the inter-node rings */
     LA_STAGE_RING_RS = 10, /* one iteration of the first loop of Algorithm 1 */
     LA_STAGE_RING_AG = 11, /* one iteration of the second loop of Algorithm 1 */
-    LA_STAGE_PACK = 20     /* staged exchange: copy of incoming segments into the staging area */
+    LA_STAGE_PACK = 20,    /* staged exchange: copy of incoming segments into the staging area */
+    LA_STAGE_COPY_INPUT = 21 /* out-of-place: ranges that no step reduces, copied from send to receive */
 };
 
 /* ---- topology ------------------------------------------------------------------------- */
@@ -152,8 +157,9 @@ la_status_t la_schedule_step_info(const la_schedule_t* sched, int step, int* kin
 
 /* Copy out the table of one step [host arrays sized from la_schedule_step_info]:
  * seg_len[S]; src_buf/src_off[S*fan_in]; dst_buf/dst_off[S*fan_out].  A buffer index below
- * la_schedule_num_buffers() is a caller buffer; that number itself is the staging area.  Offsets
- * are in elements. */
+ * la_schedule_num_buffers() is a caller buffer (the receive buffer in an out-of-place schedule);
+ * that number itself is the staging area; that number + 1 + b is send buffer b of an
+ * out-of-place schedule.  Offsets are in elements. */
 la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_t* seg_len, int32_t* src_buf,
                                    uint64_t* src_off, int32_t* dst_buf, uint64_t* dst_off);
 
@@ -180,6 +186,13 @@ la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_
  */
 la_status_t la_allreduce_emulated(const la_schedule_t* sched, void* const* bufs, size_t n, la_dtype_t dtype,
                                   la_op_t op, void* hip_stream);
+
+/* The same all-reduce with separate buffers: sendbufs[b] is read only, recvbufs[b] receives the
+ * result; all 2 * la_schedule_num_buffers() buffers must be pairwise disjoint.  The schedule must
+ * have been built with LA_SCHED_OUT_OF_PLACE (and la_allreduce_emulated refuses such a schedule). */
+la_status_t la_allreduce_emulated_out_of_place(const la_schedule_t* sched, const void* const* sendbufs,
+                                               void* const* recvbufs, size_t n, la_dtype_t dtype, la_op_t op,
+                                               void* hip_stream);
 
 /* Enqueue a single step of the schedule (same conventions): for per-step timing and for tests
  * that look at intermediate states. */

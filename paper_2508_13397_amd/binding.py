@@ -18,16 +18,17 @@ LA_I32, LA_F32, LA_BF16, LA_F16, LA_F64 = 0, 1, 2, 3, 4
 LA_SUM, LA_PROD, LA_MAX, LA_MIN = 0, 1, 2, 3
 OPS = {"sum": LA_SUM, "prod": LA_PROD, "max": LA_MAX, "min": LA_MIN}
 LA_SCHED_DEFAULT, LA_SCHED_P2P_GATHER, LA_SCHED_STAGED, LA_SCHED_INNER_RING = 0, 1, 2, 4
-LA_SCHED_SHARED_BUFFERS = 8
+LA_SCHED_SHARED_BUFFERS, LA_SCHED_OUT_OF_PLACE = 8, 16
 LA_STEP_REDUCE, LA_STEP_COPY = 0, 1
 LA_STAGE_S1, LA_STAGE_S2A, LA_STAGE_S2B, LA_STAGE_S3, LA_STAGE_S2 = 1, 2, 3, 4, 5
 LA_STAGE_RING_RS, LA_STAGE_RING_AG, LA_STAGE_PACK = 10, 11, 20
 LA_STAGE_S2_RING_RS, LA_STAGE_S2_RING_AG = 6, 7
+LA_STAGE_COPY_INPUT = 21
 
 ALGOS = {"ring": LA_ALGO_RING, "lane": LA_ALGO_LANE, "lane_multiproc": LA_ALGO_LANE_MULTIPROC}
 DTYPES = {"int32": LA_I32, "float32": LA_F32, "bfloat16": LA_BF16, "float16": LA_F16, "float64": LA_F64}
 ELEM_SIZE = {LA_I32: 4, LA_F32: 4, LA_BF16: 2, LA_F16: 2, LA_F64: 8}
-STAGE_NAMES = {1: "S1", 2: "S2a", 3: "S2b", 4: "S3", 5: "S2", 6: "S2-ring-RS", 7: "S2-ring-AG", 10: "ring-RS",
+STAGE_NAMES = {21: "copy-input", 1: "S1", 2: "S2a", 3: "S2b", 4: "S3", 5: "S2", 6: "S2-ring-RS", 7: "S2-ring-AG", 10: "ring-RS",
                11: "ring-AG", 20: "pack"}
 
 # every symbol include/lane_allreduce.h declares
@@ -36,7 +37,7 @@ EXPORTS = (
     "la_schedule_build", "la_schedule_build_ex", "la_schedule_destroy", "la_schedule_num_steps",
     "la_schedule_num_buffers",
     "la_schedule_staging_elems", "la_schedule_step_info", "la_schedule_step_table",
-    "la_allreduce_emulated", "la_schedule_run_step", "la_reduce_segments",
+    "la_allreduce_emulated", "la_allreduce_emulated_out_of_place", "la_schedule_run_step", "la_reduce_segments",
     "la_status_string", "la_last_error", "la_tuning_set", "la_tuning_get",
 )
 
@@ -75,6 +76,7 @@ def lib() -> ctypes.CDLL:
     L.la_schedule_step_info.argtypes = [vp, i32, pp(i32), pp(i32), pp(sz), pp(sz), pp(i32), pp(i32), pp(sz), pp(sz)]
     L.la_schedule_step_table.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     L.la_allreduce_emulated.argtypes = [vp, pp(vp), sz, i32, i32, vp]
+    L.la_allreduce_emulated_out_of_place.argtypes = [vp, pp(vp), pp(vp), sz, i32, i32, vp]
     L.la_schedule_run_step.argtypes = [vp, i32, pp(vp), vp]
     L.la_reduce_segments.argtypes = [vp, pp(vp), i32, pp(sz), sz, sz, i32, i32, vp]
     L.la_status_string.argtypes = [i32]
@@ -225,6 +227,14 @@ def la_allreduce_emulated(sched: Schedule, bufs: Sequence[int], n: int, dtype, o
     dtype = DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
     _check(lib().la_allreduce_emulated(sched.handle, _ptr_array(bufs), int(n), dtype, int(op),
                                        ctypes.c_void_p(stream)), "la_allreduce_emulated")
+
+
+def la_allreduce_emulated_out_of_place(sched: Schedule, sendbufs: Sequence[int], recvbufs: Sequence[int], n: int, dtype,
+                                       op: int = LA_SUM, stream: int = 0) -> None:
+    dtype = DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
+    _check(lib().la_allreduce_emulated_out_of_place(sched.handle, _ptr_array(sendbufs), _ptr_array(recvbufs), int(n),
+                                                    dtype, int(op), ctypes.c_void_p(stream)),
+           "la_allreduce_emulated_out_of_place")
 
 
 def la_schedule_run_step(sched: Schedule, step: int, bufs: Sequence[int], stream: int = 0) -> None:

@@ -251,22 +251,35 @@ void relocate(std::vector<StepTable>& view, const void* device_base)
     }
 }
 
-la_status_t check_buffers(const la_schedule& s, void* const* bufs, std::vector<uint64_t>& addr)
+// addr layout: [0, P) the (receive) buffers, [P] the staging area (filled by bind), and for an
+// out-of-place schedule [P + 1, 2P + 1) the send buffers.
+la_status_t check_buffers(const la_schedule& s, void* const* bufs, const void* const* sendbufs,
+                          std::vector<uint64_t>& addr)
 {
     const int P = s.nbuf;
     const size_t e = dtype_size(s.dtype);
-    addr.resize(P + 1);
+    const bool oop = (s.flags & LA_SCHED_OUT_OF_PLACE) != 0;
+    if (oop != (sendbufs != nullptr))
+        return fail(LA_ERR_INVALID_ARG, oop ? "the schedule is out-of-place: use la_allreduce_emulated_out_of_place"
+                                            : "the schedule was not built with LA_SCHED_OUT_OF_PLACE");
+    addr.assign(oop ? 2 * P + 1 : P + 1, 0);
+    std::vector<uint64_t> sorted;
     for (int r = 0; r < P; ++r) {
         if (!bufs[r]) return fail(LA_ERR_INVALID_ARG, "bufs[%d] is NULL", r);
         addr[r] = reinterpret_cast<uint64_t>(bufs[r]);
         if (addr[r] % e) return fail(LA_ERR_INVALID_ARG, "bufs[%d] is not aligned to the element size", r);
+        sorted.push_back(addr[r]);
+        if (oop) {
+            if (!sendbufs[r]) return fail(LA_ERR_INVALID_ARG, "sendbufs[%d] is NULL", r);
+            addr[P + 1 + r] = reinterpret_cast<uint64_t>(sendbufs[r]);
+            if (addr[P + 1 + r] % e) return fail(LA_ERR_INVALID_ARG, "sendbufs[%d] is not aligned to the element size", r);
+            sorted.push_back(addr[P + 1 + r]);
+        }
     }
-    std::vector<uint64_t> sorted(addr.begin(), addr.begin() + P);
     std::sort(sorted.begin(), sorted.end());
-    for (int r = 1; r < P; ++r)
+    for (size_t r = 1; r < sorted.size(); ++r)
         if (sorted[r] < sorted[r - 1] + s.n * e)
-            return fail(LA_ERR_INVALID_ARG, "rank buffers overlap (or one pointer was passed twice)");
-    addr[P] = 0;
+            return fail(LA_ERR_INVALID_ARG, "buffers overlap (or one pointer was passed twice)");
     return LA_OK;
 }
 
@@ -277,9 +290,8 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     LA_HIP(hipGetDevice(&dev));
     la_binding* b = s.bound;
     const int P = s.nbuf;
-    if (b && b->device == dev && b->requested == tune && b->bufs.size() == (size_t)P &&
-        std::equal(addr.begin(), addr.begin() + P, b->bufs.begin()))
-        return LA_OK;
+    const std::vector<uint64_t> key = addr; // caller addresses only: the staging slot is still 0
+    if (b && b->device == dev && b->requested == tune && b->bufs == key) return LA_OK;
     if (b && b->used) LA_HIP(hipEventSynchronize(b->last_use)); // earlier work still reads the tables
     if (b && b->device != dev) {
         release_binding(b);
@@ -320,7 +332,7 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     LA_HIP(hipMemcpy(b->tables, ht.blob.data(), ht.blob.size(), hipMemcpyHostToDevice));
     relocate(ht.view, b->tables);
     b->step = std::move(ht.view);
-    b->bufs.assign(addr.begin(), addr.begin() + P);
+    b->bufs = key;
     drop_graph(b); // recorded launches point at the old tables
     b->requested = tune;
     b->shape = std::move(shapes);
@@ -357,10 +369,11 @@ la_status_t capture_graph(const la_schedule_t* sched, la_binding* b, uint32_t op
     return LA_OK;
 }
 
-la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, int first, int last, uint32_t op, void* hip_stream)
+la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void* const* sendbufs, int first,
+                      int last, uint32_t op, void* hip_stream)
 {
     std::vector<uint64_t> addr;
-    la_status_t st = check_buffers(*sched, bufs, addr);
+    la_status_t st = check_buffers(*sched, bufs, sendbufs, addr);
     if (st != LA_OK) return st;
     std::lock_guard<std::mutex> lock(sched->mu);
     const Tuning tune = current_tuning();
@@ -465,7 +478,22 @@ la_status_t la_allreduce_emulated(const la_schedule_t* sched, void* const* bufs,
     if (n != sched->n || dtype != sched->dtype)
         return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated: n/dtype differ from the schedule's (%llu, %d)",
                     (unsigned long long)sched->n, (int)sched->dtype);
-    return run_steps(sched, bufs, 0, (int)sched->steps.size(), (uint32_t)op, hip_stream);
+    return run_steps(sched, bufs, nullptr, 0, (int)sched->steps.size(), (uint32_t)op, hip_stream);
+}
+
+la_status_t la_allreduce_emulated_out_of_place(const la_schedule_t* sched, const void* const* sendbufs,
+                                               void* const* recvbufs, size_t n, la_dtype_t dtype, la_op_t op,
+                                               void* hip_stream)
+{
+    if (!sched) return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated_out_of_place: schedule is NULL");
+    if (!sendbufs || !recvbufs) return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated_out_of_place: a buffer array is NULL");
+    if (!known_op((int)op)) return fail(LA_ERR_UNSUPPORTED, "la_allreduce_emulated_out_of_place: unknown operation %d", (int)op);
+    if (!known_dtype((int)dtype))
+        return fail(LA_ERR_UNSUPPORTED, "la_allreduce_emulated_out_of_place: unknown dtype %d", (int)dtype);
+    if (n != sched->n || dtype != sched->dtype)
+        return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated_out_of_place: n/dtype differ from the schedule's (%llu, %d)",
+                    (unsigned long long)sched->n, (int)sched->dtype);
+    return run_steps(sched, recvbufs, sendbufs, 0, (int)sched->steps.size(), (uint32_t)op, hip_stream);
 }
 
 la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* const* bufs, void* hip_stream)
@@ -474,7 +502,7 @@ la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* con
     if (!bufs) return fail(LA_ERR_INVALID_ARG, "la_schedule_run_step: bufs is NULL");
     if (step < 0 || step >= (int)sched->steps.size())
         return fail(LA_ERR_INVALID_ARG, "la_schedule_run_step: step %d out of range", step);
-    return run_steps(sched, bufs, step, step + 1, (uint32_t)LA_SUM, hip_stream);
+    return run_steps(sched, bufs, nullptr, step, step + 1, (uint32_t)LA_SUM, hip_stream);
 }
 
 la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const size_t* seg_offsets,

@@ -408,6 +408,79 @@ void wrap_copy_in_out(la_schedule& s, Staging& st, int Q)
     }
 }
 
+// ---- out-of-place form ---------------------------------------------------------------------------
+// Algorithm 1 is printed with separate send and receive buffers (buf_send, buf_recv, and
+// buf_sendfrom switching from one to the other after the first iteration).  With
+// LA_SCHED_OUT_OF_PLACE the caller passes both: a source range that no earlier step has written is
+// an original input and is read from the send buffer (index nbuf + 1 + b in the tables); all
+// stores go to the receive buffers, and the send buffers are never written.
+
+struct Covered { // sorted, disjoint [lo, hi) ranges of one buffer that have been written
+    std::vector<std::pair<uint64_t, uint64_t>> iv;
+    // 1: fully written, 0: not written at all, -1: partly
+    int query(uint64_t lo, uint64_t hi) const
+    {
+        uint64_t have = 0;
+        for (const auto& r : iv) {
+            const uint64_t a = std::max(lo, r.first), b = std::min(hi, r.second);
+            if (a < b) have += b - a;
+        }
+        return have == hi - lo ? 1 : have == 0 ? 0 : -1;
+    }
+    void add(uint64_t lo, uint64_t hi)
+    {
+        std::vector<std::pair<uint64_t, uint64_t>> out;
+        for (const auto& r : iv) {
+            if (r.second < lo || r.first > hi) {
+                out.push_back(r);
+            } else {
+                lo = std::min(lo, r.first);
+                hi = std::max(hi, r.second);
+            }
+        }
+        out.emplace_back(lo, hi);
+        std::sort(out.begin(), out.end());
+        iv.swap(out);
+    }
+};
+
+la_status_t make_out_of_place(la_schedule& s)
+{
+    const int B = s.nbuf;
+    std::vector<Covered> written(B);
+    for (Step& p : s.steps) {
+        const size_t S = p.num_segments();
+        for (size_t g = 0; g < S; ++g)
+            for (int t = 0; t < p.k; ++t) {
+                Operand& o = p.src[g * p.k + t];
+                if (o.buf >= B) continue; // staging is always written before it is read
+                const int c = written[o.buf].query(o.off, o.off + p.len[g]);
+                if (c < 0) return fail(LA_ERR_UNSUPPORTED, "out-of-place: a segment mixes original and reduced data");
+                if (c == 0) o.buf = B + 1 + o.buf; // original input: from the send buffer
+            }
+        for (size_t g = 0; g < S; ++g)
+            for (int d = 0; d < p.m; ++d) {
+                const Operand& o = p.dst[g * p.m + d];
+                if (o.buf < B) written[o.buf].add(o.off, o.off + p.len[g]);
+            }
+    }
+    // whatever no step wrote (a single rank, a node of one rank, ...) is copied across
+    Step cp;
+    cp.kind = LA_STEP_COPY;
+    cp.stage = LA_STAGE_COPY_INPUT;
+    cp.k = cp.m = 1;
+    for (int b = 0; b < B; ++b) {
+        uint64_t at = 0;
+        for (const auto& r : written[b].iv) {
+            push_copy(cp, r.first - at, Operand{B + 1 + b, at}, Operand{b, at});
+            at = r.second;
+        }
+        push_copy(cp, s.n - at, Operand{B + 1 + b, at}, Operand{b, at});
+    }
+    if (!cp.len.empty()) s.steps.push_back(std::move(cp));
+    return LA_OK;
+}
+
 } // namespace
 
 la_status_t generate_steps(la_schedule& s)
@@ -436,6 +509,10 @@ la_status_t generate_steps(la_schedule& s)
         }
     }
     s.staging_elems = st.peak;
+    if (s.flags & LA_SCHED_OUT_OF_PLACE) {
+        const la_status_t st2 = make_out_of_place(s);
+        if (st2 != LA_OK) return st2;
+    }
     for (const Step& p : s.steps) {
         const size_t S = p.num_segments();
         if (p.src.size() != S * (size_t)p.k || p.dst.size() != S * (size_t)p.m)
@@ -473,7 +550,8 @@ la_status_t validate_hazards(const la_schedule& s)
         }
         for (const Iv& x : iv) {
             const uint64_t cap = x.buf == P ? limit_stage : s.n;
-            if (x.buf < 0 || x.buf > P || x.hi > cap)
+            const int top = (s.flags & LA_SCHED_OUT_OF_PLACE) ? 2 * P : P;
+            if (x.buf < 0 || x.buf > top || x.hi > cap || (x.write && x.buf > P))
                 return fail(LA_ERR_INVALID_ARG, "internal: step %zu has a range outside its buffer", si);
         }
         std::sort(iv.begin(), iv.end(), [](const Iv& a, const Iv& b) {
@@ -542,7 +620,8 @@ la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size
     if (!known_dtype((int)dtype)) return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown dtype %d", (int)dtype);
     if (algo != LA_ALGO_RING && algo != LA_ALGO_LANE && algo != LA_ALGO_LANE_MULTIPROC)
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown algorithm %d", (int)algo);
-    if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED | LA_SCHED_INNER_RING | LA_SCHED_SHARED_BUFFERS))
+    if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED | LA_SCHED_INNER_RING | LA_SCHED_SHARED_BUFFERS |
+                               LA_SCHED_OUT_OF_PLACE))
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown flag bits 0x%x", flags);
     la_schedule* s = new (std::nothrow) la_schedule;
     if (!s) return fail(LA_ERR_OUT_OF_MEMORY, "la_schedule_build: out of host memory");

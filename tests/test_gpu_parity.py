@@ -383,6 +383,28 @@ def test_many_gpus_per_node_fan_in_beyond_64(oracle):
         assert np.array_equal(bits(got), bits(ref)), algo
 
 
+# ------------------------------------------------------------------------------ out-of-place form
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("extra", [0, la.LA_SCHED_STAGED, la.LA_SCHED_INNER_RING, la.LA_SCHED_P2P_GATHER])
+def test_out_of_place_send_untouched_receive_complete(oracle, algo, extra):
+    for (topo, n), kind in itertools.product([((2, 2, 2), 100003), ((1, 1, 1), 1000), ((3, 1, 2), 7), ((2, 3, 1), 40961)],
+                                             ("i32wrap", "f32order", "bf16")):
+        N, G, Q = topo
+        P = N * G * Q
+        x = make(P, n, kind, seed=n)
+        sched = la.la_schedule_build(la.la_topology_create(N, G, Q), algo, n, NAME[x.dtype], la.LA_SCHED_OUT_OF_PLACE | extra)
+        send = [to_dev(x[r]) for r in range(P)]
+        recv = [torch.full_like(send[r], 7) for r in range(P)]
+        print("oop case", algo, extra, topo, n, kind, flush=True)
+        la.la_allreduce_emulated_out_of_place(sched, [t.data_ptr() for t in send], [t.data_ptr() for t in recv], n,
+                                              NAME[x.dtype], la.LA_SUM, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        ref = oracle.allreduce(oracle_name(algo, extra), N, G, Q, x)
+        assert np.array_equal(bits(np.stack([to_host(t) for t in recv])), bits(ref)), (algo, extra, topo, n, kind)
+        assert np.array_equal(bits(np.stack([to_host(t) for t in send])), bits(x))
+
+
 # ------------------------------------------------------------------------------ shared-buffer model
 
 SHARED = la.LA_SCHED_SHARED_BUFFERS

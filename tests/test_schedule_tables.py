@@ -68,7 +68,7 @@ def test_schedule_build_errors():
         (dict(algo=7, n=16, dtype="float32"), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype=9), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype="float32", flags=64), la.LA_ERR_UNSUPPORTED),
-        (dict(algo="lane", n=16, dtype="float32", flags=16), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=32), la.LA_ERR_UNSUPPORTED),
     ):
         with pytest.raises(la.LaError) as e:
             la.la_schedule_build(t, **kwargs)
@@ -124,6 +124,15 @@ def test_run_calls_reject_bad_arguments_before_touching_a_device():
     overlap = (ctypes.c_void_p * 2)(0x1000, 0x1080)
     assert L.la_allreduce_emulated(s.handle, overlap, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
     assert L.la_schedule_run_step(s.handle, 5, bufs, None) == la.LA_ERR_INVALID_ARG
+    oop = la.la_schedule_build(t, "lane", 64, "float32", la.LA_SCHED_OUT_OF_PLACE)
+    other = (ctypes.c_void_p * 2)(0x5000, 0x6000)
+    f = L.la_allreduce_emulated_out_of_place
+    assert L.la_allreduce_emulated(oop.handle, bufs, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert f(s.handle, other, bufs, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG   # in-place schedule
+    assert f(oop.handle, None, bufs, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
+    assert f(oop.handle, bufs, bufs, 64, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG   # send aliases receive
+    assert f(oop.handle, other, bufs, 64, la.LA_F32, 9, None) == la.LA_ERR_UNSUPPORTED
+    assert f(oop.handle, other, bufs, 32, la.LA_F32, la.LA_SUM, None) == la.LA_ERR_INVALID_ARG
     offs = (ctypes.c_size_t * 2)(0, 8)
     srcs = (ctypes.c_void_p * 1)(0x3000)
     rs = L.la_reduce_segments
@@ -272,6 +281,72 @@ def test_shared_buffer_shapes_and_bytes():
     with pytest.raises(la.LaError) as err:
         la.la_schedule_build(t, "lane_multiproc", n, "float32", SHARED | la.LA_SCHED_INNER_RING)
     assert err.value.status == la.LA_ERR_UNSUPPORTED
+
+
+def run_tables_out_of_place(sched, inputs):
+    """Interpreter for LA_SCHED_OUT_OF_PLACE tables: buffers [0,B) receive (pre-filled with junk),
+    B staging, B+1+b send buffer b.  Returns (receive buffers, send buffers) after the run."""
+    B, n = inputs.shape
+    junk = np.full(n, 0x5A5A5A5A5A5A5A5A, dtype=np.uint64).view(np.uint8)[: n * inputs.dtype.itemsize].view(inputs.dtype)
+    state = [junk.copy() for _ in range(B)] + [np.zeros(max(sched.staging_elems, 1), dtype=inputs.dtype)] + \
+            [inputs[b].copy() for b in range(B)]
+    for i in range(sched.num_steps):
+        t = sched.step_table(i)
+        old = [b.copy() for b in state]
+        assert np.all(t["dst_buf"] <= B)  # send buffers are never written
+        for g in range(t["num_segments"]):
+            ln = int(t["seg_len"][g])
+            ops = [old[int(b)][int(o):int(o) + ln] for b, o in zip(t["src_buf"][g], t["src_off"][g])]
+            if inputs.dtype == np.int32:
+                acc = ops[0].view(np.uint32).copy()
+                for x in ops[1:]:
+                    acc = acc + x.view(np.uint32)
+                res = acc.view(np.int32)
+            else:
+                acc = ops[0].copy()
+                for x in ops[1:]:
+                    acc = acc + x
+                res = acc
+            for b, o in zip(t["dst_buf"][g], t["dst_off"][g]):
+                state[int(b)][int(o):int(o) + ln] = res
+    return np.stack(state[:B]), np.stack(state[B + 1:])
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("extra", [0, la.LA_SCHED_P2P_GATHER, la.LA_SCHED_STAGED, la.LA_SCHED_INNER_RING,
+                                   la.LA_SCHED_SHARED_BUFFERS, la.LA_SCHED_SHARED_BUFFERS | la.LA_SCHED_STAGED])
+def test_out_of_place_tables(oracle, algo, extra):
+    OOP = la.LA_SCHED_OUT_OF_PLACE
+    shared = bool(extra & la.LA_SCHED_SHARED_BUFFERS)
+    for (N, G, Q) in TOPOS:
+        B = N * G if shared else N * G * Q
+        topo = la.la_topology_create(N, G, Q)
+        for n in (1, 4, 17, 36):
+            for x in (np.random.default_rng(n).integers(-(1 << 31), 1 << 31, size=(B, n), dtype=np.int64).astype(np.int32),
+                      synth.order_sensitive_f32(B, n)):
+                sched = la.la_schedule_build(topo, algo, n, "int32" if x.dtype == np.int32 else "float32", OOP | extra)
+                recv, send = run_tables_out_of_place(sched, x)
+                if shared:
+                    ref = oracle.allreduce("lane_multiproc" if algo == "lane" else algo, N, G, 1 if algo == "lane" else Q, x, shared=True)
+                else:
+                    ref = oracle.allreduce(oracle_name(algo, extra), N, G, Q, x)
+                assert np.array_equal(recv.view(np.uint8), ref.view(np.uint8)), (algo, extra, N, G, Q, n)
+                assert np.array_equal(send.view(np.uint8), x.view(np.uint8))
+
+
+def test_out_of_place_ring_reads_send_buffers_like_algorithm_1():
+    P, n = 4, 64
+    s = la.la_schedule_build(la.la_topology_create(2, 2, 1), "ring", n, "float32", la.LA_SCHED_OUT_OF_PLACE)
+    first = s.step_table(0)
+    assert np.all(first["src_buf"] > P)                      # first iteration: both operands from buf_send
+    for i in range(1, P - 1):
+        t = s.step_table(i)
+        assert np.all(t["src_buf"][:, 0] > P)                # own copy: still the original input
+        assert np.all(t["src_buf"][:, 1] < P)                # incoming partial sum: from the previous rank's buf_recv
+    for i in range(P - 1, 2 * (P - 1)):
+        assert np.all(s.step_table(i)["src_buf"] < P)        # gather loop: buf_recv only
+    single = la.la_schedule_build(la.la_topology_create(1, 1, 1), "lane", n, "float32", la.LA_SCHED_OUT_OF_PLACE)
+    assert [x["stage"] for x in single.steps()] == [la.LA_STAGE_COPY_INPUT]
 
 
 def test_hazard_freedom_every_step_reads_no_range_another_segment_writes():
