@@ -21,12 +21,15 @@ _LIB = os.path.join(_HERE, "libla_oracle.so")
 I32, F32, BF16, F16, F64 = 0, 1, 2, 3, 4
 OPS = {"sum": 0, "prod": 1, "max": 2, "min": 3}
 RING, LANE, LANE_MULTIPROC, LANE_RING, LANE_MULTIPROC_RING = 0, 1, 2, 3, 4
+RECURSIVE_DOUBLING, RABENSEIFNER = 5, 6
 ALGOS = {"ring": RING, "lane": LANE, "lane_multiproc": LANE_MULTIPROC, "lane_ring": LANE_RING,
-         "lane_multiproc_ring": LANE_MULTIPROC_RING}
+         "lane_multiproc_ring": LANE_MULTIPROC_RING, "recursive_doubling": RECURSIVE_DOUBLING,
+         "rabenseifner": RABENSEIFNER}
 
 # phases in the message trace
 PH_LANE_S1, PH_LANE_S2A, PH_LANE_S2B, PH_LANE_S3, PH_RING_RS, PH_RING_AG = 1, 2, 3, 4, 10, 11
 PH_LANE_S2_RING_RS, PH_LANE_S2_RING_AG = 5, 6
+PH_RECURSIVE_DOUBLING, PH_RABENSEIFNER_RS, PH_RABENSEIFNER_AG = 20, 21, 22
 
 MSG_DTYPE = np.dtype(
     [("phase", "<i4"), ("step", "<i4"), ("src", "<i4"), ("dst", "<i4"), ("off", "<u8"), ("cnt", "<u8")]
@@ -67,6 +70,7 @@ class Oracle:
     PH_LANE_S1, PH_LANE_S2A, PH_LANE_S2B, PH_LANE_S3 = PH_LANE_S1, PH_LANE_S2A, PH_LANE_S2B, PH_LANE_S3
     PH_RING_RS, PH_RING_AG = PH_RING_RS, PH_RING_AG
     PH_LANE_S2_RING_RS, PH_LANE_S2_RING_AG = PH_LANE_S2_RING_RS, PH_LANE_S2_RING_AG
+    PH_RECURSIVE_DOUBLING, PH_RABENSEIFNER_RS, PH_RABENSEIFNER_AG = 20, 21, 22
 
     def __init__(self, libpath: str):
         lib = ctypes.CDLL(libpath)

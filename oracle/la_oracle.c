@@ -38,6 +38,11 @@
  *     part to the part's owner, who adds the operands in ascending
  *     communicator rank (its own copy taking its place in that order), and
  *     the all-reduce is that reduce-scatter followed by an all-gather;
+ *   - recursive doubling and Rabenseifner's algorithm are only described in
+ *     words (Background section): they are taken in their textbook form for a
+ *     power-of-two number of ranks (exchange with the rank that differs in one
+ *     bit; recursive halving from distance P/2 down, lower rank keeps the
+ *     first half; recursive doubling back up);
  *   - the "_ring" variants run Algorithm 1 as that inter-node all-reduce
  *     instead: the owned part is cut into N pieces and member v of the lane
  *     communicator plays rank v of a ring of N;
@@ -73,7 +78,11 @@ enum {
     /* Algorithm 2 with Algorithm 1 as the all-reduce on the lane communicator (the variant the
      * Results section measures "where the ring algorithm is used in the inter-node stage") */
     ORACLE_LANE_RING = 3,
-    ORACLE_LANE_MULTIPROC_RING = 4
+    ORACLE_LANE_MULTIPROC_RING = 4,
+    /* the small- and medium-size algorithms of the Background section, flat over the P ranks
+     * (P a power of two) */
+    ORACLE_RECURSIVE_DOUBLING = 5,
+    ORACLE_RABENSEIFNER = 6
 };
 
 /* phases recorded in the message trace */
@@ -85,7 +94,10 @@ enum {
     PH_LANE_S2_RING_RS = 5, /* inter-node stage as a ring: reduce loop */
     PH_LANE_S2_RING_AG = 6, /* inter-node stage as a ring: gather loop */
     PH_RING_RS = 10, /* ring reduce-scatter loop           */
-    PH_RING_AG = 11  /* ring all-gather loop               */
+    PH_RING_AG = 11, /* ring all-gather loop               */
+    PH_RECURSIVE_DOUBLING = 20, /* pairwise exchange of the whole buffer */
+    PH_RABENSEIFNER_RS = 21,    /* recursive halving: reduce-scatter      */
+    PH_RABENSEIFNER_AG = 22     /* recursive doubling: all-gather         */
 };
 
 typedef struct {
@@ -568,6 +580,91 @@ static int run_ring(world_t* w, int max_rounds)
     return w->failed ? 3 : 0;
 }
 
+/* ---- Background section: recursive doubling and Rabenseifner's algorithm ---- */
+
+static int log2_exact(int P)
+{
+    int L = 0;
+    while ((1 << L) < P) ++L;
+    return (1 << L) == P ? L : -1;
+}
+
+/* Recursive doubling: log2(P) rounds; in round s rank r exchanges its WHOLE buffer with the
+ * rank whose number differs in bit s, and both add what they receive to their own copy. */
+static int run_recursive_doubling(world_t* w, int max_rounds)
+{
+    int P = w->P, L = log2_exact(P);
+    if (L < 0) return 2;
+    w->phase = PH_RECURSIVE_DOUBLING;
+    for (int s = 0; s < L && w->round < max_rounds; ++s) {
+        for (int r = 0; r < P; ++r) post(w, r, r ^ (1 << s), 0, w->n);
+        for (int r = 0; r < P; ++r) {
+            const letter_t* l = letter_from(w, r, r ^ (1 << s));
+            if (!l) return 4;
+            char* own = mem(w, r);
+            const void* two[2] = {own, l->data}; /* own = own + incoming */
+            sum_operands(w->dtype, own, two, 2, l->cnt);
+        }
+        end_round(w);
+    }
+    return w->failed ? 3 : 0;
+}
+
+/* Rabenseifner: a reduce-scatter by recursive halving (the partner is at distance P/2, P/4, ...;
+ * each rank keeps one half of its current range, sends the other half, and adds the partner's
+ * copy of the half it keeps), then an all-gather by recursive doubling that walks the same
+ * ranges back.  2*log2(P) messages, the data halving at each reduce step. */
+static int run_rabenseifner(world_t* w, int max_rounds)
+{
+    int P = w->P, L = log2_exact(P);
+    if (L < 0) return 2;
+    /* lo[r][s], cnt[r][s]: the range rank r works on before reduce round s (s = L: what it owns) */
+    uint64_t* lo = (uint64_t*)calloc((size_t)P * (size_t)(L + 1), sizeof(uint64_t));
+    uint64_t* cnt = (uint64_t*)calloc((size_t)P * (size_t)(L + 1), sizeof(uint64_t));
+    if (!lo || !cnt) return 3;
+    for (int r = 0; r < P; ++r) {
+        lo[r * (L + 1)] = 0;
+        cnt[r * (L + 1)] = w->n;
+        for (int s = 0; s < L; ++s) {
+            int d = P >> (s + 1);
+            uint64_t o, c;
+            part(cnt[r * (L + 1) + s], 2, (r & d) ? 1 : 0, &o, &c); /* lower ranks keep the first half */
+            lo[r * (L + 1) + s + 1] = lo[r * (L + 1) + s] + o;
+            cnt[r * (L + 1) + s + 1] = c;
+        }
+    }
+    w->phase = PH_RABENSEIFNER_RS;
+    for (int s = 0; s < L && w->round < max_rounds; ++s) {
+        int d = P >> (s + 1);
+        for (int r = 0; r < P; ++r) {
+            int p = r ^ d; /* send the half the partner keeps */
+            post(w, r, p, lo[p * (L + 1) + s + 1], cnt[p * (L + 1) + s + 1]);
+        }
+        for (int r = 0; r < P; ++r) {
+            const letter_t* l = letter_from(w, r, r ^ d);
+            if (!l || l->off != lo[r * (L + 1) + s + 1]) return 4;
+            char* own = mem(w, r) + l->off * w->esz;
+            const void* two[2] = {own, l->data};
+            sum_operands(w->dtype, own, two, 2, l->cnt);
+        }
+        end_round(w);
+    }
+    w->phase = PH_RABENSEIFNER_AG;
+    for (int s = L - 1; s >= 0 && w->round < max_rounds; --s) {
+        int d = P >> (s + 1);
+        for (int r = 0; r < P; ++r) post(w, r, r ^ d, lo[r * (L + 1) + s + 1], cnt[r * (L + 1) + s + 1]);
+        for (int r = 0; r < P; ++r) {
+            const letter_t* l = letter_from(w, r, r ^ d);
+            if (!l) return 4;
+            overwrite(w, r, l);
+        }
+        end_round(w);
+    }
+    free(lo);
+    free(cnt);
+    return w->failed ? 3 : 0;
+}
+
 /* ---- Algorithm 2: lane_allreduce, with or without the per-process split -- */
 
 typedef struct {
@@ -986,6 +1083,10 @@ static int run_world(int shared, int algo, int N, int G, int Q, uint64_t n, int 
             rc = 2;
     } else if (algo == ORACLE_RING) {
         rc = run_ring(&w, limit);
+    } else if (algo == ORACLE_RECURSIVE_DOUBLING) {
+        rc = run_recursive_doubling(&w, limit);
+    } else if (algo == ORACLE_RABENSEIFNER) {
+        rc = run_rabenseifner(&w, limit);
     } else if (algo == ORACLE_LANE || algo == ORACLE_LANE_MULTIPROC || algo == ORACLE_LANE_RING ||
                algo == ORACLE_LANE_MULTIPROC_RING) {
         lane_cfg_t c = {N, G, Q, algo == ORACLE_LANE_MULTIPROC || algo == ORACLE_LANE_MULTIPROC_RING,

@@ -62,6 +62,13 @@ MUTATIONS = [
      "case OP_PROD: { int64_t z = (int64_t)(int32_t)a * (int32_t)b; return (uint32_t)(z > 2147483647 ? 2147483647 : z < -2147483648LL ? -2147483648LL : z); }\n    case OP_MAX: return (int32_t)b > (int32_t)a ? b : a;\n    default: return (int32_t)b < (int32_t)a ? b : a;"),
     ("f64_in_single", "double s = ((const double*)ops[0])[i];\n            for (int t = 1; t < k; ++t) s = op_f64(op, s, ((const double*)ops[t])[i]);",
      "float s = (float)((const double*)ops[0])[i];\n            for (int t = 1; t < k; ++t) s = op_f32(op, s, (float)((const double*)ops[t])[i]);"),
+    ("rd_partner_at_fixed_distance", "for (int r = 0; r < P; ++r) post(w, r, r ^ (1 << s), 0, w->n);", "for (int r = 0; r < P; ++r) post(w, r, r ^ 1, 0, w->n);"),
+    ("rd_one_round_short", "for (int s = 0; s < L && w->round < max_rounds; ++s) {\n        for (int r = 0; r < P; ++r) post(w, r, r ^ (1 << s), 0, w->n);",
+     "for (int s = 0; s < L - 1 && w->round < max_rounds; ++s) {\n        for (int r = 0; r < P; ++r) post(w, r, r ^ (1 << s), 0, w->n);"),
+    ("rab_upper_rank_keeps_first_half", "part(cnt[r * (L + 1) + s], 2, (r & d) ? 1 : 0, &o, &c);", "part(cnt[r * (L + 1) + s], 2, (r & d) ? 0 : 1, &o, &c);"),
+    ("rab_starts_at_distance_one", "int d = P >> (s + 1);\n        for (int r = 0; r < P; ++r) {\n            int p = r ^ d; /* send", "int d = 1 << s;\n        for (int r = 0; r < P; ++r) {\n            int p = r ^ d; /* send"),
+    ("rab_sends_own_half", "post(w, r, p, lo[p * (L + 1) + s + 1], cnt[p * (L + 1) + s + 1]);", "post(w, r, p, lo[r * (L + 1) + s + 1], cnt[r * (L + 1) + s + 1]);"),
+    ("rab_gather_skips_last_round", "for (int s = L - 1; s >= 0 && w->round < max_rounds; --s) {", "for (int s = L - 1; s >= 1 && w->round < max_rounds; --s) {"),
     ("rank_numbering_gpu_minor", "return node * c->G * c->Q + local;", "return local * c->N + node;"),
     ("bf16_truncates", "if (lost > 0x8000u)\n        kept += 1;", "if (lost > 0xffffu)\n        kept += 1;"),
     ("bf16_ties_away", "else if (lost == 0x8000u && (kept & 1u))", "else if (lost == 0x8000u)"),
@@ -111,6 +118,10 @@ def pin_calls(o):
         lambda: pins.test_f16_rounds_once_per_reduce_step(o),
         lambda: pins.test_schedules_with_operations_and_wide_types(o, "ring"),
         lambda: pins.test_schedules_with_operations_and_wide_types(o, "lane_multiproc"),
+        lambda: pins.test_recursive_doubling_messages_and_order(o),
+        lambda: pins.test_rabenseifner_messages_halve_and_order(o),
+        lambda: pins.test_small_message_algorithms_bruteforce(o, "recursive_doubling"),
+        lambda: pins.test_small_message_algorithms_bruteforce(o, "rabenseifner"),
         lambda: pins.test_shared_model_with_one_process_per_gpu_is_the_private_model(o),
         lambda: pins.test_shared_standard_messages_scale_with_processes_per_gpu(o),
         lambda: pins.test_shared_lane_stages_and_order(o),

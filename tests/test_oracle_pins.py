@@ -587,6 +587,75 @@ def test_lane_ring_messages_and_boundaries(oracle):
             assert np.array_equal(before_s3[r, other * c:(other + 1) * c], x[r, other * c:(other + 1) * c])
 
 
+# --------------------------------------------------------------------------- Background section algorithms
+
+POW2_TOPOS = [(1, 1, 1), (2, 1, 1), (1, 2, 2), (2, 2, 1), (2, 2, 2), (4, 2, 2), (1, 4, 4)]
+
+
+@pytest.mark.parametrize("algo", ["recursive_doubling", "rabenseifner"])
+def test_small_message_algorithms_bruteforce(oracle, algo):
+    rng = np.random.default_rng(5)
+    for (N, G, Q) in POW2_TOPOS:
+        P = N * G * Q
+        for n in list(range(1, 20)) + [33, 40, 64]:
+            x = rng.integers(-(1 << 31), 1 << 31, size=(P, n), dtype=np.int64).astype(np.int32)
+            out = oracle.allreduce(algo, N, G, Q, x)
+            assert np.array_equal(out, np.broadcast_to(exact_int_sum(x), out.shape)), (algo, N, G, Q, n)
+            f = synth.make_inputs(P, n, "uniform_pm1", seed=n)
+            got = oracle.allreduce(algo, N, G, Q, f)
+            assert all(np.array_equal(got[0], got[r]) for r in range(P))
+            exact = np.array([math.fsum(f[:, i].astype(np.float64)) for i in range(n)])
+            assert np.all(np.abs(got[0] - exact) <= 1e-5 * np.abs(f).sum(axis=0))
+    with pytest.raises(RuntimeError):
+        oracle.allreduce(algo, 3, 1, 1, np.zeros((3, 4), dtype=np.int32))   # not a power of two
+
+
+def test_recursive_doubling_messages_and_order(oracle):
+    P, n = 8, 24
+    x = synth.order_sensitive_f32(P, n)
+    out, tr = oracle.allreduce("recursive_doubling", 2, 2, 2, x, want_trace=True)
+    assert len(tr) == P * 3                                      # log2(p) messages per rank ...
+    assert np.all(tr["cnt"] == n) and np.all(tr["off"] == 0)     # ... each carrying the whole buffer
+    for s in range(3):
+        t = tr[tr["step"] == s]
+        assert np.array_equal(t["dst"], t["src"] ^ (1 << s))
+    # the sum is a balanced tree over neighbours at distance 1, 2, 4
+    v = [x[r] for r in range(P)]
+    for s in range(3):
+        v = [v[r] + v[r ^ (1 << s)] for r in range(P)]
+    assert np.array_equal(out[0].view(np.uint32), v[0].view(np.uint32))
+    assert np.array_equal(out[5].view(np.uint32), v[0].view(np.uint32))
+    flat = f32_sum_in_order(x, list(range(P)))
+    assert not np.array_equal(flat.view(np.uint32), v[0].view(np.uint32))
+
+
+def test_rabenseifner_messages_halve_and_order(oracle):
+    P, n = 8, 64
+    x = synth.order_sensitive_f32(P, n)
+    out, tr = oracle.allreduce("rabenseifner", 1, 4, 2, x, want_trace=True)
+    assert len(tr) == P * 6                                      # 2 log2(p) messages per rank
+    rs, ag = tr[tr["phase"] == oracle.PH_RABENSEIFNER_RS], tr[tr["phase"] == oracle.PH_RABENSEIFNER_AG]
+    for s, (d, size) in enumerate(((4, 32), (2, 16), (1, 8))):   # data cut in half at each step
+        t = rs[rs["step"] == s]
+        assert np.all(t["cnt"] == size) and np.array_equal(t["dst"], t["src"] ^ d)
+    for s, (d, size) in enumerate(((1, 8), (2, 16), (4, 32))):
+        t = ag[ag["step"] == 3 + s]
+        assert np.all(t["cnt"] == size) and np.array_equal(t["dst"], t["src"] ^ d)
+    # after the reduce-scatter rank r owns block number bit-composed from its rank: lower ranks keep first halves
+    xi = synth.make_inputs(P, n, "int_pm1000")
+    mid = oracle.allreduce("rabenseifner", 1, 4, 2, xi, max_rounds=3)
+    total = exact_int_sum(xi)
+    for r in range(P):
+        assert np.array_equal(mid[r, r * 8:(r + 1) * 8], total[r * 8:(r + 1) * 8])
+    # order: partners at distance 4 first, then 2, then 1
+    v = [x[r] for r in range(P)]
+    for d in (4, 2, 1):
+        v = [v[r] + v[r ^ d] for r in range(P)]
+    assert np.array_equal(out[3].view(np.uint32), v[0].view(np.uint32))
+    rd = oracle.allreduce("recursive_doubling", 1, 4, 2, x)
+    assert not np.array_equal(rd.view(np.uint32), out.view(np.uint32))
+
+
 # --------------------------------------------------------------------------- shared-buffer model
 
 SHARED_ALGOS = ("ring", "lane_multiproc")
