@@ -45,8 +45,15 @@ typedef enum {
     LA_ALGO_RING = 0,          /* Algorithm 1, ring_allreduce, over all P ranks */
     LA_ALGO_LANE = 1,          /* Algorithm 2, lane_allreduce: one lane per GPU, owned by the GPU's
                                   leader process (local rank 0) */
-    LA_ALGO_LANE_MULTIPROC = 2 /* Algorithm 2 run per process ("Multi-lane Approach"): each lane
-                                  is split again into one sub-chunk per process of the GPU */
+    LA_ALGO_LANE_MULTIPROC = 2, /* Algorithm 2 run per process ("Multi-lane Approach"): each lane
+                                   is split again into one sub-chunk per process of the GPU */
+    /* The small- and medium-size algorithms of the Background section, flat over all P ranks; P
+     * must be a power of two (else LA_ERR_UNSUPPORTED).  Not available with
+     * LA_SCHED_SHARED_BUFFERS. */
+    LA_ALGO_RECURSIVE_DOUBLING = 3, /* log2 P launches; ranks that differ in one bit exchange and
+                                       add their whole buffers */
+    LA_ALGO_RABENSEIFNER = 4        /* reduce-scatter by recursive halving (log2 P launches, the
+                                       data halving each time) + all-gather by recursive doubling */
 } la_algo_t;
 
 /* Element types.  The paper reduces 32-bit floats; the others follow the same schedules.  The
@@ -109,6 +116,9 @@ enum {
     LA_STAGE_S2_RING_AG = 7, /* LA_SCHED_INNER_RING: one gather iteration of the inter-node rings */
     LA_STAGE_RING_RS = 10, /* one iteration of the first loop of Algorithm 1 */
     LA_STAGE_RING_AG = 11, /* one iteration of the second loop of Algorithm 1 */
+    LA_STAGE_RECURSIVE_DOUBLING = 12, /* one round of recursive doubling */
+    LA_STAGE_RABENSEIFNER_RS = 13,    /* one halving round of Rabenseifner's reduce-scatter */
+    LA_STAGE_RABENSEIFNER_AG = 14,    /* one doubling round of Rabenseifner's all-gather */
     LA_STAGE_PACK = 20,    /* staged exchange: copy of incoming segments into the staging area */
     LA_STAGE_COPY_INPUT = 21 /* out-of-place: ranges that no step reduces, copied from send to receive */
 };

@@ -129,6 +129,73 @@ void gen_ring(la_schedule& s, Staging& st)
     }
 }
 
+// ---- Background section: recursive doubling and Rabenseifner's algorithm ------------------------
+// Both are flat over the P ranks and need P to be a power of two.
+
+int log2_exact(int P)
+{
+    int L = 0;
+    while ((1 << L) < P) ++L;
+    return (1 << L) == P ? L : -1;
+}
+
+// Recursive doubling: in round s the ranks that differ in bit s exchange their whole buffers and
+// each adds the other's to its own.  The two sums of a pair are the same value (the operations
+// are commutative), so one segment computes it once and stores it to both buffers.
+void gen_recursive_doubling(la_schedule& s, Staging& st, int L)
+{
+    const int P = s.topo.ranks();
+    for (int b = 0; b < L; ++b) {
+        ReduceBuilder rb(s, st, LA_STAGE_RECURSIVE_DOUBLING, 2, 2);
+        for (int r = 0; r < P; ++r) {
+            if (r & (1 << b)) continue;
+            const int partner = r | (1 << b);
+            rb.add(s.n, {Operand{r, 0}, Operand{partner, 0}}, {Operand{r, 0}, Operand{partner, 0}}, r);
+        }
+        rb.emit(s.steps);
+    }
+}
+
+// Rabenseifner: reduce-scatter by recursive halving (partners at distance P/2, P/4, ..., 1; the
+// lower rank of a pair keeps the first half of the pair's current range, the upper rank the
+// second, and each adds the partner's copy of the half it keeps), then an all-gather by recursive
+// doubling over the same ranges in reverse.
+void gen_rabenseifner(la_schedule& s, Staging& st, int L)
+{
+    const int P = s.topo.ranks();
+    // range[r][lvl]: what rank r works on before halving round lvl; range[r][L] is what it owns
+    std::vector<std::vector<Part>> range(P, std::vector<Part>(L + 1));
+    for (int r = 0; r < P; ++r) {
+        range[r][0] = Part{0, s.n};
+        for (int lvl = 0; lvl < L; ++lvl) {
+            const int d = P >> (lvl + 1);
+            const Part half = split_part(range[r][lvl].cnt, 2, (r & d) ? 1 : 0);
+            range[r][lvl + 1] = Part{range[r][lvl].off + half.off, half.cnt};
+        }
+    }
+    for (int lvl = 0; lvl < L; ++lvl) {
+        const int d = P >> (lvl + 1);
+        ReduceBuilder rb(s, st, LA_STAGE_RABENSEIFNER_RS, 2, 1);
+        for (int r = 0; r < P; ++r) {
+            const Part keep = range[r][lvl + 1];
+            rb.add(keep.cnt, {Operand{r, keep.off}, Operand{r ^ d, keep.off}}, {Operand{r, keep.off}}, r);
+        }
+        rb.emit(s.steps);
+    }
+    for (int lvl = L - 1; lvl >= 0; --lvl) {
+        const int d = P >> (lvl + 1);
+        Step cp;
+        cp.kind = LA_STEP_COPY;
+        cp.stage = LA_STAGE_RABENSEIFNER_AG;
+        cp.k = cp.m = 1;
+        for (int r = 0; r < P; ++r) {
+            const Part have = range[r ^ d][lvl + 1]; // what the partner holds complete
+            push_copy(cp, have.cnt, Operand{r ^ d, have.off}, Operand{r, have.off});
+        }
+        if (!cp.len.empty()) s.steps.push_back(std::move(cp));
+    }
+}
+
 // ---- Algorithm 2 ---------------------------------------------------------------------------
 // The buffer is cut into J parts: one lane per GPU, and with the per-process split one
 // sub-chunk per process inside each lane.  Part j is owned, on every node, by the process with
@@ -501,10 +568,16 @@ la_status_t generate_steps(la_schedule& s)
         s.flags |= staged;
         if (staged) wrap_copy_in_out(s, st, s.algo == LA_ALGO_RING ? s.topo.procs : Q);
     } else {
+        const int L = log2_exact(s.topo.ranks());
+        if ((s.algo == LA_ALGO_RECURSIVE_DOUBLING || s.algo == LA_ALGO_RABENSEIFNER) && L < 0)
+            return fail(LA_ERR_UNSUPPORTED, "recursive doubling / Rabenseifner need a power-of-two number of ranks (got %d)",
+                        s.topo.ranks());
         switch (s.algo) {
         case LA_ALGO_RING: gen_ring(s, st); break;
         case LA_ALGO_LANE: gen_lane(s, st, false); break;
         case LA_ALGO_LANE_MULTIPROC: gen_lane(s, st, true); break;
+        case LA_ALGO_RECURSIVE_DOUBLING: gen_recursive_doubling(s, st, L); break;
+        case LA_ALGO_RABENSEIFNER: gen_rabenseifner(s, st, L); break;
         default: return fail(LA_ERR_UNSUPPORTED, "unknown algorithm %d", (int)s.algo);
         }
     }
@@ -614,11 +687,13 @@ la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size
     if (!out) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: out is NULL");
     *out = nullptr;
     if (!topo) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: topology is NULL");
-    if (algo == LA_ALGO_RING) flags &= ~(unsigned)LA_SCHED_INNER_RING; // the flat ring has no inner stage
+    if (algo != LA_ALGO_LANE && algo != LA_ALGO_LANE_MULTIPROC)
+        flags &= ~(unsigned)LA_SCHED_INNER_RING; // the flat algorithms have no inner stage
     if (n == 0) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: n is 0");
     if (n > (uint64_t(1) << 40)) return fail(LA_ERR_INVALID_ARG, "la_schedule_build: n exceeds 2^40");
     if (!known_dtype((int)dtype)) return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown dtype %d", (int)dtype);
-    if (algo != LA_ALGO_RING && algo != LA_ALGO_LANE && algo != LA_ALGO_LANE_MULTIPROC)
+    if (algo != LA_ALGO_RING && algo != LA_ALGO_LANE && algo != LA_ALGO_LANE_MULTIPROC &&
+        algo != LA_ALGO_RECURSIVE_DOUBLING && algo != LA_ALGO_RABENSEIFNER)
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown algorithm %d", (int)algo);
     if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED | LA_SCHED_INNER_RING | LA_SCHED_SHARED_BUFFERS |
                                LA_SCHED_OUT_OF_PLACE))

@@ -383,6 +383,21 @@ def test_many_gpus_per_node_fan_in_beyond_64(oracle):
         assert np.array_equal(bits(got), bits(ref)), algo
 
 
+# ------------------------------------------------------------------------------ Background-section algorithms
+
+@pytest.mark.parametrize("algo", ["recursive_doubling", "rabenseifner"])
+@pytest.mark.parametrize("extra", [0, la.LA_SCHED_STAGED])
+def test_small_message_algorithms(oracle, algo, extra):
+    for (topo, n), kind in itertools.product([((2, 2, 2), 100003), ((1, 1, 1), 50), ((4, 4, 1), 7), ((2, 4, 4), 65536), ((1, 2, 1), 4099)],
+                                             ("i32wrap", "f32order", "bf16")):
+        P = topo[0] * topo[1] * topo[2]
+        x = make(P, n, kind, seed=n)
+        print("small-message case", algo, extra, topo, n, kind, flush=True)
+        got = gpu_allreduce(topo, algo, x, extra)
+        ref = oracle.allreduce(algo, *topo, x)
+        assert np.array_equal(bits(got), bits(ref)), (algo, extra, topo, n, kind)
+
+
 # ------------------------------------------------------------------------------ out-of-place form
 
 @pytest.mark.parametrize("algo", ALGOS)

@@ -65,7 +65,7 @@ def test_schedule_build_errors():
     t = la.la_topology_create(2, 2, 1)
     for kwargs, status in (
         (dict(algo="lane", n=0, dtype="float32"), la.LA_ERR_INVALID_ARG),
-        (dict(algo=7, n=16, dtype="float32"), la.LA_ERR_UNSUPPORTED),
+        (dict(algo=9, n=16, dtype="float32"), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype=9), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype="float32", flags=64), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype="float32", flags=32), la.LA_ERR_UNSUPPORTED),
@@ -347,6 +347,44 @@ def test_out_of_place_ring_reads_send_buffers_like_algorithm_1():
         assert np.all(s.step_table(i)["src_buf"] < P)        # gather loop: buf_recv only
     single = la.la_schedule_build(la.la_topology_create(1, 1, 1), "lane", n, "float32", la.LA_SCHED_OUT_OF_PLACE)
     assert [x["stage"] for x in single.steps()] == [la.LA_STAGE_COPY_INPUT]
+
+
+@pytest.mark.parametrize("algo", ["recursive_doubling", "rabenseifner"])
+@pytest.mark.parametrize("extra", [0, la.LA_SCHED_STAGED, la.LA_SCHED_OUT_OF_PLACE])
+def test_small_message_algorithm_tables(oracle, algo, extra):
+    for (N, G, Q) in [(1, 1, 1), (2, 1, 1), (1, 2, 2), (2, 2, 2), (4, 2, 2)]:
+        P = N * G * Q
+        topo = la.la_topology_create(N, G, Q)
+        for n in (1, 3, 8, 17, 40, 64):
+            for x in (np.random.default_rng(n).integers(-(1 << 31), 1 << 31, size=(P, n), dtype=np.int64).astype(np.int32),
+                      synth.order_sensitive_f32(P, n)):
+                sched = la.la_schedule_build(topo, algo, n, "int32" if x.dtype == np.int32 else "float32", extra)
+                ref = oracle.allreduce(algo, N, G, Q, x)
+                if extra & la.LA_SCHED_OUT_OF_PLACE:
+                    got, send = run_tables_out_of_place(sched, x)
+                    assert np.array_equal(send.view(np.uint8), x.view(np.uint8))
+                else:
+                    got = run_tables(sched, x)
+                    assert np.array_equal(run_tables(sched, x, snapshot=False).view(np.uint8), got.view(np.uint8))
+                assert np.array_equal(got.view(np.uint8), ref.view(np.uint8)), (algo, extra, N, G, Q, n)
+
+
+def test_small_message_algorithm_shapes():
+    P, n, e = 16, 1 << 20, 4
+    t = la.la_topology_create(4, 4, 1)
+    rd = la.la_schedule_build(t, "recursive_doubling", n, "float32")
+    assert rd.num_steps == 4                                                  # log2 p exchanges ...
+    assert all((x["num_segments"], x["seg_len_max"], x["fan_in"], x["fan_out"]) == (P // 2, n, 2, 2) for x in rd.steps())  # ... of the whole buffer
+    rab = la.la_schedule_build(t, "rabenseifner", n, "float32")
+    assert rab.num_steps == 8                                                 # 2 log2 p
+    assert [x["seg_len_max"] for x in rab.steps()] == [n >> 1, n >> 2, n >> 3, n >> 4, n >> 4, n >> 3, n >> 2, n >> 1]
+    assert sum(totals(rab)) == (3 * (P - 1) * n // P * P + 2 * (P - 1) * n // P * P) * e // 1  # 5 (p-1)/p n per rank, p ranks
+    for algo in ("recursive_doubling", "rabenseifner"):
+        with pytest.raises(la.LaError) as err:
+            la.la_schedule_build(la.la_topology_create(3, 2, 1), algo, n, "float32")
+        assert err.value.status == la.LA_ERR_UNSUPPORTED
+        with pytest.raises(la.LaError):
+            la.la_schedule_build(t, algo, n, "float32", la.LA_SCHED_SHARED_BUFFERS)
 
 
 def test_hazard_freedom_every_step_reads_no_range_another_segment_writes():
