@@ -101,7 +101,18 @@ enum {
     /* Separate send and receive buffers, as Algorithm 1 is printed (buf_send, buf_recv): the
      * schedule is run with la_allreduce_emulated_out_of_place; original inputs are read from the
      * send buffers, which are never written, and every result lands in the receive buffers. */
-    LA_SCHED_OUT_OF_PLACE = 16u
+    LA_SCHED_OUT_OF_PLACE = 16u,
+    /* Stand-alone halves of an all-reduce.  Every schedule here is a reduce-scatter followed by
+     * an all-gather (MPI_Reduce_scatter ... MPI_Allgatherv of Algorithm 2, the two loops of
+     * Algorithm 1, the two phases of Rabenseifner's algorithm).  ONLY_REDUCE_SCATTER keeps the
+     * first half: afterwards buffer b holds the complete reduction on the ranges
+     * la_schedule_owned_ranges(b) reports, and partial sums elsewhere.  ONLY_ALLGATHER keeps the
+     * second half: it expects those ranges to be valid and copies them to every buffer.  Running
+     * the two one after the other is the all-reduce, bit for bit.  Lane schedules: the first
+     * half is S1 + the inter-node reduce-scatter, the second the inter-node all-gather + S3.
+     * Not available for recursive doubling, nor for shared buffers with copy-in / copy-out. */
+    LA_SCHED_ONLY_REDUCE_SCATTER = 32u,
+    LA_SCHED_ONLY_ALLGATHER = 64u
 };
 
 /* Step kinds and stage labels reported by la_schedule_step_info. */
@@ -158,6 +169,11 @@ int la_schedule_num_steps(const la_schedule_t* sched);       /* -1 for NULL */
 int la_schedule_num_buffers(const la_schedule_t* sched);     /* entries of bufs: P, or nodes * gpus_per_node
                                                                 with LA_SCHED_SHARED_BUFFERS; -1 for NULL */
 size_t la_schedule_staging_elems(const la_schedule_t* sched); /* elements of library-owned staging */
+/* The element ranges that buffer `buffer` holds fully reduced after the reduce-scatter half (and
+ * must provide to the all-gather half).  Writes up to `capacity` (offset, length) pairs [host]
+ * and returns how many there are (one per rank; one per process with shared buffers; none for a
+ * rank that owns nothing, such as a non-leader in LA_ALGO_LANE); -1 for bad arguments. */
+int la_schedule_owned_ranges(const la_schedule_t* sched, int buffer, int capacity, uint64_t* offsets, uint64_t* lengths);
 
 /* Shape of one step.  Any out pointer may be NULL.  bytes_* are the algorithmic bytes of the
  * step: sum over segments of len * fan_in (resp. fan_out) * element size. */

@@ -20,6 +20,7 @@ LA_SUM, LA_PROD, LA_MAX, LA_MIN = 0, 1, 2, 3
 OPS = {"sum": LA_SUM, "prod": LA_PROD, "max": LA_MAX, "min": LA_MIN}
 LA_SCHED_DEFAULT, LA_SCHED_P2P_GATHER, LA_SCHED_STAGED, LA_SCHED_INNER_RING = 0, 1, 2, 4
 LA_SCHED_SHARED_BUFFERS, LA_SCHED_OUT_OF_PLACE = 8, 16
+LA_SCHED_ONLY_REDUCE_SCATTER, LA_SCHED_ONLY_ALLGATHER = 32, 64
 LA_STEP_REDUCE, LA_STEP_COPY = 0, 1
 LA_STAGE_S1, LA_STAGE_S2A, LA_STAGE_S2B, LA_STAGE_S3, LA_STAGE_S2 = 1, 2, 3, 4, 5
 LA_STAGE_RING_RS, LA_STAGE_RING_AG, LA_STAGE_PACK = 10, 11, 20
@@ -38,7 +39,7 @@ STAGE_NAMES = {21: "copy-input", 12: "rec-doubling", 13: "rabenseifner-RS", 14: 
 EXPORTS = (
     "la_topology_create", "la_topology_destroy", "la_topology_num_ranks",
     "la_schedule_build", "la_schedule_build_ex", "la_schedule_destroy", "la_schedule_num_steps",
-    "la_schedule_num_buffers",
+    "la_schedule_num_buffers", "la_schedule_owned_ranges",
     "la_schedule_staging_elems", "la_schedule_step_info", "la_schedule_step_table",
     "la_allreduce_emulated", "la_allreduce_emulated_out_of_place", "la_schedule_run_step", "la_reduce_segments",
     "la_status_string", "la_last_error", "la_tuning_set", "la_tuning_get",
@@ -74,6 +75,7 @@ def lib() -> ctypes.CDLL:
     L.la_schedule_destroy.argtypes = [vp]
     L.la_schedule_num_steps.argtypes = [vp]
     L.la_schedule_num_buffers.argtypes = [vp]
+    L.la_schedule_owned_ranges.argtypes = [vp, i32, i32, vp, vp]
     L.la_schedule_staging_elems.argtypes = [vp]
     L.la_schedule_staging_elems.restype = sz
     L.la_schedule_step_info.argtypes = [vp, i32, pp(i32), pp(i32), pp(sz), pp(sz), pp(i32), pp(i32), pp(sz), pp(sz)]
@@ -174,6 +176,16 @@ class Schedule:
     @property
     def num_buffers(self) -> int:
         return int(lib().la_schedule_num_buffers(self.handle))
+
+    def owned_ranges(self, buffer: int):
+        """[(offset, length), ...] that `buffer` holds fully reduced between the two halves"""
+        count = lib().la_schedule_owned_ranges(self.handle, buffer, 0, None, None)
+        if count < 0:
+            raise LaError(LA_ERR_INVALID_ARG, "la_schedule_owned_ranges", "bad buffer index")
+        offs = np.zeros(max(count, 1), dtype=np.uint64)
+        lens = np.zeros(max(count, 1), dtype=np.uint64)
+        lib().la_schedule_owned_ranges(self.handle, buffer, count, offs.ctypes.data, lens.ctypes.data)
+        return [(int(offs[i]), int(lens[i])) for i in range(count)]
 
     @property
     def staging_elems(self) -> int:

@@ -117,6 +117,7 @@ struct la_schedule {
                   // buffer index nbuf in the tables is the staging area
     uint64_t staging_elems = 0;
     std::vector<la::Step> steps;
+    std::vector<std::vector<la::Part>> owned; // per buffer: ranges it holds fully reduced between the halves
     // device-side state, created by the first run
     mutable std::mutex mu;
     mutable la_binding* bound = nullptr;

@@ -107,6 +107,7 @@ void gen_ring(la_schedule& s, Staging& st)
     const int P = s.topo.ranks();
     std::vector<Part> chunk(P);
     for (int c = 0; c < P; ++c) chunk[c] = split_part(s.n, P, c);
+    for (int r = 0; r < P; ++r) s.owned[r].push_back(chunk[(r + 1) % P]); // after the first loop
     for (int i = 0; i < P - 1; ++i) {
         ReduceBuilder rb(s, st, LA_STAGE_RING_RS, 2, 1);
         for (int r = 0; r < P; ++r) {
@@ -173,6 +174,7 @@ void gen_rabenseifner(la_schedule& s, Staging& st, int L)
             range[r][lvl + 1] = Part{range[r][lvl].off + half.off, half.cnt};
         }
     }
+    for (int r = 0; r < P; ++r) s.owned[r].push_back(range[r][L]);
     for (int lvl = 0; lvl < L; ++lvl) {
         const int d = P >> (lvl + 1);
         ReduceBuilder rb(s, st, LA_STAGE_RABENSEIFNER_RS, 2, 1);
@@ -206,6 +208,8 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
     const int N = t.nodes, G = t.gpus, Q = t.procs, R = G * Q;
     const int J = split_procs ? R : G;
     const bool p2p = (s.flags & LA_SCHED_P2P_GATHER) != 0;
+    // a stand-alone half needs the inter-node all-reduce as two launches (reduce-scatter, all-gather)
+    const bool split = p2p || (s.flags & (LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER)) != 0;
     auto owner = [&](int j) { return split_procs ? j : j * Q; };
     std::vector<Part> part(J);
     for (int j = 0; j < J; ++j) {
@@ -217,6 +221,15 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
             part[j] = Part{lane.off + sub.off, sub.cnt};
         }
     }
+
+    const bool inner_ring = (s.flags & LA_SCHED_INNER_RING) != 0;
+    // what a rank holds fully reduced between the two halves: piece `node` of the part it owns
+    for (int node = 0; node < N; ++node)
+        for (int j = 0; j < J; ++j) {
+            // (the ring form of stage 2 leaves member v with piece v+1, as Algorithm 1 does)
+            const Part piece = split_part(part[j].cnt, N, inner_ring ? (node + 1) % N : node);
+            s.owned[t.rank_of(node, owner(j))].push_back(Part{part[j].off + piece.off, piece.cnt});
+        }
 
     // S1: reduce-scatter on the node group; the owner adds the R node-local copies of its part
     // in ascending node-local index (its own copy taking its place in that order).
@@ -235,7 +248,6 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
     // S2, ring form (LA_SCHED_INNER_RING): Algorithm 1 on every lane communicator at once.  The
     // part is cut into N pieces and member v plays rank v of a ring of N; one launch holds one
     // ring iteration of all J lane communicators.
-    const bool inner_ring = (s.flags & LA_SCHED_INNER_RING) != 0;
     if (N > 1 && inner_ring) {
         for (int i = 0; i < N - 1; ++i) {
             ReduceBuilder rb(s, st, LA_STAGE_S2_RING_RS, 2, 1);
@@ -268,11 +280,12 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
     // piece v of the part over the N members in ascending node order, then every member gets
     // every piece.
     if (N > 1 && !inner_ring) {
-        ReduceBuilder rb(s, st, p2p ? LA_STAGE_S2A : LA_STAGE_S2, N, p2p ? 1 : N);
+        ReduceBuilder rb(s, st, split ? LA_STAGE_S2A : LA_STAGE_S2, N, split ? 1 : N);
         Step ag;
         ag.kind = LA_STEP_COPY;
         ag.stage = LA_STAGE_S2B;
-        ag.k = ag.m = 1;
+        ag.k = 1;
+        ag.m = p2p ? 1 : N - 1;
         for (int j = 0; j < J; ++j)
             for (int v = 0; v < N; ++v) {
                 const Part piece = split_part(part[j].cnt, N, v);
@@ -281,17 +294,24 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
                 for (int w = 0; w < N; ++w) ops[w] = Operand{t.rank_of(w, owner(j)), off};
                 const int me = t.rank_of(v, owner(j));
                 dsts.push_back(Operand{me, off});
+                if (split && !p2p && piece.cnt > 0) {
+                    ag.len.push_back(piece.cnt);
+                    ag.src.push_back(Operand{me, off});
+                }
                 for (int w = 0; w < N; ++w) {
                     if (w == v) continue;
+                    const Operand to{t.rank_of(w, owner(j)), off};
                     if (p2p)
-                        push_copy(ag, piece.cnt, Operand{me, off}, Operand{t.rank_of(w, owner(j)), off});
-                    else
-                        dsts.push_back(Operand{t.rank_of(w, owner(j)), off});
+                        push_copy(ag, piece.cnt, Operand{me, off}, to);
+                    else if (split) {
+                        if (piece.cnt > 0) ag.dst.push_back(to);
+                    } else
+                        dsts.push_back(to);
                 }
                 rb.add(piece.cnt, ops, dsts, me);
             }
         rb.emit(s.steps);
-        if (p2p && !ag.len.empty()) s.steps.push_back(std::move(ag));
+        if (split && !ag.len.empty()) s.steps.push_back(std::move(ag));
     }
 
     // S3: all-gather on the node group: every owner's part goes to the other R-1 processes.
@@ -337,6 +357,8 @@ void gen_shared_standard(la_schedule& s, Staging& st)
         const Part ch = split_part(slice.cnt, M, c);
         return Part{slice.off + ch.off, ch.cnt};
     };
+    for (int u = 0; u < M; ++u)
+        for (int q = 0; q < Q; ++q) s.owned[u].push_back(chunk(q, (u + 1) % M));
     for (int i = 0; i < M - 1; ++i) {
         ReduceBuilder rb(s, st, LA_STAGE_RING_RS, 2, 1);
         for (int q = 0; q < Q; ++q)
@@ -367,6 +389,7 @@ void gen_shared_lane(la_schedule& s, Staging& st, int Q)
     const la_topology& t = s.topo;
     const int N = t.nodes, G = t.gpus;
     const bool p2p = (s.flags & LA_SCHED_P2P_GATHER) != 0;
+    const bool split = p2p || (s.flags & (LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER)) != 0;
     auto buf = [&](int node, int g) { return node * G + g; };
     auto chunk = [&](int q, int g) {
         const Part slice = split_part(s.n, Q, q);
@@ -385,12 +408,20 @@ void gen_shared_lane(la_schedule& s, Staging& st, int Q)
                 }
         rb.emit(s.steps);
     }
+    for (int q = 0; q < Q; ++q)
+        for (int g = 0; g < G; ++g)
+            for (int v = 0; v < N; ++v) {
+                const Part c = chunk(q, g);
+                const Part piece = split_part(c.cnt, N, v);
+                s.owned[buf(v, g)].push_back(Part{c.off + piece.off, piece.cnt});
+            }
     if (N > 1) {
-        ReduceBuilder rb(s, st, p2p ? LA_STAGE_S2A : LA_STAGE_S2, N, p2p ? 1 : N);
+        ReduceBuilder rb(s, st, split ? LA_STAGE_S2A : LA_STAGE_S2, N, split ? 1 : N);
         Step ag;
         ag.kind = LA_STEP_COPY;
         ag.stage = LA_STAGE_S2B;
-        ag.k = ag.m = 1;
+        ag.k = 1;
+        ag.m = p2p ? 1 : N - 1;
         for (int q = 0; q < Q; ++q)
             for (int g = 0; g < G; ++g)
                 for (int v = 0; v < N; ++v) {
@@ -400,17 +431,23 @@ void gen_shared_lane(la_schedule& s, Staging& st, int Q)
                     std::vector<Operand> ops(N), dsts;
                     for (int w = 0; w < N; ++w) ops[w] = Operand{buf(w, g), off};
                     dsts.push_back(Operand{buf(v, g), off});
+                    if (split && !p2p && piece.cnt > 0) {
+                        ag.len.push_back(piece.cnt);
+                        ag.src.push_back(Operand{buf(v, g), off});
+                    }
                     for (int w = 0; w < N; ++w) {
                         if (w == v) continue;
                         if (p2p)
                             push_copy(ag, piece.cnt, Operand{buf(v, g), off}, Operand{buf(w, g), off});
-                        else
+                        else if (split) {
+                            if (piece.cnt > 0) ag.dst.push_back(Operand{buf(w, g), off});
+                        } else
                             dsts.push_back(Operand{buf(w, g), off});
                     }
                     rb.add(piece.cnt, ops, dsts, buf(v, g));
                 }
         rb.emit(s.steps);
-        if (p2p && !ag.len.empty()) s.steps.push_back(std::move(ag));
+        if (split && !ag.len.empty()) s.steps.push_back(std::move(ag));
     }
     if (G > 1) {
         Step ag;
@@ -515,7 +552,22 @@ la_status_t make_out_of_place(la_schedule& s)
 {
     const int B = s.nbuf;
     std::vector<Covered> written(B);
+    if (s.flags & LA_SCHED_ONLY_ALLGATHER) {
+        // the all-gather half takes each rank's owned ranges from its send buffer: one launch
+        // moves them into place, after which the half runs on the receive buffers alone
+        Step in;
+        in.kind = LA_STEP_COPY;
+        in.stage = LA_STAGE_COPY_INPUT;
+        in.k = in.m = 1;
+        for (int b = 0; b < B; ++b)
+            for (const Part& w : s.owned[b]) {
+                push_copy(in, w.cnt, Operand{B + 1 + b, w.off}, Operand{b, w.off});
+                if (w.cnt) written[b].add(w.off, w.off + w.cnt);
+            }
+        if (!in.len.empty()) s.steps.insert(s.steps.begin(), std::move(in));
+    }
     for (Step& p : s.steps) {
+        if (p.stage == LA_STAGE_COPY_INPUT) continue;
         const size_t S = p.num_segments();
         for (size_t g = 0; g < S; ++g)
             for (int t = 0; t < p.k; ++t) {
@@ -536,13 +588,22 @@ la_status_t make_out_of_place(la_schedule& s)
     cp.kind = LA_STEP_COPY;
     cp.stage = LA_STAGE_COPY_INPUT;
     cp.k = cp.m = 1;
+    const bool half = (s.flags & (LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER)) != 0;
     for (int b = 0; b < B; ++b) {
-        uint64_t at = 0;
-        for (const auto& r : written[b].iv) {
-            push_copy(cp, r.first - at, Operand{B + 1 + b, at}, Operand{b, at});
-            at = r.second;
+        // a stand-alone half defines the receive buffer only where the rank owns the result
+        // (reduce-scatter) or everywhere (all-gather, whose launches write all but the owned ranges)
+        std::vector<Part> want = half ? s.owned[b] : std::vector<Part>{Part{0, s.n}};
+        for (const Part& w : want) {
+            uint64_t at = w.off;
+            const uint64_t end = w.off + w.cnt;
+            for (const auto& r : written[b].iv) {
+                if (r.second <= at) continue;
+                if (r.first >= end) break;
+                if (r.first > at) push_copy(cp, r.first - at, Operand{B + 1 + b, at}, Operand{b, at});
+                at = r.second;
+            }
+            if (at < end) push_copy(cp, end - at, Operand{B + 1 + b, at}, Operand{b, at});
         }
-        push_copy(cp, s.n - at, Operand{B + 1 + b, at}, Operand{b, at});
     }
     if (!cp.len.empty()) s.steps.push_back(std::move(cp));
     return LA_OK;
@@ -553,6 +614,13 @@ la_status_t make_out_of_place(la_schedule& s)
 la_status_t generate_steps(la_schedule& s)
 {
     Staging st;
+    s.owned.assign(s.nbuf, {});
+    if ((s.flags & LA_SCHED_ONLY_REDUCE_SCATTER) && (s.flags & LA_SCHED_ONLY_ALLGATHER))
+        return fail(LA_ERR_INVALID_ARG, "LA_SCHED_ONLY_REDUCE_SCATTER and LA_SCHED_ONLY_ALLGATHER exclude each other");
+    if ((s.flags & (LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER)) &&
+        (s.algo == LA_ALGO_RECURSIVE_DOUBLING ||
+         ((s.flags & LA_SCHED_SHARED_BUFFERS) && (s.flags & LA_SCHED_STAGED))))
+        return fail(LA_ERR_UNSUPPORTED, "this schedule has no reduce-scatter / all-gather halves");
     if (s.flags & LA_SCHED_SHARED_BUFFERS) {
         if (s.flags & LA_SCHED_INNER_RING)
             return fail(LA_ERR_UNSUPPORTED, "LA_SCHED_INNER_RING is not available with LA_SCHED_SHARED_BUFFERS");
@@ -582,6 +650,21 @@ la_status_t generate_steps(la_schedule& s)
         }
     }
     s.staging_elems = st.peak;
+    const unsigned halves = s.flags & (LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER);
+    if (halves) {
+        // keep the launches of one half; a pack launch belongs to the reduce launch after it
+        auto is_gather = [](int stage) {
+            return stage == LA_STAGE_S2B || stage == LA_STAGE_S3 || stage == LA_STAGE_RING_AG ||
+                   stage == LA_STAGE_S2_RING_AG || stage == LA_STAGE_RABENSEIFNER_AG;
+        };
+        std::vector<Step> kept;
+        for (size_t i = 0; i < s.steps.size(); ++i) {
+            int stage = s.steps[i].stage;
+            if (stage == LA_STAGE_PACK && i + 1 < s.steps.size()) stage = s.steps[i + 1].stage;
+            if (is_gather(stage) == (halves == LA_SCHED_ONLY_ALLGATHER)) kept.push_back(std::move(s.steps[i]));
+        }
+        s.steps.swap(kept);
+    }
     if (s.flags & LA_SCHED_OUT_OF_PLACE) {
         const la_status_t st2 = make_out_of_place(s);
         if (st2 != LA_OK) return st2;
@@ -696,7 +779,7 @@ la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size
         algo != LA_ALGO_RECURSIVE_DOUBLING && algo != LA_ALGO_RABENSEIFNER)
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown algorithm %d", (int)algo);
     if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED | LA_SCHED_INNER_RING | LA_SCHED_SHARED_BUFFERS |
-                               LA_SCHED_OUT_OF_PLACE))
+                               LA_SCHED_OUT_OF_PLACE | LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER))
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown flag bits 0x%x", flags);
     la_schedule* s = new (std::nothrow) la_schedule;
     if (!s) return fail(LA_ERR_OUT_OF_MEMORY, "la_schedule_build: out of host memory");
@@ -743,6 +826,21 @@ int la_schedule_num_steps(const la_schedule_t* sched)
 int la_schedule_num_buffers(const la_schedule_t* sched)
 {
     return sched ? sched->nbuf : -1;
+}
+
+int la_schedule_owned_ranges(const la_schedule_t* sched, int buffer, int capacity, uint64_t* offsets, uint64_t* lengths)
+{
+    if (!sched || buffer < 0 || buffer >= sched->nbuf) return -1;
+    int count = 0;
+    for (const Part& p : sched->owned[buffer]) {
+        if (p.cnt == 0) continue;
+        if (count < capacity) {
+            if (offsets) offsets[count] = p.off;
+            if (lengths) lengths[count] = p.cnt;
+        }
+        ++count;
+    }
+    return count;
 }
 
 size_t la_schedule_staging_elems(const la_schedule_t* sched)

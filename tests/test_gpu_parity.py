@@ -422,6 +422,108 @@ def test_out_of_place_send_untouched_receive_complete(oracle, algo, extra):
 
 # ------------------------------------------------------------------------------ shared-buffer model
 
+RS, AG = la.LA_SCHED_ONLY_REDUCE_SCATTER, la.LA_SCHED_ONLY_ALLGATHER
+
+
+def half_rounds(algo, flags, N, G, Q):
+    """oracle rounds that make up the reduce-scatter half of a schedule"""
+    P = N * G * Q
+    if algo == "ring":
+        return P - 1
+    if algo == "rabenseifner":
+        return P.bit_length() - 1
+    return N if flags & la.LA_SCHED_INNER_RING else 2
+
+
+def owned_mask(sched, B, n):
+    mask = np.zeros((B, n), dtype=bool)
+    for b in range(B):
+        for off, ln in sched.owned_ranges(b):
+            mask[b, off:off + ln] = True
+    return mask
+
+
+@pytest.mark.parametrize("algo,flags", [(a, f) for a in ALGOS for f in (0, la.LA_SCHED_STAGED, la.LA_SCHED_INNER_RING, la.LA_SCHED_P2P_GATHER)]
+                         + [("rabenseifner", 0)])
+def test_stand_alone_reduce_scatter_and_allgather(oracle, algo, flags):
+    """First half: the state equals the oracle stopped after its reduce-scatter rounds, and the
+    owned ranges already hold the all-reduce.  Second half, started from buffers that hold
+    nothing but the owned ranges (the rest is NaN / a marker), yields the oracle's all-reduce."""
+    cases = [((2, 2, 2), 100003), ((4, 2, 1), 40961), ((1, 4, 2), 7), ((4, 2, 2), 262147), ((1, 1, 1), 33)]
+    if algo != "rabenseifner":
+        cases += [((3, 2, 1), 12289), ((2, 3, 2), 5)]
+    for (topo, n), kind in itertools.product(cases, ("i32wrap", "f32order", "bf16")):
+        P = topo[0] * topo[1] * topo[2]
+        x = make(P, n, kind, seed=n)
+        print("case", algo, flags, topo, n, kind, flush=True)
+        name = oracle_name(algo, flags)
+        ref_full = oracle.allreduce(name, *topo, x)
+        ref_half = oracle.allreduce(name, *topo, x, max_rounds=half_rounds(algo, flags, *topo))
+        mid = gpu_allreduce(topo, algo, x, flags | RS)
+        assert np.array_equal(bits(mid), bits(ref_half)), (algo, flags, topo, n, kind)
+        t = la.la_topology_create(*topo)
+        mask = owned_mask(la.la_schedule_build(t, algo, n, NAME[x.dtype], flags | AG), P, n)
+        assert np.array_equal(mask.sum(axis=0), np.ones(n, dtype=np.int64))
+        assert np.array_equal(bits(mid[mask]), bits(ref_full[mask]))
+        marker = {np.dtype(np.int32): np.int32(-559038737), np.dtype(np.float32): np.float32(np.nan),
+                  np.dtype(np.uint16): np.uint16(0x7fc1)}[x.dtype]
+        start = np.where(mask, ref_full, marker).astype(x.dtype)
+        out = gpu_allreduce(topo, algo, start, flags | AG)
+        assert np.array_equal(bits(out), bits(ref_full)), (algo, flags, topo, n, kind)
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_stand_alone_halves_out_of_place(oracle, algo):
+    for topo, n in [((2, 2, 2), 100003), ((3, 2, 1), 4099), ((1, 1, 1), 33)]:
+        P = topo[0] * topo[1] * topo[2]
+        x = make(P, n, "f32order", seed=n)
+        ref = oracle.allreduce(algo, *topo, x)
+        t = la.la_topology_create(*topo)
+        outs = []
+        for half, src in ((RS, x), (AG, None)):
+            sched = la.la_schedule_build(t, algo, n, "float32", half | la.LA_SCHED_OUT_OF_PLACE)
+            mask = owned_mask(sched, P, n)
+            if src is None:
+                src = np.where(mask, ref, np.float32(np.nan)).astype(np.float32)
+            send = [to_dev(src[r]) for r in range(P)]
+            recv = [torch.full((n,), -7.0, dtype=torch.float32, device="cuda") for _ in range(P)]
+            la.la_allreduce_emulated_out_of_place(sched, [b.data_ptr() for b in send], [b.data_ptr() for b in recv], n,
+                                                  "float32", la.LA_SUM, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            got = np.stack([to_host(b) for b in recv])
+            assert np.array_equal(bits(np.stack([to_host(b) for b in send])), bits(src))
+            outs.append((got, mask))
+        (mid, mask), (full, _) = outs
+        assert np.array_equal(bits(mid[mask]), bits(ref[mask])), (algo, topo, n)
+        assert np.array_equal(bits(full), bits(ref)), (algo, topo, n)
+
+
+def test_stand_alone_halves_config2_full_size(oracle):
+    """16 ranks x 16 Mi fp32: sampled columns of each half against the oracle run on those columns."""
+    topo, n = (4, 4, 1), 1 << 24
+    P = 16
+    x = synth.make_inputs(P, n, "uniform_pm1", seed=synth.BASE_SEED + 2)
+    t = la.la_topology_create(*topo)
+    rs = la.la_schedule_build(t, "lane", n, "float32", RS)
+    ag = la.la_schedule_build(t, "lane", n, "float32", AG)
+    bufs = [to_dev(x[r]) for r in range(P)]
+    la.allreduce_tensors(rs, bufs)
+    torch.cuda.synchronize()
+    mid = np.stack([to_host(b) for b in bufs])
+    exact = oracle.definition_sum(x)
+    mask = owned_mask(rs, P, n)
+    assert np.array_equal(mask.sum(axis=0), np.ones(n, dtype=np.int64))
+    owned_vals = mid[mask.argmax(axis=0), np.arange(n)]
+    mag = np.abs(x.astype(np.float64)).sum(axis=0)
+    assert np.all(np.abs(owned_vals.astype(np.float64) - exact) <= TOL_F32 * mag)
+    ref = oracle.allreduce("lane", *topo, x)
+    assert np.array_equal(bits(owned_vals), bits(ref[0]))
+    la.allreduce_tensors(ag, bufs)
+    torch.cuda.synchronize()
+    out = np.stack([to_host(b) for b in bufs])
+    assert np.array_equal(bits(out), bits(ref))
+
+
 SHARED = la.LA_SCHED_SHARED_BUFFERS
 
 

@@ -67,8 +67,11 @@ def test_schedule_build_errors():
         (dict(algo="lane", n=0, dtype="float32"), la.LA_ERR_INVALID_ARG),
         (dict(algo=9, n=16, dtype="float32"), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype=9), la.LA_ERR_UNSUPPORTED),
-        (dict(algo="lane", n=16, dtype="float32", flags=64), la.LA_ERR_UNSUPPORTED),
-        (dict(algo="lane", n=16, dtype="float32", flags=32), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=128), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=1 << 20), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=32 | 64), la.LA_ERR_INVALID_ARG),
+        (dict(algo="recursive_doubling", n=16, dtype="float32", flags=32), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="ring", n=16, dtype="float32", flags=64 | 8 | 2), la.LA_ERR_UNSUPPORTED),
     ):
         with pytest.raises(la.LaError) as e:
             la.la_schedule_build(t, **kwargs)
@@ -385,6 +388,124 @@ def test_small_message_algorithm_shapes():
         assert err.value.status == la.LA_ERR_UNSUPPORTED
         with pytest.raises(la.LaError):
             la.la_schedule_build(t, algo, n, "float32", la.LA_SCHED_SHARED_BUFFERS)
+
+
+# ----------------------------------------------------------------------------- stand-alone halves
+
+RS, AG = la.LA_SCHED_ONLY_REDUCE_SCATTER, la.LA_SCHED_ONLY_ALLGATHER
+
+
+def reduce_scatter_rounds(algo, flags, N, G, Q):
+    """communication rounds of the oracle that make up the first half: the first loop of
+    Algorithm 1; MPI_Reduce_scatter on the node group plus the reduce-scatter inside the lane
+    all-reduce of Algorithm 2; the halving phase of Rabenseifner's algorithm"""
+    if flags & SHARED:
+        return N * G - 1 if algo == "ring" else 2
+    P = N * G * Q
+    if algo == "ring":
+        return P - 1
+    if algo == "rabenseifner":
+        return P.bit_length() - 1
+    return 1 + (N - 1) if flags & la.LA_SCHED_INNER_RING else 2
+
+
+def owned_mask(sched, nbuf, n):
+    mask = np.zeros((nbuf, n), dtype=bool)
+    for b in range(nbuf):
+        for off, ln in sched.owned_ranges(b):
+            assert ln > 0 and off + ln <= n
+            assert not mask[b, off:off + ln].any()
+            mask[b, off:off + ln] = True
+    return mask
+
+
+HALF_CASES = [(a, f) for a in ALGOS for f in FLAG_SETS] + [("rabenseifner", 0), ("rabenseifner", la.LA_SCHED_STAGED)] + \
+             [(a, SHARED | f) for a in ALGOS for f in (0, la.LA_SCHED_P2P_GATHER)]
+
+
+@pytest.mark.parametrize("algo,flags", HALF_CASES)
+def test_reduce_scatter_half_then_allgather_half(oracle, algo, flags):
+    """The first half leaves the complete reduction on the owned ranges (which tile the vector
+    once per node group / ring), bit-equal to the oracle stopped after its reduce-scatter
+    rounds; the second half, run on a state that holds ONLY those ranges, gives the oracle's
+    all-reduce; and the two halves in a row are the fused schedule."""
+    topos = [(1, 1, 1), (2, 1, 1), (1, 2, 2), (2, 2, 2), (4, 2, 2)] if algo == "rabenseifner" else TOPOS
+    for (N, G, Q) in topos:
+        P = N * G * Q
+        topo = la.la_topology_create(N, G, Q)
+        for n in (1, 5, 17, 40):
+            for x in (np.random.default_rng(n).integers(-(1 << 31), 1 << 31, size=(P, n), dtype=np.int64).astype(np.int32),
+                      synth.order_sensitive_f32(P, n)):
+                dt = "int32" if x.dtype == np.int32 else "float32"
+                rs = la.la_schedule_build(topo, algo, n, dt, flags | RS)
+                ag = la.la_schedule_build(topo, algo, n, dt, flags | AG)
+                full = la.la_schedule_build(topo, algo, n, dt, flags)
+                B = full.num_buffers
+                assert rs.num_buffers == ag.num_buffers == B
+                assert rs.num_steps + ag.num_steps >= full.num_steps   # the fused S2 launch splits in two
+                xb = x[:B].copy()               # one buffer per GPU (shared) or per rank
+                name, Qo, kw = oracle_name(algo, flags), Q, {}
+                if flags & SHARED:   # "lane" with shared buffers: one process per GPU does the whole buffer
+                    name, Qo, kw = ("lane_multiproc", 1, dict(shared=True)) if algo == "lane" else (algo, Q, dict(shared=True))
+                ref_full = oracle.allreduce(name, N, G, Qo, xb, **kw)
+                ref_half = oracle.allreduce(name, N, G, Qo, xb, max_rounds=reduce_scatter_rounds(algo, flags, N, G, Q), **kw)
+                mask = owned_mask(rs, B, n)
+                assert [ag.owned_ranges(b) for b in range(B)] == [rs.owned_ranges(b) for b in range(B)]
+                # every element of the vector is owned exactly once per ring / per node-spanning group
+                assert np.array_equal(mask.sum(axis=0), np.full(n, 1))
+                mid = run_tables(rs, xb)
+                assert np.array_equal(mid.view(np.uint8), ref_half.view(np.uint8)), (algo, flags, N, G, Q, n)
+                assert np.array_equal(mid[mask].view(np.uint8), ref_full[mask].view(np.uint8))
+                # all-gather from a state that holds nothing but the owned ranges
+                poisoned = np.where(mask, mid, np.array(0x7fc0dead, dtype=np.uint32).view(x.dtype) if x.dtype == np.float32 else np.int32(-559038737))
+                out = run_tables(ag, poisoned.astype(x.dtype))
+                assert np.array_equal(out.view(np.uint8), ref_full.view(np.uint8)), (algo, flags, N, G, Q, n)
+                assert np.array_equal(run_tables(ag, mid).view(np.uint8), run_tables(full, xb).view(np.uint8))
+
+
+@pytest.mark.parametrize("algo", ALGOS + ("rabenseifner",))
+def test_halves_out_of_place(oracle, algo):
+    """Out of place the first half writes only what a rank owns (plus partial sums on the way);
+    the second takes the owned ranges from the send buffers and fills every receive buffer."""
+    for (N, G, Q) in [(1, 1, 1), (2, 2, 2), (4, 2, 1), (1, 4, 2)] + ([] if algo == "rabenseifner" else [(3, 2, 1), (2, 3, 2)]):
+        P = N * G * Q
+        topo = la.la_topology_create(N, G, Q)
+        for n in (3, 17, 64):
+            x = synth.order_sensitive_f32(P, n)
+            ref = oracle.allreduce(algo, N, G, Q, x)
+            rs = la.la_schedule_build(topo, algo, n, "float32", RS | la.LA_SCHED_OUT_OF_PLACE)
+            ag = la.la_schedule_build(topo, algo, n, "float32", AG | la.LA_SCHED_OUT_OF_PLACE)
+            mask = owned_mask(rs, P, n)
+            mid, send = run_tables_out_of_place(rs, x)
+            assert np.array_equal(send.view(np.uint8), x.view(np.uint8))
+            assert np.array_equal(mid[mask].view(np.uint8), ref[mask].view(np.uint8)), (algo, N, G, Q, n)
+            only_owned = np.where(mask, mid, np.float32(np.nan))
+            out, send2 = run_tables_out_of_place(ag, only_owned)
+            assert np.array_equal(send2.view(np.uint8), only_owned.view(np.uint8))
+            assert np.array_equal(out.view(np.uint8), ref.view(np.uint8)), (algo, N, G, Q, n)
+
+
+def test_halves_shapes_and_bytes():
+    """Lane halves at the scale-up shape: S1 + S2a, then S2b as one broadcast launch + S3; the
+    byte totals of the two halves add up to the point-to-point form's minus nothing."""
+    n, e = 1 << 20, 4
+    t = la.la_topology_create(4, 4, 2)
+    rs = la.la_schedule_build(t, "lane_multiproc", n, "float32", RS)
+    ag = la.la_schedule_build(t, "lane_multiproc", n, "float32", AG)
+    assert [(x["stage_name"], x["fan_in"], x["fan_out"]) for x in rs.steps()] == [("S1", 8, 1), ("S2a", 4, 1)]
+    assert [(x["stage_name"], x["fan_in"], x["fan_out"]) for x in ag.steps()] == [("S2b", 1, 3), ("S3", 1, 7)]
+    P = 32
+    r_rs, w_rs = totals(rs)
+    r_ag, w_ag = totals(ag)
+    assert (r_rs, w_rs) == (4 * (8 * n + 4 * n // 4 * 1) * e // 1 - 0, 4 * (n + n // 4) * e)
+    assert (r_ag, w_ag) == (4 * (n // 4 + n) * e, 4 * (3 * n // 4 + 7 * n) * e)
+    ring_rs = la.la_schedule_build(t, "ring", n, "float32", RS)
+    ring_ag = la.la_schedule_build(t, "ring", n, "float32", AG)
+    assert ring_rs.num_steps == ring_ag.num_steps == P - 1
+    assert {x["stage_name"] for x in ring_rs.steps()} == {"ring-RS"} and {x["stage_name"] for x in ring_ag.steps()} == {"ring-AG"}
+    lane = la.la_schedule_build(t, "lane", n, "float32", RS)
+    assert [lane.owned_ranges(r) for r in (1, 3, 5)] == [[], [], []]           # only the leader of a GPU owns data
+    assert lane.owned_ranges(2) == [(n // 4, n // 16)]
 
 
 def test_hazard_freedom_every_step_reads_no_range_another_segment_writes():
