@@ -24,9 +24,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # file (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors calibrated on the ring's plain-copy launches
 # of known size; profiles/seg_reduce_kernel_c2_lane_pmc.md).  Keyed by (config, algo, flags, stage).
 MEASURED_TRAFFIC = {
-    ("c2", "lane", 0, "S1"): 1342245069,
+    ("c2", "lane", 0, "S1"): 1342246093,
     ("c2", "lane", 0, "S2"): 536945664,
-    ("c2", "lane", 0, "S3"): 1075162829,
+    ("c2", "lane", 0, "S3"): 1075078348,
 }
 
 CONFIGS = {
