@@ -274,11 +274,27 @@ __device__ inline u32x4 load_src(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, bo
     }
 }
 
+// The step tables are written by the host before the launch and never by a kernel.  Reading
+// them through the constant address space tells the compiler so: an address that is uniform
+// across the wave is then fetched with scalar loads into SGPRs even after the kernel has issued
+// stores.  Through a generic pointer the destination addresses of the store loop came back as
+// vector loads, each followed by a wait for every outstanding store and a per-lane uniformity
+// loop around every store instruction.
+#define LA_CONSTANT __attribute__((address_space(4)))
+using table_u64 = const LA_CONSTANT uint64_t*;
+using table_seg = const LA_CONSTANT SegInfo*;
+
+template <typename X>
+__device__ inline const LA_CONSTANT X* as_table(const X* p)
+{
+    return (const LA_CONSTANT X*)p;
+}
+
 // One element of one segment, all k operands in order: the slow lanes (segment heads and
 // tails that do not fill a 16-byte vector, and segments whose operands are not congruent
 // modulo 16 bytes).
 template <typename T>
-__device__ inline void reduce_one(const uint64_t* sp, const uint64_t* dp, uint32_t k, uint32_t m, uint64_t e, uint32_t op)
+__device__ inline void reduce_one(table_u64 sp, table_u64 dp, uint32_t k, uint32_t m, uint64_t e, uint32_t op)
 {
     using elem = typename T::elem;
     typename T::sacc a = T::swiden(reinterpret_cast<const elem*>(sp[0])[e]);
@@ -297,9 +313,14 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     const uint32_t seg = blockIdx.x / tab.tiles_per_seg;
     const uint32_t tile = blockIdx.x - seg * tab.tiles_per_seg;
     const uint32_t k = tab.k, m = tab.m, op = SUM_ONLY ? (uint32_t)LA_SUM : tab.op;
-    const SegInfo si = tab.seg[seg];
-    const uint64_t* sp = tab.src_ptr + (uint64_t)seg * k;
-    const uint64_t* dp = tab.dst_ptr + (uint64_t)seg * m;
+    const table_seg sg = as_table(tab.seg) + seg;
+    SegInfo si;
+    si.len = sg->len;
+    si.head = sg->head;
+    si.vec_ok = sg->vec_ok;
+    si.alias_mask = sg->alias_mask;
+    const table_u64 sp = as_table(tab.src_ptr) + (uint64_t)seg * k;
+    const table_u64 dp = as_table(tab.dst_ptr) + (uint64_t)seg * m;
     const uint32_t tid = threadIdx.x;
     constexpr uint64_t TILE = (uint64_t)BLOCK * U; // vectors per tile
 
