@@ -21,7 +21,8 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int KBATCH = 4; // operands whose loads are issued together
+// operands whose loads are issued together: about 8 independent 16-byte loads per lane
+constexpr int batch_for(int unroll) { return unroll >= 8 ? 1 : unroll >= 4 ? 2 : 4; }
 
 // ---- binary operations -----------------------------------------------------------------------
 // The paper reduces with MPI_SUM; product, maximum and minimum run on the same schedules.  The
@@ -350,6 +351,7 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     const uint64_t tile_off = (uint64_t)si.head * sizeof(typename T::elem) + tile_v0 * 16u;
     const uint64_t in_place = si.alias_mask;
 
+    constexpr int KBATCH = batch_for(U);
     uint32_t off[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) off[u] = (tid + (uint32_t)u * BLOCK) * 16u;
@@ -378,9 +380,10 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
             for (int u = 0; u < U; ++u) T::add(acc[u], x[b][u], op);
     }
     // remaining 0..KBATCH-1 operands
-    if (t < k) {
+    if constexpr (KBATCH > 1) {
+      if (t < k) {
         const uint32_t rem = k - t;
-        u32x4 x[KBATCH - 1][U];
+        u32x4 x[KBATCH > 1 ? KBATCH - 1 : 1][U];
 #pragma unroll
         for (int b = 0; b < KBATCH - 1; ++b) {
             if ((uint32_t)b < rem) {
@@ -397,6 +400,7 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
                 for (int u = 0; u < U; ++u) T::add(acc[u], x[b][u], op);
             }
         }
+      }
     }
 
     u32x4 out[U];
@@ -444,8 +448,11 @@ la_status_t launch_unroll(const StepTable& t, const Tuning& tune, dim3 grid, hip
     case 1: return launch_policy<T, 1, BLOCK>(t, tune.cache_policy, grid, s);
     case 2: return launch_policy<T, 2, BLOCK>(t, tune.cache_policy, grid, s);
     case 4: return launch_policy<T, 4, BLOCK>(t, tune.cache_policy, grid, s);
+    case 8: // 128 KiB tiles: workgroups of 1024 lanes only
+        if constexpr (BLOCK == 1024) return launch_policy<T, 8, BLOCK>(t, tune.cache_policy, grid, s);
+        break;
     }
-    return fail(LA_ERR_INVALID_ARG, "unsupported unroll %d", tune.unroll);
+    return fail(LA_ERR_INVALID_ARG, "unsupported unroll %d for workgroups of %d lanes", tune.unroll, BLOCK);
 }
 
 template <typename T>

@@ -56,9 +56,12 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
     if (k >= 2 && m == 1) {
         cls = 0;
         t.cache_policy = fits ? 6 : 3;
-        if (k >= 8) {
+        if (k >= 16) {
             t.block = 1024;
             t.unroll = 4;
+        } else if (k >= 8) {
+            t.block = 1024;
+            t.unroll = 8;
         } else if (k >= 3) {
             t.block = 1024;
             t.unroll = 1;
@@ -79,13 +82,18 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
         } else {
             t.cache_policy = fits ? 4 : 7;
             t.block = 1024;
-            t.unroll = 4;
+            t.unroll = 8;
         }
     } else {
         cls = 1;
         t.cache_policy = 7;
-        t.block = 256;
-        t.unroll = 4;
+        if (k < 8) {
+            t.block = 1024;
+            t.unroll = 1;
+        } else {
+            t.block = 256;
+            t.unroll = 4;
+        }
     }
     if (req.unroll > 0) t.unroll = req.unroll;
     if (req.block > 0) t.block = req.block;
@@ -101,6 +109,7 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
         while (t.unroll > 1 && (uint64_t)t.block * t.unroll > longest_units) t.unroll /= 2;
     if (req.block <= 0)
         if (t.block > 256 && (uint64_t)t.block * t.unroll > longest_units) t.block = 256;
+    if (t.unroll == 8 && t.block != 1024) t.unroll = 4; // 128 KiB tiles exist for 1024 lanes only
     return t;
 }
 } // namespace la
@@ -593,8 +602,8 @@ la_status_t la_tuning_set(const char* key, int value)
     if (!key) return fail(LA_ERR_INVALID_ARG, "la_tuning_set: key is NULL");
     const std::string k(key);
     if (k == "unroll") {
-        if (value != 0 && value != 1 && value != 2 && value != 4)
-            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: unroll must be 0 (auto), 1, 2 or 4");
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+            return fail(LA_ERR_INVALID_ARG, "la_tuning_set: unroll must be 0 (auto), 1, 2, 4 or 8");
         g_unroll.store(value);
         return LA_OK;
     }

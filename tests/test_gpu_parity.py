@@ -123,7 +123,7 @@ def test_small_topologies_ragged_sizes_all_dtypes(oracle, algo, flags):
 
 
 @pytest.mark.parametrize("unroll,nt,block", [(u, nt, b) for u in (1, 2, 4) for nt in range(8) for b in (256, 1024)]
-                         + [(0, -1, 0)])
+                         + [(8, nt, 1024) for nt in range(8)] + [(8, 3, 256), (0, -1, 0)])
 def test_every_launch_shape_gives_the_same_bits(oracle, unroll, nt, block):
     try:
         la.la_tuning_set("unroll", unroll)
@@ -137,6 +137,23 @@ def test_every_launch_shape_gives_the_same_bits(oracle, unroll, nt, block):
     finally:
         la.la_tuning_set("unroll", 0)
         la.la_tuning_set("cache_policy", -1)
+        la.la_tuning_set("block", 0)
+
+
+@pytest.mark.parametrize("kind", ["f32order", "bf16", "i32wrap"])
+def test_largest_tiles_whole_and_ragged(oracle, kind):
+    """128 KiB tiles (8 vectors per lane, 1024 lanes): segments of many whole tiles plus a tail"""
+    try:
+        la.la_tuning_set("unroll", 8)
+        la.la_tuning_set("block", 1024)
+        for algo, topo, n in (("lane", (2, 2, 1), 1000003), ("lane_multiproc", (2, 2, 2), 1500007), ("ring", (1, 2, 1), 300001)):
+            P = topo[0] * topo[1] * topo[2]
+            x = make(P, n, kind, seed=n)
+            got = gpu_allreduce(topo, algo, x)
+            ref = oracle.allreduce(algo, *topo, x)
+            assert np.array_equal(bits(got), bits(ref)), (algo, kind)
+    finally:
+        la.la_tuning_set("unroll", 0)
         la.la_tuning_set("block", 0)
 
 
