@@ -112,7 +112,15 @@ enum {
      * half is S1 + the inter-node reduce-scatter, the second the inter-node all-gather + S3.
      * Not available for recursive doubling, nor for shared buffers with copy-in / copy-out. */
     LA_SCHED_ONLY_REDUCE_SCATTER = 32u,
-    LA_SCHED_ONLY_ALLGATHER = 64u
+    LA_SCHED_ONLY_ALLGATHER = 64u,
+    /* Lane schedules: fold both all-gathers of Algorithm 2 (the one inside the lane all-reduce and
+     * MPI_Allgatherv on the node group) into the store of the inter-node reduce, which then writes
+     * each reduced piece to all N * R rank buffers (k = N, m = N * R; with one node the intra-node
+     * reduce does it: k = R, m = R).  Same sums in the same order, so the result is bit-identical
+     * to the unfused schedule; the launch that re-reads every owner's part to copy it is gone
+     * (N * n elements less to read; the writes are the same).  An emulation-level fusion: between real ranks the
+     * two all-gathers use different networks.  Excludes P2P_GATHER, INNER_RING and the halves. */
+    LA_SCHED_FUSED_GATHER = 128u
 };
 
 /* Step kinds and stage labels reported by la_schedule_step_info. */
@@ -125,6 +133,8 @@ enum {
     LA_STAGE_S2 = 5,       /* S2A and S2B in one launch (multi-destination store) */
     LA_STAGE_S2_RING_RS = 6, /* LA_SCHED_INNER_RING: one reduce iteration of the inter-node rings */
     LA_STAGE_S2_RING_AG = 7, /* LA_SCHED_INNER_RING: one gather iteration of the inter-node rings */
+    LA_STAGE_S2_S3 = 8,    /* LA_SCHED_FUSED_GATHER: inter-node reduce storing to every rank */
+    LA_STAGE_S1_S3 = 9,    /* LA_SCHED_FUSED_GATHER on one node: intra-node reduce storing to every rank */
     LA_STAGE_RING_RS = 10, /* one iteration of the first loop of Algorithm 1 */
     LA_STAGE_RING_AG = 11, /* one iteration of the second loop of Algorithm 1 */
     LA_STAGE_RECURSIVE_DOUBLING = 12, /* one round of recursive doubling */

@@ -45,7 +45,8 @@ Tuning current_tuning()
 //    last-level cache it is read with ordinary loads and the destinations are written with
 //    non-temporal stores, so that the written stream does not evict it;
 //  - reduce with multi-destination store: every source is overwritten in place; ordinary loads,
-//    scope-1 stores.
+//    scope-1 stores.  With many more destinations than sources (LA_SCHED_FUSED_GATHER) the step
+//    behaves like a broadcast and takes its shape: 128 KiB tiles, streaming stores.
 constexpr uint64_t LAST_LEVEL_CACHE_BYTES = 256ull << 20;
 
 Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longest_units, uint64_t bytes_per_operand)
@@ -87,7 +88,12 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
     } else {
         cls = 1;
         t.cache_policy = 7;
-        if (k < 8) {
+        if (m >= 8 && m > k) {
+            // the all-gathers folded into the reduce: store-dominated, like a broadcast
+            t.cache_policy = fits ? 4 : 6;
+            t.block = 1024;
+            t.unroll = 8;
+        } else if (k < 8) {
             t.block = 1024;
             t.unroll = 1;
         } else {

@@ -233,14 +233,22 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
 
     // S1: reduce-scatter on the node group; the owner adds the R node-local copies of its part
     // in ascending node-local index (its own copy taking its place in that order).
+    // LA_SCHED_FUSED_GATHER: the last reduce of a part stores to every rank that the all-gathers
+    // would have copied it to, and the all-gather launches disappear.
+    const bool fused = (s.flags & LA_SCHED_FUSED_GATHER) != 0;
+    const bool s1_is_last = fused && N == 1;
     if (R > 1) {
-        ReduceBuilder rb(s, st, LA_STAGE_S1, R, 1);
+        ReduceBuilder rb(s, st, s1_is_last ? LA_STAGE_S1_S3 : LA_STAGE_S1, R, s1_is_last ? R : 1);
         for (int node = 0; node < N; ++node)
             for (int j = 0; j < J; ++j) {
-                std::vector<Operand> ops(R);
+                std::vector<Operand> ops(R), dsts;
                 for (int l = 0; l < R; ++l) ops[l] = Operand{t.rank_of(node, l), part[j].off};
                 const int me = t.rank_of(node, owner(j));
-                rb.add(part[j].cnt, ops, {Operand{me, part[j].off}}, me);
+                dsts.push_back(Operand{me, part[j].off});
+                if (s1_is_last)
+                    for (int l = 0; l < R; ++l)
+                        if (l != owner(j)) dsts.push_back(Operand{t.rank_of(node, l), part[j].off});
+                rb.add(part[j].cnt, ops, dsts, me);
             }
         rb.emit(s.steps);
     }
@@ -280,7 +288,8 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
     // piece v of the part over the N members in ascending node order, then every member gets
     // every piece.
     if (N > 1 && !inner_ring) {
-        ReduceBuilder rb(s, st, split ? LA_STAGE_S2A : LA_STAGE_S2, N, split ? 1 : N);
+        ReduceBuilder rb(s, st, fused ? LA_STAGE_S2_S3 : split ? LA_STAGE_S2A : LA_STAGE_S2, N,
+                         fused ? N * R : split ? 1 : N);
         Step ag;
         ag.kind = LA_STEP_COPY;
         ag.stage = LA_STAGE_S2B;
@@ -294,6 +303,13 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
                 for (int w = 0; w < N; ++w) ops[w] = Operand{t.rank_of(w, owner(j)), off};
                 const int me = t.rank_of(v, owner(j));
                 dsts.push_back(Operand{me, off});
+                if (fused) { // every rank of every node, the reducing member first
+                    for (int w = 0; w < N; ++w)
+                        for (int l = 0; l < R; ++l)
+                            if (t.rank_of(w, l) != me) dsts.push_back(Operand{t.rank_of(w, l), off});
+                    rb.add(piece.cnt, ops, dsts, me);
+                    continue;
+                }
                 if (split && !p2p && piece.cnt > 0) {
                     ag.len.push_back(piece.cnt);
                     ag.src.push_back(Operand{me, off});
@@ -315,7 +331,7 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
     }
 
     // S3: all-gather on the node group: every owner's part goes to the other R-1 processes.
-    if (R > 1) {
+    if (R > 1 && !fused) {
         Step ag;
         ag.kind = LA_STEP_COPY;
         ag.stage = LA_STAGE_S3;
@@ -396,15 +412,21 @@ void gen_shared_lane(la_schedule& s, Staging& st, int Q)
         const Part ch = split_part(slice.cnt, G, g);
         return Part{slice.off + ch.off, ch.cnt};
     };
+    const bool fused = (s.flags & LA_SCHED_FUSED_GATHER) != 0;
+    const bool s1_is_last = fused && N == 1;
     if (G > 1) {
-        ReduceBuilder rb(s, st, LA_STAGE_S1, G, 1);
+        ReduceBuilder rb(s, st, s1_is_last ? LA_STAGE_S1_S3 : LA_STAGE_S1, G, s1_is_last ? G : 1);
         for (int node = 0; node < N; ++node)
             for (int q = 0; q < Q; ++q)
                 for (int g = 0; g < G; ++g) {
                     const Part c = chunk(q, g);
-                    std::vector<Operand> ops(G);
+                    std::vector<Operand> ops(G), dsts;
                     for (int h = 0; h < G; ++h) ops[h] = Operand{buf(node, h), c.off};
-                    rb.add(c.cnt, ops, {Operand{buf(node, g), c.off}}, buf(node, g));
+                    dsts.push_back(Operand{buf(node, g), c.off});
+                    if (s1_is_last)
+                        for (int h = 0; h < G; ++h)
+                            if (h != g) dsts.push_back(Operand{buf(node, h), c.off});
+                    rb.add(c.cnt, ops, dsts, buf(node, g));
                 }
         rb.emit(s.steps);
     }
@@ -416,7 +438,8 @@ void gen_shared_lane(la_schedule& s, Staging& st, int Q)
                 s.owned[buf(v, g)].push_back(Part{c.off + piece.off, piece.cnt});
             }
     if (N > 1) {
-        ReduceBuilder rb(s, st, split ? LA_STAGE_S2A : LA_STAGE_S2, N, split ? 1 : N);
+        ReduceBuilder rb(s, st, fused ? LA_STAGE_S2_S3 : split ? LA_STAGE_S2A : LA_STAGE_S2, N,
+                         fused ? N * G : split ? 1 : N);
         Step ag;
         ag.kind = LA_STEP_COPY;
         ag.stage = LA_STAGE_S2B;
@@ -431,6 +454,13 @@ void gen_shared_lane(la_schedule& s, Staging& st, int Q)
                     std::vector<Operand> ops(N), dsts;
                     for (int w = 0; w < N; ++w) ops[w] = Operand{buf(w, g), off};
                     dsts.push_back(Operand{buf(v, g), off});
+                    if (fused) {
+                        for (int w = 0; w < N; ++w)
+                            for (int h = 0; h < G; ++h)
+                                if (buf(w, h) != buf(v, g)) dsts.push_back(Operand{buf(w, h), off});
+                        rb.add(piece.cnt, ops, dsts, buf(v, g));
+                        continue;
+                    }
                     if (split && !p2p && piece.cnt > 0) {
                         ag.len.push_back(piece.cnt);
                         ag.src.push_back(Operand{buf(v, g), off});
@@ -449,7 +479,7 @@ void gen_shared_lane(la_schedule& s, Staging& st, int Q)
         rb.emit(s.steps);
         if (split && !ag.len.empty()) s.steps.push_back(std::move(ag));
     }
-    if (G > 1) {
+    if (G > 1 && !fused) {
         Step ag;
         ag.kind = LA_STEP_COPY;
         ag.stage = LA_STAGE_S3;
@@ -617,6 +647,12 @@ la_status_t generate_steps(la_schedule& s)
     s.owned.assign(s.nbuf, {});
     if ((s.flags & LA_SCHED_ONLY_REDUCE_SCATTER) && (s.flags & LA_SCHED_ONLY_ALLGATHER))
         return fail(LA_ERR_INVALID_ARG, "LA_SCHED_ONLY_REDUCE_SCATTER and LA_SCHED_ONLY_ALLGATHER exclude each other");
+    if (s.flags & LA_SCHED_FUSED_GATHER) {
+        if (s.flags & (LA_SCHED_P2P_GATHER | LA_SCHED_INNER_RING | LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER))
+            return fail(LA_ERR_INVALID_ARG, "LA_SCHED_FUSED_GATHER excludes the point-to-point gather, the inner ring and the stand-alone halves");
+        if (s.algo != LA_ALGO_LANE && s.algo != LA_ALGO_LANE_MULTIPROC)
+            return fail(LA_ERR_UNSUPPORTED, "LA_SCHED_FUSED_GATHER applies to the lane schedules only");
+    }
     if ((s.flags & (LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER)) &&
         (s.algo == LA_ALGO_RECURSIVE_DOUBLING ||
          ((s.flags & LA_SCHED_SHARED_BUFFERS) && (s.flags & LA_SCHED_STAGED))))
@@ -779,7 +815,8 @@ la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size
         algo != LA_ALGO_RECURSIVE_DOUBLING && algo != LA_ALGO_RABENSEIFNER)
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown algorithm %d", (int)algo);
     if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED | LA_SCHED_INNER_RING | LA_SCHED_SHARED_BUFFERS |
-                               LA_SCHED_OUT_OF_PLACE | LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER))
+                               LA_SCHED_OUT_OF_PLACE | LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER |
+                               LA_SCHED_FUSED_GATHER))
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown flag bits 0x%x", flags);
     la_schedule* s = new (std::nothrow) la_schedule;
     if (!s) return fail(LA_ERR_OUT_OF_MEMORY, "la_schedule_build: out of host memory");

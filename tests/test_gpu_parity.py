@@ -439,6 +439,24 @@ def test_out_of_place_send_untouched_receive_complete(oracle, algo, extra):
 
 # ------------------------------------------------------------------------------ shared-buffer model
 
+@pytest.mark.parametrize("algo", ["lane", "lane_multiproc"])
+@pytest.mark.parametrize("extra", [0, la.LA_SCHED_STAGED, la.LA_SCHED_SHARED_BUFFERS])
+def test_fused_gather_small_topologies(oracle, algo, extra):
+    cases = [((2, 2, 2), 100003), ((3, 2, 1), 40961), ((1, 3, 2), 7), ((2, 1, 3), 12289), ((1, 1, 1), 100),
+             ((2, 3, 2), 5), ((4, 2, 2), 262147), ((1, 4, 2), 300007)]
+    for (topo, n), kind in itertools.product(cases, ("i32wrap", "f32order", "bf16")):
+        N, G, Q = topo
+        B = N * G if extra & la.LA_SCHED_SHARED_BUFFERS else N * G * Q
+        x = make(B, n, kind, seed=n)
+        print("fused case", algo, extra, topo, n, kind, flush=True)
+        got = gpu_allreduce(topo, algo, x, la.LA_SCHED_FUSED_GATHER | extra)
+        if extra & la.LA_SCHED_SHARED_BUFFERS:
+            ref = oracle.allreduce("lane_multiproc", N, G, 1 if algo == "lane" else Q, x, shared=True)
+        else:
+            ref = oracle.allreduce(algo, N, G, Q, x)
+        assert np.array_equal(bits(got), bits(ref)), (algo, extra, topo, n, kind)
+
+
 RS, AG = la.LA_SCHED_ONLY_REDUCE_SCATTER, la.LA_SCHED_ONLY_ALLGATHER
 
 
@@ -681,6 +699,18 @@ def test_config3_inner_ring(oracle):
 
 def test_config5_scale_out_inner_ring(oracle):
     full_size_case(oracle, (32, 4, 8), "lane_multiproc", 1 << 20, "uniform_pm1", flags=la.LA_SCHED_INNER_RING)
+
+
+def test_config2_fused_gather(oracle):
+    full_size_case(oracle, (4, 4, 1), "lane", 1 << 24, "normal", flags=la.LA_SCHED_FUSED_GATHER)
+
+
+def test_config4_fused_gather(oracle):
+    full_size_case(oracle, (2, 4, 2), "lane_multiproc", 1 << 27, "normal_bf16", flags=la.LA_SCHED_FUSED_GATHER)
+
+
+def test_config5_fused_gather_fan_out_1024(oracle):
+    full_size_case(oracle, (32, 4, 8), "lane_multiproc", 1 << 20, "uniform_pm1", flags=la.LA_SCHED_FUSED_GATHER, tol=False)
 
 
 def test_config5_scale_out_point_to_point_gather(oracle):

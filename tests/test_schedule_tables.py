@@ -67,7 +67,12 @@ def test_schedule_build_errors():
         (dict(algo="lane", n=0, dtype="float32"), la.LA_ERR_INVALID_ARG),
         (dict(algo=9, n=16, dtype="float32"), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype=9), la.LA_ERR_UNSUPPORTED),
-        (dict(algo="lane", n=16, dtype="float32", flags=128), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=256), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="ring", n=16, dtype="float32", flags=128), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="rabenseifner", n=16, dtype="float32", flags=128), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=128 | 1), la.LA_ERR_INVALID_ARG),
+        (dict(algo="lane", n=16, dtype="float32", flags=128 | 4), la.LA_ERR_INVALID_ARG),
+        (dict(algo="lane", n=16, dtype="float32", flags=128 | 32), la.LA_ERR_INVALID_ARG),
         (dict(algo="lane", n=16, dtype="float32", flags=1 << 20), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype="float32", flags=32 | 64), la.LA_ERR_INVALID_ARG),
         (dict(algo="recursive_doubling", n=16, dtype="float32", flags=32), la.LA_ERR_UNSUPPORTED),
@@ -163,6 +168,27 @@ def bf16_narrow(x32):
     return torch.from_numpy(x32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
 
 
+def sum_in_order(ops):
+    """one segment: the operands added in table order (uint16 = bf16 bits: fp32 accumulation, one
+    rounding at the end; int32 wraps)"""
+    if ops[0].dtype == np.uint16:
+        if len(ops) == 1:
+            return ops[0].copy()
+        acc = (ops[0].astype(np.uint32) << 16).view(np.float32)
+        for x in ops[1:]:
+            acc = acc + (x.astype(np.uint32) << 16).view(np.float32)
+        return bf16_narrow(np.ascontiguousarray(acc))
+    if ops[0].dtype == np.int32:
+        acc = ops[0].view(np.uint32).copy()
+        for x in ops[1:]:
+            acc = acc + x.view(np.uint32)
+        return acc.view(np.int32)
+    acc = ops[0].copy()
+    for x in ops[1:]:
+        acc = acc + x
+    return acc
+
+
 def run_tables(sched, inputs, snapshot=True, upto=None):
     """Execute the step tables on host arrays.  With snapshot=True every step reads the state
     from before the step (what concurrent workgroups see if the step is hazard-free)."""
@@ -175,21 +201,7 @@ def run_tables(sched, inputs, snapshot=True, upto=None):
         for g in range(t["num_segments"]):
             ln = int(t["seg_len"][g])
             ops = [old[int(b)][int(o):int(o) + ln] for b, o in zip(t["src_buf"][g], t["src_off"][g])]
-            if inputs.dtype == np.uint16:
-                acc = (ops[0].astype(np.uint32) << 16).view(np.float32)
-                for x in ops[1:]:
-                    acc = acc + (x.astype(np.uint32) << 16).view(np.float32)
-                res = bf16_narrow(np.ascontiguousarray(acc))
-            elif inputs.dtype == np.int32:
-                acc = ops[0].view(np.uint32).copy()
-                for x in ops[1:]:
-                    acc = acc + x.view(np.uint32)
-                res = acc.view(np.int32)
-            else:
-                acc = ops[0].copy()
-                for x in ops[1:]:
-                    acc = acc + x
-                res = acc
+            res = sum_in_order(ops)
             for b, o in zip(t["dst_buf"][g], t["dst_off"][g]):
                 state[int(b)][int(o):int(o) + ln] = res
     return np.stack(state[:P])
@@ -300,16 +312,7 @@ def run_tables_out_of_place(sched, inputs):
         for g in range(t["num_segments"]):
             ln = int(t["seg_len"][g])
             ops = [old[int(b)][int(o):int(o) + ln] for b, o in zip(t["src_buf"][g], t["src_off"][g])]
-            if inputs.dtype == np.int32:
-                acc = ops[0].view(np.uint32).copy()
-                for x in ops[1:]:
-                    acc = acc + x.view(np.uint32)
-                res = acc.view(np.int32)
-            else:
-                acc = ops[0].copy()
-                for x in ops[1:]:
-                    acc = acc + x
-                res = acc
+            res = sum_in_order(ops)
             for b, o in zip(t["dst_buf"][g], t["dst_off"][g]):
                 state[int(b)][int(o):int(o) + ln] = res
     return np.stack(state[:B]), np.stack(state[B + 1:])
@@ -388,6 +391,62 @@ def test_small_message_algorithm_shapes():
         assert err.value.status == la.LA_ERR_UNSUPPORTED
         with pytest.raises(la.LaError):
             la.la_schedule_build(t, algo, n, "float32", la.LA_SCHED_SHARED_BUFFERS)
+
+
+# ----------------------------------------------------------------------------- fused all-gathers
+
+FUSED = la.LA_SCHED_FUSED_GATHER
+
+
+@pytest.mark.parametrize("algo", ["lane", "lane_multiproc"])
+@pytest.mark.parametrize("extra", [0, la.LA_SCHED_STAGED, la.LA_SCHED_OUT_OF_PLACE, SHARED, SHARED | la.LA_SCHED_STAGED])
+def test_fused_gather_tables_reproduce_oracle_bitwise(oracle, algo, extra):
+    """With the all-gathers folded into the last reduce's store the result is still the oracle's,
+    bit for bit, and the schedule has no copy launch left (staging and input copies aside)."""
+    for (N, G, Q) in TOPOS:
+        topo = la.la_topology_create(N, G, Q)
+        B = N * G if extra & SHARED else N * G * Q
+        for n in (1, 5, 17, 40):
+            for x in (np.random.default_rng(n).integers(-(1 << 31), 1 << 31, size=(B, n), dtype=np.int64).astype(np.int32),
+                      synth.order_sensitive_f32(B, n), synth.to_bf16_bits(synth.order_sensitive_f32(B, n) * np.float32(2.0 ** -20))):
+                dt = {np.dtype(np.int32): "int32", np.dtype(np.float32): "float32", np.dtype(np.uint16): "bfloat16"}[x.dtype]
+                sched = la.la_schedule_build(topo, algo, n, dt, FUSED | extra)
+                if extra & SHARED:
+                    ref = oracle.allreduce("lane_multiproc", N, G, 1 if algo == "lane" else Q, x, shared=True)
+                else:
+                    ref = oracle.allreduce(algo, N, G, Q, x)
+                if extra & la.LA_SCHED_OUT_OF_PLACE:
+                    got, send = run_tables_out_of_place(sched, x)
+                    assert np.array_equal(send.view(np.uint8), x.view(np.uint8))
+                else:
+                    got = run_tables(sched, x)
+                    assert np.array_equal(run_tables(sched, x, snapshot=False).view(np.uint8), got.view(np.uint8))
+                assert np.array_equal(got.view(np.uint8), ref.view(np.uint8)), (algo, extra, N, G, Q, n, dt)
+                stages = [st["stage_name"] for st in sched.steps()]
+                assert not {"S2b", "S3", "S2"} & set(stages)
+                if not extra:
+                    R = G * Q
+                    assert stages == ([] if R == 1 and N == 1 else ["S1+S3"] if N == 1 else (["S1"] if R > 1 else []) + ["S2+S3"])
+
+
+def test_fused_gather_shapes_and_bytes():
+    """C2 shape: S1 (4 -> 1) and one launch with k = N sources and m = N * R destinations; the
+    bytes are those of the unfused schedule minus S3's read of every owner's part."""
+    n, e = 1 << 20, 4
+    N, G, Q = 4, 4, 1
+    P, R = N * G * Q, G * Q
+    t = la.la_topology_create(N, G, Q)
+    fused = la.la_schedule_build(t, "lane", n, "float32", FUSED)
+    plain = la.la_schedule_build(t, "lane", n, "float32")
+    assert [(x["stage_name"], x["fan_in"], x["fan_out"], x["num_segments"]) for x in fused.steps()] == \
+        [("S1", R, 1, N * G), ("S2+S3", N, N * R, G * N)]
+    rf, wf = totals(fused)
+    rp, wp = totals(plain)
+    assert (rf, wf) == ((P + N) * n * e, (N + P) * n * e)
+    assert rp - rf == N * n * e          # S3 no longer re-reads the owners' parts
+    assert wp == wf                      # every buffer is still written once per all-gathered element
+    one = la.la_schedule_build(la.la_topology_create(1, 4, 2), "lane_multiproc", n, "float32", FUSED)
+    assert [(x["stage_name"], x["fan_in"], x["fan_out"]) for x in one.steps()] == [("S1+S3", 8, 8)]
 
 
 # ----------------------------------------------------------------------------- stand-alone halves
