@@ -24,9 +24,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # file (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors calibrated on the ring's plain-copy launches
 # of known size; profiles/seg_reduce_kernel_c2_lane_pmc.md).  Keyed by (config, algo, flags, stage).
 MEASURED_TRAFFIC = {
-    ("c2", "lane", 0, "S1"): 1342246093,
-    ("c2", "lane", 0, "S2"): 536945664,
-    ("c2", "lane", 0, "S3"): 1075078348,
+    ("c2", "lane", 0, "S1"): 1342241997,
+    ("c2", "lane", 0, "S2"): 536937472,
+    ("c2", "lane", 0, "S3"): 1074858496,
 }
 
 CONFIGS = {
@@ -251,6 +251,15 @@ def main():
                                   "GBps": round(rbytes / (rms * 1e-3) / 1e9, 1),
                                   "allreduce_bytes_per_s_per_rank": round(n * e / (rms * 1e-3), 1),
                                   "lane_speedup_over_ring": round(rms / ms, 3)}
+    if algo in ("lane", "lane_multiproc") and args.flags == 0 and not args.no_ring:
+        # the same all-reduce with both all-gathers folded into the last reduce's store
+        fz = la.la_schedule_build(topo, algo, n, cfg["dtype"], la.LA_SCHED_FUSED_GATHER)
+        fbytes = sum(s["bytes_read"] + s["bytes_written"] for s in fz.steps())
+        fk = max(3, args.steps // 2)
+        fms, _, _ = time_schedule(la, torch, fz, bufs, fk, 1)
+        out["fused_gather_variant"] = {"ms_per_allreduce": round(fms, 5), "launches": fz.num_steps, "steps_timed": fk,
+                                       "algorithmic_bytes": fbytes, "GBps": round(fbytes / (fms * 1e-3) / 1e9, 1),
+                                       "allreduce_bytes_per_s_per_rank": round(n * e / (fms * 1e-3), 1)}
     del bufs, slab
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
