@@ -54,6 +54,7 @@ def parse():
     ap.add_argument("--flags", type=int, default=0, help="LA_SCHED_* bits: 1 = point-to-point gather, 2 = staged")
     ap.add_argument("--unroll", type=int, default=None)
     ap.add_argument("--cache-policy", type=int, default=None)
+    ap.add_argument("--block", type=int, default=None, help="lanes per workgroup for every step: 256 or 1024")
     ap.add_argument("--skew", type=int, default=0, help="extra bytes between consecutive rank buffers")
     ap.add_argument("--flush-cache", action="store_true",
                     help="overwrite a 1 GiB scratch buffer before every timed all-reduce, so that nothing "
@@ -178,6 +179,8 @@ def main():
         la.la_tuning_set("unroll", args.unroll)
     if args.cache_policy is not None:
         la.la_tuning_set("cache_policy", args.cache_policy)
+    if args.block is not None:
+        la.la_tuning_set("block", args.block)
     N, G, Q = cfg["topo"]
     P, n = N * G * Q, cfg["n"]
     e = la.ELEM_SIZE[la.DTYPES[cfg["dtype"]]]
