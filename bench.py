@@ -90,6 +90,29 @@ def device_buffers(x, skew_bytes):
     return bufs, slab
 
 
+def plain_copy_ceiling(torch, dominant_gbs):
+    """What a plain device-to-device copy of 1 GiB (torch's own copy kernel, 2 GiB of traffic,
+    nothing cache-resident) reaches on this GPU, measured here: the second reference, beside the
+    published peak, for the dominant kernel's rate."""
+    a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").uniform_(-1, 1)
+    b = torch.empty_like(a)
+    for _ in range(2):
+        b.copy_(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 10
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    gbs = 2 * a.numel() * 4 * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del a, b
+    torch.cuda.empty_cache()
+    return {"plain_copy_GBps": round(gbs, 1), "what": "torch device copy of 1 GiB (read + write bytes)",
+            "dominant_kernel_over_plain_copy": round(dominant_gbs / gbs, 3)}
+
+
 def time_schedule(la, torch, sched, bufs, steps, warmup, flush=None):
     """W warm-up all-reduces, then K timed ones with an event after every launch."""
     stream = torch.cuda.current_stream()
@@ -254,6 +277,8 @@ def main():
                                   "GBps": round(rbytes / (rms * 1e-3) / 1e9, 1),
                                   "allreduce_bytes_per_s_per_rank": round(n * e / (rms * 1e-3), 1),
                                   "lane_speedup_over_ring": round(rms / ms, 3)}
+    if not args.no_ring:
+        out["achievable"] = plain_copy_ceiling(torch, dom_gbs)
     if algo in ("lane", "lane_multiproc") and args.flags == 0 and not args.no_ring:
         # the same all-reduce with both all-gathers folded into the last reduce's store
         fz = la.la_schedule_build(topo, algo, n, cfg["dtype"], la.LA_SCHED_FUSED_GATHER)

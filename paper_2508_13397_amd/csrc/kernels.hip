@@ -370,7 +370,7 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
 #pragma unroll
         for (int b = 0; b < KBATCH; ++b) {
             const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[t + b], tile_off, tile_bytes);
-            const bool ip = (in_place >> ((t + b) & 63u)) & 1u;
+            const bool ip = t + b < 64u && ((in_place >> (t + b)) & 1u); // the mask covers 64 sources
 #pragma unroll
             for (int u = 0; u < U; ++u) x[b][u] = load_src<P>(r, off[u], ip);
         }
@@ -388,7 +388,7 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
         for (int b = 0; b < KBATCH - 1; ++b) {
             if ((uint32_t)b < rem) {
                 const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[t + b], tile_off, tile_bytes);
-                const bool ip = (in_place >> ((t + b) & 63u)) & 1u;
+                const bool ip = t + b < 64u && ((in_place >> (t + b)) & 1u); // the mask covers 64 sources
 #pragma unroll
                 for (int u = 0; u < U; ++u) x[b][u] = load_src<P>(r, off[u], ip);
             }
