@@ -282,6 +282,50 @@ def test_side_stream_rebinding_and_repeated_calls(oracle):
     assert np.array_equal(bits(np.stack([to_host(v) for v in b])), bits(oracle.allreduce("lane_multiproc", *topo, rolled)))
 
 
+def test_two_host_threads_with_their_own_schedules_and_streams(oracle):
+    """Handles are independent: two host threads, each with its own schedule, buffers and stream,
+    call the library at the same time (ctypes releases the interpreter lock during the call);
+    la_reduce_segments calls from both share the library's pinned upload pool."""
+    import threading
+
+    cases = [("lane_multiproc", (2, 2, 2), 90001, "f32order"), ("ring", (3, 2, 1), 50021, "bf16")]
+    inputs = [make(t[0] * t[1] * t[2], n, kind, seed=n) for _, t, n, kind in cases]
+    results, errors = [None, None], []
+
+    def work(i):
+        try:
+            algo, topo, n, _ = cases[i]
+            x = inputs[i]
+            stream = torch.cuda.Stream()
+            sched = la.la_schedule_build(la.la_topology_create(*topo), algo, n, NAME[x.dtype])
+            outs = []
+            for _ in range(20):
+                with torch.cuda.stream(stream):
+                    bufs = [to_dev(x[r]) for r in range(x.shape[0])]
+                    la.allreduce_tensors(sched, bufs, stream)
+                    extra = torch.zeros(1024, dtype=torch.float32, device="cuda")
+                    ones = torch.ones(1024, dtype=torch.float32, device="cuda")
+                    la.la_reduce_segments(extra.data_ptr(), [ones.data_ptr()] * 1, [0, 512], 512, "float32", la.LA_SUM,
+                                          stream.cuda_stream)
+                stream.synchronize()
+                assert torch.equal(extra, ones)
+                outs.append(np.stack([to_host(b) for b in bufs]))
+            results[i] = outs
+        except Exception as exc:  # reported by the main thread
+            errors.append((i, repr(exc)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    for i, (algo, topo, n, _) in enumerate(cases):
+        ref = oracle.allreduce(algo, *topo, inputs[i])
+        for got in results[i]:
+            assert np.array_equal(bits(got), bits(ref)), (algo, topo)
+
+
 @pytest.mark.parametrize("algo,flags,topo", [("ring", 0, (4, 2, 2)), ("lane_multiproc", la.LA_SCHED_INNER_RING, (6, 2, 2))])
 def test_graph_replays_match_step_by_step_launches(oracle, algo, flags, topo):
     """Schedules with many launches are replayed as one HIP graph.  Replay it several times, with
