@@ -64,8 +64,9 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
             t.block = 1024;
             t.unroll = 8;
         } else if (k >= 3) {
+            // operands that stream from DRAM want long runs; cache-resident ones small tiles
             t.block = 1024;
-            t.unroll = 1;
+            t.unroll = fits ? 1 : 8;
         } else {
             t.block = 256;
             t.unroll = 4;
@@ -78,8 +79,8 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
             t.unroll = 4;
         } else if (m <= 4) {
             t.cache_policy = fits ? 4 : 7;
-            t.block = 256;
-            t.unroll = 1;
+            t.block = fits ? 256 : 1024;
+            t.unroll = fits ? 1 : 4;
         } else {
             t.cache_policy = fits ? 4 : 7;
             t.block = 1024;
@@ -97,7 +98,7 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
             t.block = 1024;
             t.unroll = 1;
         } else {
-            t.block = 256;
+            t.block = fits ? 256 : 1024;
             t.unroll = 4;
         }
     }
