@@ -40,6 +40,11 @@ CONFIGS = {
                name="C4: 2 nodes x 4 GPUs x 2 procs = 16 ranks, bf16 in / fp32 acc, 128 Mi elements (256 MiB) per rank"),
     "c5": dict(topo=(32, 4, 8), algo="lane_multiproc", n=1 << 20, dist="uniform_pm1", dtype="float32",
                name="C5: 32 nodes x 4 GPUs x 8 procs = 1024 ranks, fp32 SUM, 1 Mi elements (4 MiB) per rank"),
+    # the size the paper's 8-node runs are quoted on, in the shared-buffer model (one buffer per GPU,
+    # 16 processes per GPU on slices of it): 32 buffers of 512 MiB
+    "paper8": dict(topo=(8, 4, 16), algo="lane_multiproc", n=1 << 27, dist="uniform_pm1", dtype="float32", flags=8,
+                   name="paper size: 8 nodes x 4 GPUs, 2^27 fp32 (512 MiB) per GPU buffer, 16 processes per GPU "
+                        "sharing it (multi-lane approach; --algo ring = standard approach)"),
 }
 DTYPE_TAG = {"float32": "f32", "int32": "i32", "bfloat16": "bf16 in, f32 accumulate"}
 
@@ -146,20 +151,20 @@ def time_schedule(la, torch, sched, bufs, steps, warmup, flush=None):
     return wall_ms, per_step_ms, (t3 - t2) / steps * 1e3
 
 
-def cpu_baseline(cfg, algo, total_bytes_full):
+def cpu_baseline(cfg, algo, total_bytes_full, shared=False):
     """The oracle as it stands, on the host cores, on a bounded sample of the workload."""
     import oracle
     from paper_2508_13397_amd import synth
 
     N, G, Q = cfg["topo"]
-    P = N * G * Q
+    P = N * G if shared else N * G * Q
     threads = min(oracle.max_threads(), os.cpu_count() or 1, 16)
     oracle.set_threads(threads)
     n = cfg["n"]
     sample_n = max(n // 16, 1024)
     x = synth.make_inputs(P, sample_n, cfg["dist"])
     t0 = time.perf_counter()
-    oracle.allreduce(algo, N, G, Q, x, in_place=True)
+    oracle.allreduce(algo, N, G, Q, x, in_place=True, shared=shared)
     dt = time.perf_counter() - t0
     frac = sample_n / n
     if dt / frac < 25.0 and sample_n < n:  # the full workload fits the time budget: time that instead
@@ -168,7 +173,7 @@ def cpu_baseline(cfg, algo, total_bytes_full):
         runs, spent = [], 0.0
         while len(runs) < 3 and spent < 12.0:  # repeat a short run for a steadier figure
             t0 = time.perf_counter()
-            oracle.allreduce(algo, N, G, Q, x, in_place=True)
+            oracle.allreduce(algo, N, G, Q, x, in_place=True, shared=shared)
             runs.append(time.perf_counter() - t0)
             spent += runs[-1]
         dt = sum(runs) / len(runs)
@@ -205,7 +210,9 @@ def main():
     if args.block is not None:
         la.la_tuning_set("block", args.block)
     N, G, Q = cfg["topo"]
-    P, n = N * G * Q, cfg["n"]
+    args.flags |= cfg.get("flags", 0)
+    shared = bool(args.flags & la.LA_SCHED_SHARED_BUFFERS)
+    P, n = (N * G if shared else N * G * Q), cfg["n"]   # number of buffers
     e = la.ELEM_SIZE[la.DTYPES[cfg["dtype"]]]
 
     x = synth.make_inputs(P, n, cfg["dist"], workers=16)
@@ -250,7 +257,7 @@ def main():
         "dtype": DTYPE_TAG[cfg["dtype"]],
         "data": "synthetic",
         "config": {"workload": cfg["name"], "config_id": args.config, "algo": algo, "schedule_flags": args.flags,
-                   "virtual_ranks": P, "elements_per_rank": n, "launches_per_allreduce": len(info),
+                   "virtual_ranks": N * G * Q, "buffers": P, "elements_per_rank": n, "launches_per_allreduce": len(info),
                    "unroll": la.la_tuning_get("unroll"), "cache_policy": la.la_tuning_get("cache_policy"),
                    "skew_bytes": args.skew, "flush_cache_between_allreduces": bool(args.flush_cache)},
         "pct_of_hbm_peak": round(total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS * 100, 2),
@@ -279,9 +286,9 @@ def main():
                                   "lane_speedup_over_ring": round(rms / ms, 3)}
     if not args.no_ring:
         out["achievable"] = plain_copy_ceiling(torch, dom_gbs)
-    if algo in ("lane", "lane_multiproc") and args.flags == 0 and not args.no_ring:
+    if algo in ("lane", "lane_multiproc") and (args.flags & ~la.LA_SCHED_SHARED_BUFFERS) == 0 and not args.no_ring:
         # the same all-reduce with both all-gathers folded into the last reduce's store
-        fz = la.la_schedule_build(topo, algo, n, cfg["dtype"], la.LA_SCHED_FUSED_GATHER)
+        fz = la.la_schedule_build(topo, algo, n, cfg["dtype"], args.flags | la.LA_SCHED_FUSED_GATHER)
         fbytes = sum(s["bytes_read"] + s["bytes_written"] for s in fz.steps())
         fk = max(3, args.steps // 2)
         fms, _, _ = time_schedule(la, torch, fz, bufs, fk, 1)
@@ -291,7 +298,7 @@ def main():
     del bufs, slab
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, algo, total_bytes)
+        out["cpu_baseline"] = cpu_baseline(cfg, algo, total_bytes, shared)
     print(json.dumps(out), flush=True)
 
 

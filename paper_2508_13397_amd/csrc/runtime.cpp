@@ -68,14 +68,14 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
             t.block = 1024;
             t.unroll = fits ? 1 : 8;
         } else {
-            t.block = 256;
+            t.block = fits ? 256 : 1024; // short launches start and drain faster with small workgroups
             t.unroll = 4;
         }
     } else if (k == 1) {
         cls = 2;
         if (m == 1) {
             t.cache_policy = 6;
-            t.block = 256;
+            t.block = fits ? 256 : 1024;
             t.unroll = 4;
         } else if (m <= 4) {
             t.cache_policy = fits ? 4 : 7;

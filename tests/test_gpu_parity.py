@@ -651,6 +651,32 @@ def test_shared_buffers_full_size_16_gpus_4_procs_64Mi_fp32(oracle, algo, extra)
 
 # ------------------------------------------------------------------------------ la_reduce_segments
 
+@pytest.mark.parametrize("algo,extra", [("lane_multiproc", 0), ("lane_multiproc", la.LA_SCHED_FUSED_GATHER), ("ring", 0)])
+def test_paper_size_8_nodes_4_gpus_16_procs_128Mi_fp32(oracle, algo, extra):
+    """The size the paper's Delta runs are quoted on (Results: 2^27 floats per GPU, 8 nodes of 4
+    GPUs, up to 16 processes per GPU), shared-buffer model: 32 buffers of 512 MiB resident."""
+    N, G, Q, n = 8, 4, 16, 1 << 27
+    B = N * G
+    print("generating", B, "x", n, flush=True)
+    x = synth.make_inputs(B, n, "uniform_pm1", workers=16)
+    sched = la.la_schedule_build(la.la_topology_create(N, G, Q), algo, n, "float32", SHARED | extra)
+    bufs = [to_dev(x[b]) for b in range(B)]
+    print("running", algo, extra, flush=True)
+    la.allreduce_tensors(sched, bufs)
+    torch.cuda.synchronize()
+    got0 = to_host(bufs[0])
+    for b in range(1, B):
+        assert torch.equal(bufs[b].view(torch.int32), bufs[0].view(torch.int32)), b
+    del bufs
+    torch.cuda.empty_cache()
+    idx = np.unique(np.concatenate([np.arange(0, 4096), np.arange(n - 4096, n), np.random.default_rng(2).integers(0, n, 100000)]))
+    check_tolerance(oracle, np.ascontiguousarray(x[:, idx]), got0[idx])
+    print("oracle", flush=True)
+    oracle.set_threads(min(16, oracle.max_threads()))
+    ref = oracle.allreduce(algo, N, G, Q, x, in_place=True, shared=True)
+    assert np.array_equal(bits(got0), bits(ref[0]))
+
+
 @pytest.mark.parametrize("kind", ["i32wrap", "f32order", "bf16"])
 def test_reduce_segments_matches_oracle(oracle, kind):
     n = 200000
