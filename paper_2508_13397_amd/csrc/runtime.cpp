@@ -44,6 +44,9 @@ Tuning current_tuning()
 //  - copy / broadcast (k == 1): the source was produced by the previous launch.  If it fits the
 //    last-level cache it is read with ordinary loads and the destinations are written with
 //    non-temporal stores, so that the written stream does not evict it;
+//  - tiles: an operand stream that exceeds the last-level cache comes from DRAM and wants long
+//    contiguous runs per workgroup (64..128 KiB); one that the previous launch left in the cache
+//    is served faster in small tiles (16 KiB) by many workgroups;
 //  - reduce with multi-destination store: every source is overwritten in place; ordinary loads,
 //    scope-1 stores.  With many more destinations than sources (LA_SCHED_FUSED_GATHER) the step
 //    behaves like a broadcast and takes its shape: 128 KiB tiles, streaming stores.
@@ -299,6 +302,10 @@ la_status_t check_buffers(const la_schedule& s, void* const* bufs, const void* c
     return LA_OK;
 }
 
+// Serialises the library's synchronous device calls (allocation, table upload) with its graph
+// captures, across all schedules of the process.
+std::mutex g_device_mu;
+
 // Make sched.bound describe `addr` on the current device with the current tile shape.
 la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning& tune)
 {
@@ -308,6 +315,7 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     const int P = s.nbuf;
     const std::vector<uint64_t> key = addr; // caller addresses only: the staging slot is still 0
     if (b && b->device == dev && b->requested == tune && b->bufs == key) return LA_OK;
+    std::lock_guard<std::mutex> device_lock(g_device_mu); // not while another schedule records its graph
     if (b && b->used) LA_HIP(hipEventSynchronize(b->last_use)); // earlier work still reads the tables
     if (b && b->device != dev) {
         release_binding(b);
@@ -360,8 +368,14 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
 // captured (no memset or copy nodes).  On failure the binding falls back to stream launches.
 la_status_t capture_graph(const la_schedule_t* sched, la_binding* b, uint32_t op)
 {
+    // Relaxed mode: the capture holds nothing but this library's kernel launches on a private
+    // stream, so other threads (the caller's allocator, another schedule's table upload) need not
+    // be kept from synchronous calls while it runs; in the stricter modes such a call in another
+    // thread was seen to fail and to invalidate the capture.  The library's own synchronous device
+    // calls are kept out of the window by g_device_mu as well.
+    std::lock_guard<std::mutex> device_lock(g_device_mu);
     if (!b->capture_stream) LA_HIP(hipStreamCreateWithFlags(&b->capture_stream, hipStreamNonBlocking));
-    LA_HIP(hipStreamBeginCapture(b->capture_stream, hipStreamCaptureModeThreadLocal));
+    LA_HIP(hipStreamBeginCapture(b->capture_stream, hipStreamCaptureModeRelaxed));
     la_status_t st = LA_OK;
     for (size_t i = 0; i < b->step.size() && st == LA_OK; ++i) {
         StepTable t = b->step[i];

@@ -288,17 +288,20 @@ def test_two_host_threads_with_their_own_schedules_and_streams(oracle):
     la_reduce_segments calls from both share the library's pinned upload pool."""
     import threading
 
-    cases = [("lane_multiproc", (2, 2, 2), 90001, "f32order"), ("ring", (3, 2, 1), 50021, "bf16")]
-    inputs = [make(t[0] * t[1] * t[2], n, kind, seed=n) for _, t, n, kind in cases]
+    # both schedules have 8 or more launches, so both threads record and replay graphs, and every
+    # iteration allocates new buffers, so both rebind (table upload) and record again all the time
+    cases = [("lane_multiproc", (4, 2, 2), 90001, "f32order", la.LA_SCHED_INNER_RING), ("ring", (3, 2, 1), 50021, "bf16", 0)]
+    inputs = [make(t[0] * t[1] * t[2], n, kind, seed=n) for _, t, n, kind, _ in cases]
     results, errors = [None, None], []
 
     def work(i):
         try:
-            algo, topo, n, _ = cases[i]
+            algo, topo, n, _, flags = cases[i]
             x = inputs[i]
             stream = torch.cuda.Stream()
-            sched = la.la_schedule_build(la.la_topology_create(*topo), algo, n, NAME[x.dtype])
-            outs = []
+            sched = la.la_schedule_build(la.la_topology_create(*topo), algo, n, NAME[x.dtype], flags)
+            assert sched.num_steps >= 8
+            outs, keep = [], []
             for _ in range(20):
                 with torch.cuda.stream(stream):
                     bufs = [to_dev(x[r]) for r in range(x.shape[0])]
@@ -310,6 +313,7 @@ def test_two_host_threads_with_their_own_schedules_and_streams(oracle):
                 stream.synchronize()
                 assert torch.equal(extra, ones)
                 outs.append(np.stack([to_host(b) for b in bufs]))
+                keep.append(bufs)  # the next iteration gets other addresses
             results[i] = outs
         except Exception as exc:  # reported by the main thread
             errors.append((i, repr(exc)))
@@ -320,8 +324,8 @@ def test_two_host_threads_with_their_own_schedules_and_streams(oracle):
     for th in threads:
         th.join()
     assert not errors, errors
-    for i, (algo, topo, n, _) in enumerate(cases):
-        ref = oracle.allreduce(algo, *topo, inputs[i])
+    for i, (algo, topo, n, _, flags) in enumerate(cases):
+        ref = oracle.allreduce(oracle_name(algo, flags), *topo, inputs[i])
         for got in results[i]:
             assert np.array_equal(bits(got), bits(ref)), (algo, topo)
 
