@@ -295,6 +295,13 @@ def main():
         out["fused_gather_variant"] = {"ms_per_allreduce": round(fms, 5), "launches": fz.num_steps, "steps_timed": fk,
                                        "algorithmic_bytes": fbytes, "GBps": round(fbytes / (fms * 1e-3) / 1e9, 1),
                                        "allreduce_bytes_per_s_per_rank": round(n * e / (fms * 1e-3), 1)}
+        # and the whole of Algorithm 2 as one two-level reduce launch
+        one = la.la_schedule_build(topo, algo, n, cfg["dtype"], args.flags | la.LA_SCHED_SINGLE_LAUNCH)
+        obytes = sum(s["bytes_read"] + s["bytes_written"] for s in one.steps())
+        oms, _, _ = time_schedule(la, torch, one, bufs, fk, 1)
+        out["single_launch_variant"] = {"ms_per_allreduce": round(oms, 5), "launches": one.num_steps, "steps_timed": fk,
+                                        "algorithmic_bytes": obytes, "GBps": round(obytes / (oms * 1e-3) / 1e9, 1),
+                                        "allreduce_bytes_per_s_per_rank": round(n * e / (oms * 1e-3), 1)}
     del bufs, slab
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:

@@ -120,7 +120,17 @@ enum {
      * to the unfused schedule; the launch that re-reads every owner's part to copy it is gone
      * (N * n elements less to read; the writes are the same).  An emulation-level fusion: between real ranks the
      * two all-gathers use different networks.  Excludes P2P_GATHER, INNER_RING and the halves. */
-    LA_SCHED_FUSED_GATHER = 128u
+    LA_SCHED_FUSED_GATHER = 128u,
+    /* Lane schedules: the whole of Algorithm 2 as ONE launch.  Piece v of part j is computed as a
+     * two-level sum straight from the inputs: for every node, its R rank buffers in ascending
+     * node-local index (what MPI_Reduce_scatter on the node group leaves at the owner, rounded to
+     * the element type as that result is when it is stored), then the node results in ascending
+     * node order (the lane all-reduce); the result is stored to all N * R rank buffers (both
+     * all-gathers).  k = m = N * R, la_schedule_step_group() = R.  Bit-identical to the staged
+     * schedule; every input is read once and every output written once, the lower bound of the
+     * definition.  Like LA_SCHED_FUSED_GATHER a fusion of the emulation, not of the algorithm.
+     * Combines only with LA_SCHED_SHARED_BUFFERS and LA_SCHED_OUT_OF_PLACE. */
+    LA_SCHED_SINGLE_LAUNCH = 256u
 };
 
 /* Step kinds and stage labels reported by la_schedule_step_info. */
@@ -140,6 +150,7 @@ enum {
     LA_STAGE_RECURSIVE_DOUBLING = 12, /* one round of recursive doubling */
     LA_STAGE_RABENSEIFNER_RS = 13,    /* one halving round of Rabenseifner's reduce-scatter */
     LA_STAGE_RABENSEIFNER_AG = 14,    /* one doubling round of Rabenseifner's all-gather */
+    LA_STAGE_S1_S2_S3 = 15, /* LA_SCHED_SINGLE_LAUNCH: Algorithm 2 as one two-level reduce */
     LA_STAGE_PACK = 20,    /* staged exchange: copy of incoming segments into the staging area */
     LA_STAGE_COPY_INPUT = 21 /* out-of-place: ranges that no step reduces, copied from send to receive */
 };
@@ -190,6 +201,11 @@ int la_schedule_owned_ranges(const la_schedule_t* sched, int buffer, int capacit
 la_status_t la_schedule_step_info(const la_schedule_t* sched, int step, int* kind, int* stage,
                                   size_t* num_segments, size_t* seg_len_max, int* fan_in, int* fan_out,
                                   size_t* bytes_read, size_t* bytes_written);
+
+/* Sources per first-level sum of a step: the fan-in for an ordinary step; for the two-level step
+ * of LA_SCHED_SINGLE_LAUNCH the sources are added in runs of this many, each run rounded to the
+ * element type, and the run results are then added in order.  -1 for bad arguments. */
+int la_schedule_step_group(const la_schedule_t* sched, int step);
 
 /* Copy out the table of one step [host arrays sized from la_schedule_step_info]:
  * seg_len[S]; src_buf/src_off[S*fan_in]; dst_buf/dst_off[S*fan_out].  A buffer index below

@@ -6,7 +6,7 @@ memory and to provide a stream."""
 from .binding import (  # noqa: F401
     ALGOS, DTYPES, ELEM_SIZE, EXPORTS, LA_ALGO_LANE, LA_ALGO_LANE_MULTIPROC, LA_ALGO_RABENSEIFNER, LA_ALGO_RECURSIVE_DOUBLING, LA_ALGO_RING, LA_BF16, LA_F16, LA_F64, LA_MAX, LA_MIN, LA_PROD, OPS,
     LA_ERR_DEVICE, LA_ERR_INVALID_ARG, LA_ERR_OUT_OF_MEMORY, LA_ERR_UNSUPPORTED, LA_F32, LA_I32, LA_OK,
-    LA_SCHED_DEFAULT, LA_SCHED_FUSED_GATHER, LA_SCHED_INNER_RING, LA_SCHED_ONLY_ALLGATHER, LA_SCHED_ONLY_REDUCE_SCATTER, LA_SCHED_OUT_OF_PLACE, LA_SCHED_P2P_GATHER, LA_SCHED_SHARED_BUFFERS, LA_SCHED_STAGED, LA_STAGE_COPY_INPUT, LA_STAGE_PACK, LA_STAGE_RABENSEIFNER_AG, LA_STAGE_RABENSEIFNER_RS,
+    LA_SCHED_DEFAULT, LA_SCHED_FUSED_GATHER, LA_SCHED_INNER_RING, LA_SCHED_ONLY_ALLGATHER, LA_SCHED_ONLY_REDUCE_SCATTER, LA_SCHED_OUT_OF_PLACE, LA_SCHED_P2P_GATHER, LA_SCHED_SHARED_BUFFERS, LA_SCHED_SINGLE_LAUNCH, LA_SCHED_STAGED, LA_STAGE_COPY_INPUT, LA_STAGE_PACK, LA_STAGE_RABENSEIFNER_AG, LA_STAGE_RABENSEIFNER_RS,
     LA_STAGE_RECURSIVE_DOUBLING, LA_STAGE_RING_AG,
     LA_STAGE_RING_RS, LA_STAGE_S1, LA_STAGE_S2, LA_STAGE_S2_RING_AG, LA_STAGE_S2_RING_RS, LA_STAGE_S2A, LA_STAGE_S2B, LA_STAGE_S3, LA_STEP_COPY,
     LA_STEP_REDUCE, LA_SUM, LIB_PATH, LaError, Schedule, Topology, la_allreduce_emulated, la_allreduce_emulated_out_of_place, la_last_error,

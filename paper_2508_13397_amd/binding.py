@@ -21,12 +21,12 @@ OPS = {"sum": LA_SUM, "prod": LA_PROD, "max": LA_MAX, "min": LA_MIN}
 LA_SCHED_DEFAULT, LA_SCHED_P2P_GATHER, LA_SCHED_STAGED, LA_SCHED_INNER_RING = 0, 1, 2, 4
 LA_SCHED_SHARED_BUFFERS, LA_SCHED_OUT_OF_PLACE = 8, 16
 LA_SCHED_ONLY_REDUCE_SCATTER, LA_SCHED_ONLY_ALLGATHER = 32, 64
-LA_SCHED_FUSED_GATHER = 128
+LA_SCHED_FUSED_GATHER, LA_SCHED_SINGLE_LAUNCH = 128, 256
 LA_STEP_REDUCE, LA_STEP_COPY = 0, 1
 LA_STAGE_S1, LA_STAGE_S2A, LA_STAGE_S2B, LA_STAGE_S3, LA_STAGE_S2 = 1, 2, 3, 4, 5
 LA_STAGE_RING_RS, LA_STAGE_RING_AG, LA_STAGE_PACK = 10, 11, 20
 LA_STAGE_S2_RING_RS, LA_STAGE_S2_RING_AG = 6, 7
-LA_STAGE_S2_S3, LA_STAGE_S1_S3 = 8, 9
+LA_STAGE_S2_S3, LA_STAGE_S1_S3, LA_STAGE_S1_S2_S3 = 8, 9, 15
 LA_STAGE_COPY_INPUT = 21
 LA_STAGE_RECURSIVE_DOUBLING, LA_STAGE_RABENSEIFNER_RS, LA_STAGE_RABENSEIFNER_AG = 12, 13, 14
 
@@ -34,14 +34,14 @@ ALGOS = {"ring": LA_ALGO_RING, "lane": LA_ALGO_LANE, "lane_multiproc": LA_ALGO_L
          "recursive_doubling": LA_ALGO_RECURSIVE_DOUBLING, "rabenseifner": LA_ALGO_RABENSEIFNER}
 DTYPES = {"int32": LA_I32, "float32": LA_F32, "bfloat16": LA_BF16, "float16": LA_F16, "float64": LA_F64}
 ELEM_SIZE = {LA_I32: 4, LA_F32: 4, LA_BF16: 2, LA_F16: 2, LA_F64: 8}
-STAGE_NAMES = {21: "copy-input", 12: "rec-doubling", 13: "rabenseifner-RS", 14: "rabenseifner-AG", 1: "S1", 2: "S2a", 3: "S2b", 4: "S3", 5: "S2", 6: "S2-ring-RS", 7: "S2-ring-AG", 8: "S2+S3", 9: "S1+S3", 10: "ring-RS",
+STAGE_NAMES = {21: "copy-input", 12: "rec-doubling", 13: "rabenseifner-RS", 14: "rabenseifner-AG", 1: "S1", 2: "S2a", 3: "S2b", 4: "S3", 5: "S2", 6: "S2-ring-RS", 7: "S2-ring-AG", 8: "S2+S3", 9: "S1+S3", 15: "S1+S2+S3", 10: "ring-RS",
                11: "ring-AG", 20: "pack"}
 
 # every symbol include/lane_allreduce.h declares
 EXPORTS = (
     "la_topology_create", "la_topology_destroy", "la_topology_num_ranks",
     "la_schedule_build", "la_schedule_build_ex", "la_schedule_destroy", "la_schedule_num_steps",
-    "la_schedule_num_buffers", "la_schedule_owned_ranges",
+    "la_schedule_num_buffers", "la_schedule_owned_ranges", "la_schedule_step_group",
     "la_schedule_staging_elems", "la_schedule_step_info", "la_schedule_step_table",
     "la_allreduce_emulated", "la_allreduce_emulated_out_of_place", "la_schedule_run_step", "la_reduce_segments",
     "la_status_string", "la_last_error", "la_tuning_set", "la_tuning_get",
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
     L.la_schedule_num_steps.argtypes = [vp]
     L.la_schedule_num_buffers.argtypes = [vp]
     L.la_schedule_owned_ranges.argtypes = [vp, i32, i32, vp, vp]
+    L.la_schedule_step_group.argtypes = [vp, i32]
+    L.la_schedule_step_group.restype = i32
     L.la_schedule_staging_elems.argtypes = [vp]
     L.la_schedule_staging_elems.restype = sz
     L.la_schedule_step_info.argtypes = [vp, i32, pp(i32), pp(i32), pp(sz), pp(sz), pp(i32), pp(i32), pp(sz), pp(sz)]
@@ -203,7 +205,8 @@ class Schedule:
                "la_schedule_step_info")
         return dict(kind=kind.value, stage=stage.value, stage_name=STAGE_NAMES.get(stage.value, "?"),
                     num_segments=S.value, seg_len_max=longest.value, fan_in=k.value, fan_out=m.value,
-                    bytes_read=rd.value, bytes_written=wr.value)
+                    bytes_read=rd.value, bytes_written=wr.value,
+                    group=int(lib().la_schedule_step_group(self.handle, step)))
 
     def step_table(self, step: int) -> dict:
         info = self.step_info(step)

@@ -295,25 +295,93 @@ __device__ inline const LA_CONSTANT X* as_table(const X* p)
 // tails that do not fill a 16-byte vector, and segments whose operands are not congruent
 // modulo 16 bytes).
 template <typename T>
-__device__ inline void reduce_one(table_u64 sp, table_u64 dp, uint32_t k, uint32_t m, uint64_t e, uint32_t op)
+__device__ inline void reduce_one(table_u64 sp, table_u64 dp, uint32_t k, uint32_t m, uint32_t group, uint64_t e,
+                                  uint32_t op)
 {
     using elem = typename T::elem;
-    typename T::sacc a = T::swiden(reinterpret_cast<const elem*>(sp[0])[e]);
-    for (uint32_t t = 1; t < k; ++t) a = T::sadd(a, reinterpret_cast<const elem*>(sp[t])[e], op);
-    const elem r = T::snarrow(a);
+    typename T::sacc total = T::swiden(elem());
+    for (uint32_t t0 = 0; t0 < k; t0 += group) { // one run when group == k
+        const uint32_t t1 = t0 + group < k ? t0 + group : k;
+        typename T::sacc a = T::swiden(reinterpret_cast<const elem*>(sp[t0])[e]);
+        for (uint32_t t = t0 + 1; t < t1; ++t) a = T::sadd(a, reinterpret_cast<const elem*>(sp[t])[e], op);
+        const elem run = T::snarrow(a);
+        total = t0 == 0 ? T::swiden(run) : T::sadd(total, run, op);
+    }
+    const elem r = T::snarrow(total);
     for (uint32_t d = 0; d < m; ++d) reinterpret_cast<elem*>(dp[d])[e] = r;
 }
 
 // ---- the kernel -------------------------------------------------------------------------------
 
-// SUM_ONLY instances have the paper's operation compiled in; the others take it from the launch.
-template <typename T, int U, int POLICY, int BLOCK, bool SUM_ONLY>
+// Kernel modes.  The sum has instances of its own with the paper's operation compiled in; the
+// others take the operation from the launch.  A grouped step adds its sources in runs of
+// `group`: every run is reduced and rounded to the buffer's element type as if it had been stored,
+// and the run results are then combined in order (one launch that yields, bit for bit, what a
+// reduce launch per level would).
+enum { MODE_SUM = 0, MODE_ANY_OP = 1, MODE_GROUPED = 2 };
+
+// acc[u] = sources t0 .. t1-1 of the segment, combined in table order (t0 < t1)
+template <typename T, int U, typename P>
+__device__ __forceinline__ void reduce_run(typename T::Acc (&acc)[U], table_u64 sp, uint32_t t0, uint32_t t1,
+                                           uint64_t in_place, uint64_t tile_off, uint32_t tile_bytes,
+                                           const uint32_t (&off)[U], uint32_t op)
+{
+    constexpr int KBATCH = batch_for(U);
+    {
+        const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[t0], tile_off, tile_bytes);
+        const bool ip = t0 < 64u && ((in_place >> t0) & 1u); // the mask covers 64 sources
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u] = T::widen(load_src<P>(r, off[u], ip));
+    }
+    uint32_t t = t0 + 1;
+    // full batches: KBATCH*U independent 16-byte loads per lane are issued before the adds
+    for (; t + KBATCH <= t1; t += KBATCH) {
+        u32x4 x[KBATCH][U];
+#pragma unroll
+        for (int b = 0; b < KBATCH; ++b) {
+            const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[t + b], tile_off, tile_bytes);
+            const bool ip = t + b < 64u && ((in_place >> (t + b)) & 1u);
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[b][u] = load_src<P>(r, off[u], ip);
+        }
+#pragma unroll
+        for (int b = 0; b < KBATCH; ++b)
+#pragma unroll
+            for (int u = 0; u < U; ++u) T::add(acc[u], x[b][u], op);
+    }
+    // remaining 0..KBATCH-1 operands
+    if constexpr (KBATCH > 1) {
+        if (t < t1) {
+            const uint32_t rem = t1 - t;
+            u32x4 x[KBATCH > 1 ? KBATCH - 1 : 1][U];
+#pragma unroll
+            for (int b = 0; b < KBATCH - 1; ++b) {
+                if ((uint32_t)b < rem) {
+                    const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[t + b], tile_off, tile_bytes);
+                    const bool ip = t + b < 64u && ((in_place >> (t + b)) & 1u);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) x[b][u] = load_src<P>(r, off[u], ip);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < KBATCH - 1; ++b) {
+                if ((uint32_t)b < rem) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) T::add(acc[u], x[b][u], op);
+                }
+            }
+        }
+    }
+}
+
+template <typename T, int U, int POLICY, int BLOCK, int MODE>
 __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
 {
     using P = Policy<POLICY>;
     const uint32_t seg = blockIdx.x / tab.tiles_per_seg;
     const uint32_t tile = blockIdx.x - seg * tab.tiles_per_seg;
-    const uint32_t k = tab.k, m = tab.m, op = SUM_ONLY ? (uint32_t)LA_SUM : tab.op;
+    const uint32_t k = tab.k, m = tab.m, op = MODE == MODE_SUM ? (uint32_t)LA_SUM : tab.op;
+    const uint32_t group = MODE == MODE_GROUPED ? tab.group : k;
     const table_seg sg = as_table(tab.seg) + seg;
     SegInfo si;
     si.len = sg->len;
@@ -330,7 +398,7 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
         const uint64_t lo = (uint64_t)tile * TILE * T::VEC;
         uint64_t hi = lo + TILE * T::VEC;
         if (hi > si.len) hi = si.len;
-        for (uint64_t e = lo + tid; e < hi; e += BLOCK) reduce_one<T>(sp, dp, k, m, e, op);
+        for (uint64_t e = lo + tid; e < hi; e += BLOCK) reduce_one<T>(sp, dp, k, m, group, e, op);
         return;
     }
 
@@ -341,7 +409,7 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     if (tile == 0 && tid < si.head + tail) {
         // the few elements before the first and after the last whole vector
         const uint64_t e = tid < si.head ? tid : si.head + nvec * T::VEC + (tid - si.head);
-        reduce_one<T>(sp, dp, k, m, e, op);
+        reduce_one<T>(sp, dp, k, m, group, e, op);
     }
 
     const uint64_t tile_v0 = (uint64_t)tile * TILE;
@@ -351,61 +419,35 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     const uint64_t tile_off = (uint64_t)si.head * sizeof(typename T::elem) + tile_v0 * 16u;
     const uint64_t in_place = si.alias_mask;
 
-    constexpr int KBATCH = batch_for(U);
     uint32_t off[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) off[u] = (tid + (uint32_t)u * BLOCK) * 16u;
 
-    typename T::Acc acc[U];
-    {
-        const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[0], tile_off, tile_bytes);
-        const bool ip = in_place & 1u;
-#pragma unroll
-        for (int u = 0; u < U; ++u) acc[u] = T::widen(load_src<P>(r, off[u], ip));
-    }
-    uint32_t t = 1;
-    // full batches: KBATCH*U independent 16-byte loads per lane are issued before the adds
-    for (; t + KBATCH <= k; t += KBATCH) {
-        u32x4 x[KBATCH][U];
-#pragma unroll
-        for (int b = 0; b < KBATCH; ++b) {
-            const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[t + b], tile_off, tile_bytes);
-            const bool ip = t + b < 64u && ((in_place >> (t + b)) & 1u); // the mask covers 64 sources
-#pragma unroll
-            for (int u = 0; u < U; ++u) x[b][u] = load_src<P>(r, off[u], ip);
-        }
-#pragma unroll
-        for (int b = 0; b < KBATCH; ++b)
-#pragma unroll
-            for (int u = 0; u < U; ++u) T::add(acc[u], x[b][u], op);
-    }
-    // remaining 0..KBATCH-1 operands
-    if constexpr (KBATCH > 1) {
-      if (t < k) {
-        const uint32_t rem = k - t;
-        u32x4 x[KBATCH > 1 ? KBATCH - 1 : 1][U];
-#pragma unroll
-        for (int b = 0; b < KBATCH - 1; ++b) {
-            if ((uint32_t)b < rem) {
-                const __amdgpu_buffer_rsrc_t r = tile_rsrc(sp[t + b], tile_off, tile_bytes);
-                const bool ip = t + b < 64u && ((in_place >> (t + b)) & 1u); // the mask covers 64 sources
-#pragma unroll
-                for (int u = 0; u < U; ++u) x[b][u] = load_src<P>(r, off[u], ip);
-            }
-        }
-#pragma unroll
-        for (int b = 0; b < KBATCH - 1; ++b) {
-            if ((uint32_t)b < rem) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) T::add(acc[u], x[b][u], op);
-            }
-        }
-      }
-    }
-
     u32x4 out[U];
+    if constexpr (MODE != MODE_GROUPED) {
+        typename T::Acc acc[U];
+        reduce_run<T, U, P>(acc, sp, 0, k, in_place, tile_off, tile_bytes, off, op);
 #pragma unroll
-    for (int u = 0; u < U; ++u) out[u] = T::narrow(acc[u]);
+        for (int u = 0; u < U; ++u) out[u] = T::narrow(acc[u]);
+    } else {
+        // first level: runs of `group` sources, each rounded as a stored result would be;
+        // second level: the run results in order
+        typename T::Acc acc[U];
+        for (uint32_t t0 = 0; t0 < k; t0 += group) {
+            const uint32_t t1 = t0 + group < k ? t0 + group : k;
+            typename T::Acc run[U];
+            reduce_run<T, U, P>(run, sp, t0, t1, in_place, tile_off, tile_bytes, off, op);
+            if (t0 == 0) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[u] = T::widen(T::narrow(run[u]));
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) T::add(acc[u], T::narrow(run[u]), op);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) out[u] = T::narrow(acc[u]);
+    }
     for (uint32_t d = 0; d < m; ++d) {
         const __amdgpu_buffer_rsrc_t r = tile_rsrc(dp[d], tile_off, tile_bytes);
 #pragma unroll
@@ -416,10 +458,12 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
 template <typename T, int U, int POLICY, int BLOCK>
 void launch_op(const StepTable& t, dim3 grid, hipStream_t s)
 {
-    if (t.op == (uint32_t)LA_SUM)
-        hipLaunchKernelGGL((seg_reduce_kernel<T, U, POLICY, BLOCK, true>), grid, dim3(BLOCK), 0, s, t);
+    if (t.group > 0 && t.group < t.k)
+        hipLaunchKernelGGL((seg_reduce_kernel<T, U, POLICY, BLOCK, MODE_GROUPED>), grid, dim3(BLOCK), 0, s, t);
+    else if (t.op == (uint32_t)LA_SUM)
+        hipLaunchKernelGGL((seg_reduce_kernel<T, U, POLICY, BLOCK, MODE_SUM>), grid, dim3(BLOCK), 0, s, t);
     else
-        hipLaunchKernelGGL((seg_reduce_kernel<T, U, POLICY, BLOCK, false>), grid, dim3(BLOCK), 0, s, t);
+        hipLaunchKernelGGL((seg_reduce_kernel<T, U, POLICY, BLOCK, MODE_ANY_OP>), grid, dim3(BLOCK), 0, s, t);
 }
 
 template <typename T, int U, int BLOCK>

@@ -46,6 +46,8 @@ struct Step {
     int kind = LA_STEP_REDUCE;
     int stage = 0;
     int k = 0, m = 0;
+    int group = 0;             // > 0: the k sources are added in runs of `group`, each run rounded to
+                               // the element type, then the run results in order (two-level sum)
     std::vector<uint64_t> len; // [S]
     std::vector<Operand> src;  // [S*k]
     std::vector<Operand> dst;  // [S*m]
@@ -69,6 +71,7 @@ struct StepTable {
     uint32_t tiles_per_seg;  // grid = S * tiles_per_seg blocks
     uint32_t num_segments;
     uint32_t op = 0;         // la_op_t of the launch
+    uint32_t group = 0;      // 0 or k: one level; else sources per first-level run
 };
 
 // Launch shape of one step.  In the process-wide setting 0 (unroll, block) and -1 (cache_policy)
@@ -85,9 +88,10 @@ struct Tuning {
 Tuning current_tuning();
 // Fill the automatic fields of `requested` for a step with k sources, m destinations, a longest
 // segment of `longest_units` 16-byte vectors and `bytes_per_operand` bytes summed over its
-// segments (the size of the step's result, and of its source when k == 1).
+// segments (the size of the step's result, and of its source when k == 1).  all_inputs: the step
+// is the whole all-reduce (every source an original input, every rank a destination).
 Tuning resolve_tuning(const Tuning& requested, uint32_t k, uint32_t m, uint64_t longest_units,
-                      uint64_t bytes_per_operand);
+                      uint64_t bytes_per_operand, bool all_inputs, size_t esize);
 
 // kernels.hip
 la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream);

@@ -52,7 +52,8 @@ Tuning current_tuning()
 //    behaves like a broadcast and takes its shape: 128 KiB tiles, streaming stores.
 constexpr uint64_t LAST_LEVEL_CACHE_BYTES = 256ull << 20;
 
-Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longest_units, uint64_t bytes_per_operand)
+Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longest_units, uint64_t bytes_per_operand,
+                      bool all_inputs, size_t esize)
 {
     Tuning t;
     int cls; // step class: 0 pure reduce, 1 reduce + multi-destination store, 2 copy / broadcast
@@ -92,7 +93,14 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
     } else {
         cls = 1;
         t.cache_policy = 7;
-        if (m >= 8 && m > k) {
+        if (all_inputs) {
+            // the whole all-reduce in one launch: every source is an original input, read once
+            // and overwritten; as many stores as loads.  16-bit types keep two sets of eight
+            // fp32 accumulators per vector: 64 KiB tiles fit the register file, 128 KiB do not.
+            t.cache_policy = fits ? 6 : 3;
+            t.block = 1024;
+            t.unroll = esize < 4 ? 4 : 8;
+        } else if (m >= 8 && m > k) {
             // the all-gathers folded into the reduce: store-dominated, like a broadcast
             t.cache_policy = fits ? 4 : 6;
             t.block = 1024;
@@ -254,8 +262,10 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
         v.dst_ptr = reinterpret_cast<const uint64_t*>(dst_at[i]);
         v.k = (uint32_t)p.k;
         v.m = (uint32_t)p.m;
+        v.group = (uint32_t)p.group;
         v.num_segments = (uint32_t)S;
-        shapes[i] = resolve_tuning(tune, v.k, v.m, longest, step_elems * esize);
+        shapes[i] = resolve_tuning(tune, v.k, v.m, longest, step_elems * esize,
+                                   p.stage == LA_STAGE_S1_S2_S3 && p.k > 1 && p.m > 1, esize);
         v.tiles_per_seg = tiles_for(longest, shapes[i]);
     }
 }
@@ -611,7 +621,7 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
     t.m = 1;
     t.op = (uint32_t)op;
     t.num_segments = (uint32_t)num_segments;
-    const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest, (uint64_t)num_segments * seg_len * e);
+    const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest, (uint64_t)num_segments * seg_len * e, false, e);
     t.tiles_per_seg = tiles_for(longest, tune);
     la_status_t st = launch_step(t, dtype, tune, hip_stream);
     (void)hipFreeAsync(dev, stream); // stream-ordered: freed after the kernel has run

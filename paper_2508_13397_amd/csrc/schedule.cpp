@@ -233,6 +233,35 @@ void gen_lane(la_schedule& s, Staging& st, bool split_procs)
 
     // S1: reduce-scatter on the node group; the owner adds the R node-local copies of its part
     // in ascending node-local index (its own copy taking its place in that order).
+    // LA_SCHED_SINGLE_LAUNCH: S1, S2 and S3 as one two-level reduce.  Piece v of part j is the sum
+    // over the nodes, in ascending order, of each node's sum over its R ranks in ascending
+    // node-local index, the node sums rounded to the element type as S1 stores them; it is stored
+    // to every rank.  Every input is read once and every output written once.
+    if (s.flags & LA_SCHED_SINGLE_LAUNCH) {
+        Step all;
+        all.kind = LA_STEP_REDUCE;
+        all.stage = LA_STAGE_S1_S2_S3;
+        all.k = all.m = N * R;
+        all.group = (N > 1 && R > 1) ? R : 0;
+        if (N * R == 1) return;
+        for (int j = 0; j < J; ++j)
+            for (int v = 0; v < N; ++v) {
+                const Part piece = split_part(part[j].cnt, N, v);
+                if (piece.cnt == 0) continue;
+                const uint64_t off = part[j].off + piece.off;
+                all.len.push_back(piece.cnt);
+                for (int w = 0; w < N; ++w)
+                    for (int l = 0; l < R; ++l) all.src.push_back(Operand{t.rank_of(w, l), off});
+                const int me = t.rank_of(v, owner(j));
+                all.dst.push_back(Operand{me, off}); // the rank that reduces the piece in Algorithm 2 first
+                for (int w = 0; w < N; ++w)
+                    for (int l = 0; l < R; ++l)
+                        if (t.rank_of(w, l) != me) all.dst.push_back(Operand{t.rank_of(w, l), off});
+            }
+        if (!all.len.empty()) s.steps.push_back(std::move(all));
+        return;
+    }
+
     // LA_SCHED_FUSED_GATHER: the last reduce of a part stores to every rank that the all-gathers
     // would have copied it to, and the all-gather launches disappear.
     const bool fused = (s.flags & LA_SCHED_FUSED_GATHER) != 0;
@@ -412,6 +441,38 @@ void gen_shared_lane(la_schedule& s, Staging& st, int Q)
         const Part ch = split_part(slice.cnt, G, g);
         return Part{slice.off + ch.off, ch.cnt};
     };
+    for (int q = 0; q < Q; ++q)
+        for (int g = 0; g < G; ++g)
+            for (int v = 0; v < N; ++v) {
+                const Part c = chunk(q, g);
+                const Part piece = split_part(c.cnt, N, v);
+                s.owned[buf(v, g)].push_back(Part{c.off + piece.off, piece.cnt});
+            }
+    if (s.flags & LA_SCHED_SINGLE_LAUNCH) { // see gen_lane
+        Step all;
+        all.kind = LA_STEP_REDUCE;
+        all.stage = LA_STAGE_S1_S2_S3;
+        all.k = all.m = N * G;
+        all.group = (N > 1 && G > 1) ? G : 0;
+        if (N * G == 1) return;
+        for (int q = 0; q < Q; ++q)
+            for (int g = 0; g < G; ++g)
+                for (int v = 0; v < N; ++v) {
+                    const Part c = chunk(q, g);
+                    const Part piece = split_part(c.cnt, N, v);
+                    if (piece.cnt == 0) continue;
+                    const uint64_t off = c.off + piece.off;
+                    all.len.push_back(piece.cnt);
+                    for (int w = 0; w < N; ++w)
+                        for (int h = 0; h < G; ++h) all.src.push_back(Operand{buf(w, h), off});
+                    all.dst.push_back(Operand{buf(v, g), off});
+                    for (int w = 0; w < N; ++w)
+                        for (int h = 0; h < G; ++h)
+                            if (buf(w, h) != buf(v, g)) all.dst.push_back(Operand{buf(w, h), off});
+                }
+        if (!all.len.empty()) s.steps.push_back(std::move(all));
+        return;
+    }
     const bool fused = (s.flags & LA_SCHED_FUSED_GATHER) != 0;
     const bool s1_is_last = fused && N == 1;
     if (G > 1) {
@@ -430,13 +491,6 @@ void gen_shared_lane(la_schedule& s, Staging& st, int Q)
                 }
         rb.emit(s.steps);
     }
-    for (int q = 0; q < Q; ++q)
-        for (int g = 0; g < G; ++g)
-            for (int v = 0; v < N; ++v) {
-                const Part c = chunk(q, g);
-                const Part piece = split_part(c.cnt, N, v);
-                s.owned[buf(v, g)].push_back(Part{c.off + piece.off, piece.cnt});
-            }
     if (N > 1) {
         ReduceBuilder rb(s, st, fused ? LA_STAGE_S2_S3 : split ? LA_STAGE_S2A : LA_STAGE_S2, N,
                          fused ? N * G : split ? 1 : N);
@@ -647,6 +701,13 @@ la_status_t generate_steps(la_schedule& s)
     s.owned.assign(s.nbuf, {});
     if ((s.flags & LA_SCHED_ONLY_REDUCE_SCATTER) && (s.flags & LA_SCHED_ONLY_ALLGATHER))
         return fail(LA_ERR_INVALID_ARG, "LA_SCHED_ONLY_REDUCE_SCATTER and LA_SCHED_ONLY_ALLGATHER exclude each other");
+    if (s.flags & LA_SCHED_SINGLE_LAUNCH) {
+        if (s.flags & (LA_SCHED_P2P_GATHER | LA_SCHED_INNER_RING | LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER |
+                       LA_SCHED_FUSED_GATHER | LA_SCHED_STAGED))
+            return fail(LA_ERR_INVALID_ARG, "LA_SCHED_SINGLE_LAUNCH combines only with LA_SCHED_SHARED_BUFFERS and LA_SCHED_OUT_OF_PLACE");
+        if (s.algo != LA_ALGO_LANE && s.algo != LA_ALGO_LANE_MULTIPROC)
+            return fail(LA_ERR_UNSUPPORTED, "LA_SCHED_SINGLE_LAUNCH applies to the lane schedules only");
+    }
     if (s.flags & LA_SCHED_FUSED_GATHER) {
         if (s.flags & (LA_SCHED_P2P_GATHER | LA_SCHED_INNER_RING | LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER))
             return fail(LA_ERR_INVALID_ARG, "LA_SCHED_FUSED_GATHER excludes the point-to-point gather, the inner ring and the stand-alone halves");
@@ -816,7 +877,7 @@ la_status_t la_schedule_build_ex(const la_topology_t* topo, la_algo_t algo, size
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown algorithm %d", (int)algo);
     if (flags & ~(unsigned)(LA_SCHED_P2P_GATHER | LA_SCHED_STAGED | LA_SCHED_INNER_RING | LA_SCHED_SHARED_BUFFERS |
                                LA_SCHED_OUT_OF_PLACE | LA_SCHED_ONLY_REDUCE_SCATTER | LA_SCHED_ONLY_ALLGATHER |
-                               LA_SCHED_FUSED_GATHER))
+                               LA_SCHED_FUSED_GATHER | LA_SCHED_SINGLE_LAUNCH))
         return fail(LA_ERR_UNSUPPORTED, "la_schedule_build: unknown flag bits 0x%x", flags);
     la_schedule* s = new (std::nothrow) la_schedule;
     if (!s) return fail(LA_ERR_OUT_OF_MEMORY, "la_schedule_build: out of host memory");
@@ -908,6 +969,13 @@ la_status_t la_schedule_step_info(const la_schedule_t* sched, int step, int* kin
     if (bytes_read) *bytes_read = (size_t)(total * (uint64_t)p.k * e);
     if (bytes_written) *bytes_written = (size_t)(total * (uint64_t)p.m * e);
     return LA_OK;
+}
+
+int la_schedule_step_group(const la_schedule_t* sched, int step)
+{
+    if (!sched || step < 0 || step >= (int)sched->steps.size()) return -1;
+    const Step& p = sched->steps[step];
+    return p.group > 0 && p.group < p.k ? p.group : p.k;
 }
 
 la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_t* seg_len, int32_t* src_buf,

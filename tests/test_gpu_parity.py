@@ -385,8 +385,9 @@ def wide_inputs(P, n, kind, seed):
 
 
 @pytest.mark.parametrize("op", ["sum", "prod", "max", "min"])
-@pytest.mark.parametrize("algo", ALGOS)
-def test_operations_all_dtypes(oracle, algo, op):
+@pytest.mark.parametrize("algo,flags", [(a, 0) for a in ALGOS] + [("lane_multiproc", la.LA_SCHED_SINGLE_LAUNCH),
+                                                                  ("lane", la.LA_SCHED_FUSED_GATHER)])
+def test_operations_all_dtypes(oracle, algo, flags, op):
     topo, P = (2, 3, 2), 12
     for n, kind in itertools.product((5, 40009), ("i32wrap", "f32order", "bf16", "f16", "f64")):
         x = wide_inputs(P, n, kind, n) if kind in ("f16", "f64") else make(P, n, kind, seed=n)
@@ -395,8 +396,8 @@ def test_operations_all_dtypes(oracle, algo, op):
         if op in ("max", "min") and x.dtype in (np.float32, np.float64, np.float16):
             x[0, 1], x[1, 1], x[3, 2], x[5, 3], x[6, 3] = np.nan, 1.0, np.nan, 0.0, -0.0
             x[:5, 4], x[5:, 4] = -0.0, 0.0
-        print("op case", algo, op, n, kind, flush=True)
-        got = gpu_allreduce(topo, algo, x, op=op)
+        print("op case", algo, flags, op, n, kind, flush=True)
+        got = gpu_allreduce(topo, algo, x, flags, op=op)
         ref = oracle.allreduce(algo, *topo, x, op=op)
         fl = x.dtype in (np.float32, np.float64, np.float16)
         nan = np.isnan(ref) if fl else np.zeros(ref.shape, bool)
@@ -503,6 +504,53 @@ def test_fused_gather_small_topologies(oracle, algo, extra):
         else:
             ref = oracle.allreduce(algo, N, G, Q, x)
         assert np.array_equal(bits(got), bits(ref)), (algo, extra, topo, n, kind)
+
+
+@pytest.mark.parametrize("algo", ["lane", "lane_multiproc"])
+@pytest.mark.parametrize("extra", [0, la.LA_SCHED_SHARED_BUFFERS])
+def test_single_launch_small_topologies(oracle, algo, extra):
+    cases = [((2, 2, 2), 100003), ((3, 2, 1), 40961), ((1, 3, 2), 7), ((2, 1, 3), 12289), ((1, 1, 1), 100),
+             ((2, 3, 2), 5), ((4, 2, 2), 262147), ((1, 4, 2), 300007), ((3, 1, 1), 70001)]
+    for (topo, n), kind in itertools.product(cases, ("i32wrap", "f32order", "bf16")):
+        N, G, Q = topo
+        B = N * G if extra & la.LA_SCHED_SHARED_BUFFERS else N * G * Q
+        x = make(B, n, kind, seed=n)
+        print("one-launch case", algo, extra, topo, n, kind, flush=True)
+        got = gpu_allreduce(topo, algo, x, la.LA_SCHED_SINGLE_LAUNCH | extra)
+        if extra & la.LA_SCHED_SHARED_BUFFERS:
+            ref = oracle.allreduce("lane_multiproc", N, G, 1 if algo == "lane" else Q, x, shared=True)
+        else:
+            ref = oracle.allreduce(algo, N, G, Q, x)
+        assert np.array_equal(bits(got), bits(ref)), (algo, extra, topo, n, kind)
+
+
+def test_single_launch_every_launch_shape_and_misaligned_views(oracle):
+    """forced tile shapes, and rank buffers that start at odd element offsets (head / tail peel and
+    the element-wise path when the operands disagree modulo 16 bytes)"""
+    topo, n = (2, 2, 2), 50021
+    P = 8
+    x = make(P, n, "bf16", seed=11)
+    ref = oracle.allreduce("lane_multiproc", *topo, x)
+    t = la.la_topology_create(*topo)
+    sched = la.la_schedule_build(t, "lane_multiproc", n, "bfloat16", la.LA_SCHED_SINGLE_LAUNCH)
+    try:
+        for unroll, block in ((1, 256), (2, 256), (4, 256), (1, 1024), (2, 1024), (4, 1024), (8, 1024)):
+            la.la_tuning_set("unroll", unroll)
+            la.la_tuning_set("block", block)
+            got = gpu_allreduce(topo, "lane_multiproc", x, la.LA_SCHED_SINGLE_LAUNCH)
+            assert np.array_equal(bits(got), bits(ref)), (unroll, block)
+    finally:
+        la.la_tuning_set("unroll", 0)
+        la.la_tuning_set("block", 0)
+    for offsets in ([3] * P, [1, 2, 3, 4, 5, 6, 7, 9]):
+        slabs = [torch.zeros(n + 16, dtype=torch.bfloat16, device="cuda") for _ in range(P)]
+        views = [slabs[r][offsets[r]: offsets[r] + n] for r in range(P)]
+        for r in range(P):
+            views[r].copy_(to_dev(x[r]))
+        la.allreduce_tensors(sched, views)
+        torch.cuda.synchronize()
+        got = np.stack([to_host(v) for v in views])
+        assert np.array_equal(bits(got), bits(ref)), offsets
 
 
 RS, AG = la.LA_SCHED_ONLY_REDUCE_SCATTER, la.LA_SCHED_ONLY_ALLGATHER
@@ -785,6 +833,22 @@ def test_config4_fused_gather(oracle):
 
 def test_config5_fused_gather_fan_out_1024(oracle):
     full_size_case(oracle, (32, 4, 8), "lane_multiproc", 1 << 20, "uniform_pm1", flags=la.LA_SCHED_FUSED_GATHER, tol=False)
+
+
+def test_config2_single_launch(oracle):
+    full_size_case(oracle, (4, 4, 1), "lane", 1 << 24, "normal", flags=la.LA_SCHED_SINGLE_LAUNCH)
+
+
+def test_config4_single_launch_bf16_two_roundings(oracle):
+    full_size_case(oracle, (2, 4, 2), "lane_multiproc", 1 << 27, "normal_bf16", flags=la.LA_SCHED_SINGLE_LAUNCH)
+
+
+def test_config3_single_launch(oracle):
+    full_size_case(oracle, (8, 4, 4), "lane_multiproc", 1 << 22, "uniform_pm1", flags=la.LA_SCHED_SINGLE_LAUNCH)
+
+
+def test_config5_single_launch_fan_in_and_out_1024(oracle):
+    full_size_case(oracle, (32, 4, 8), "lane_multiproc", 1 << 20, "uniform_pm1", flags=la.LA_SCHED_SINGLE_LAUNCH, tol=False)
 
 
 def test_config5_scale_out_point_to_point_gather(oracle):

@@ -67,7 +67,11 @@ def test_schedule_build_errors():
         (dict(algo="lane", n=0, dtype="float32"), la.LA_ERR_INVALID_ARG),
         (dict(algo=9, n=16, dtype="float32"), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype=9), la.LA_ERR_UNSUPPORTED),
-        (dict(algo="lane", n=16, dtype="float32", flags=256), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=512), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="ring", n=16, dtype="float32", flags=256), la.LA_ERR_UNSUPPORTED),
+        (dict(algo="lane", n=16, dtype="float32", flags=256 | 128), la.LA_ERR_INVALID_ARG),
+        (dict(algo="lane", n=16, dtype="float32", flags=256 | 2), la.LA_ERR_INVALID_ARG),
+        (dict(algo="lane", n=16, dtype="float32", flags=256 | 64), la.LA_ERR_INVALID_ARG),
         (dict(algo="ring", n=16, dtype="float32", flags=128), la.LA_ERR_UNSUPPORTED),
         (dict(algo="rabenseifner", n=16, dtype="float32", flags=128), la.LA_ERR_UNSUPPORTED),
         (dict(algo="lane", n=16, dtype="float32", flags=128 | 1), la.LA_ERR_INVALID_ARG),
@@ -168,9 +172,12 @@ def bf16_narrow(x32):
     return torch.from_numpy(x32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
 
 
-def sum_in_order(ops):
+def sum_in_order(ops, group=None):
     """one segment: the operands added in table order (uint16 = bf16 bits: fp32 accumulation, one
-    rounding at the end; int32 wraps)"""
+    rounding at the end; int32 wraps).  With group < len(ops): runs of `group` operands are summed
+    (and rounded) first, then the run results in order."""
+    if group and group < len(ops):
+        return sum_in_order([sum_in_order(ops[i:i + group]) for i in range(0, len(ops), group)])
     if ops[0].dtype == np.uint16:
         if len(ops) == 1:
             return ops[0].copy()
@@ -201,7 +208,7 @@ def run_tables(sched, inputs, snapshot=True, upto=None):
         for g in range(t["num_segments"]):
             ln = int(t["seg_len"][g])
             ops = [old[int(b)][int(o):int(o) + ln] for b, o in zip(t["src_buf"][g], t["src_off"][g])]
-            res = sum_in_order(ops)
+            res = sum_in_order(ops, t["group"])
             for b, o in zip(t["dst_buf"][g], t["dst_off"][g]):
                 state[int(b)][int(o):int(o) + ln] = res
     return np.stack(state[:P])
@@ -312,7 +319,7 @@ def run_tables_out_of_place(sched, inputs):
         for g in range(t["num_segments"]):
             ln = int(t["seg_len"][g])
             ops = [old[int(b)][int(o):int(o) + ln] for b, o in zip(t["src_buf"][g], t["src_off"][g])]
-            res = sum_in_order(ops)
+            res = sum_in_order(ops, t["group"])
             for b, o in zip(t["dst_buf"][g], t["dst_off"][g]):
                 state[int(b)][int(o):int(o) + ln] = res
     return np.stack(state[:B]), np.stack(state[B + 1:])
@@ -447,6 +454,82 @@ def test_fused_gather_shapes_and_bytes():
     assert wp == wf                      # every buffer is still written once per all-gathered element
     one = la.la_schedule_build(la.la_topology_create(1, 4, 2), "lane_multiproc", n, "float32", FUSED)
     assert [(x["stage_name"], x["fan_in"], x["fan_out"]) for x in one.steps()] == [("S1+S3", 8, 8)]
+
+
+# ----------------------------------------------------------------------------- one launch
+
+ONE = la.LA_SCHED_SINGLE_LAUNCH
+
+
+@pytest.mark.parametrize("algo", ["lane", "lane_multiproc"])
+@pytest.mark.parametrize("extra", [0, la.LA_SCHED_OUT_OF_PLACE, SHARED, SHARED | la.LA_SCHED_OUT_OF_PLACE])
+def test_single_launch_tables_reproduce_oracle_bitwise(oracle, algo, extra):
+    """Algorithm 2 as one two-level reduce: node sums first (rounded as stored), then across the
+    nodes.  Order-sensitive fp32 and bf16 inputs tell it apart from a flat sum and from a sum that
+    skips the intermediate rounding."""
+    for (N, G, Q) in TOPOS:
+        topo = la.la_topology_create(N, G, Q)
+        B = N * G if extra & SHARED else N * G * Q
+        for n in (1, 5, 17, 40):
+            for x in (np.random.default_rng(n).integers(-(1 << 31), 1 << 31, size=(B, n), dtype=np.int64).astype(np.int32),
+                      synth.order_sensitive_f32(B, n), synth.to_bf16_bits(synth.order_sensitive_f32(B, n) * np.float32(2.0 ** -20))):
+                dt = {np.dtype(np.int32): "int32", np.dtype(np.float32): "float32", np.dtype(np.uint16): "bfloat16"}[x.dtype]
+                sched = la.la_schedule_build(topo, algo, n, dt, ONE | extra)
+                if extra & SHARED:
+                    ref = oracle.allreduce("lane_multiproc", N, G, 1 if algo == "lane" else Q, x, shared=True)
+                else:
+                    ref = oracle.allreduce(algo, N, G, Q, x)
+                if extra & la.LA_SCHED_OUT_OF_PLACE:
+                    got, send = run_tables_out_of_place(sched, x)
+                    assert np.array_equal(send.view(np.uint8), x.view(np.uint8))
+                else:
+                    got = run_tables(sched, x)
+                assert np.array_equal(got.view(np.uint8), ref.view(np.uint8)), (algo, extra, N, G, Q, n, dt)
+                steps = sched.steps()
+                reduces = [st for st in steps if st["stage_name"] != "copy-input"]
+                assert len(reduces) == (0 if B == 1 else 1)
+                if reduces:
+                    R = G if extra & SHARED else G * Q
+                    st = reduces[0]
+                    assert (st["fan_in"], st["fan_out"]) == (N * R, N * R)
+                    assert st["group"] == (R if N > 1 and R > 1 else N * R)
+
+
+def test_single_launch_differs_from_flat_and_unrounded_sums():
+    """The two-level order is not decoration: on order-sensitive inputs a flat sum over all ranks,
+    and for bf16 a two-level sum without the intermediate rounding, give other bits."""
+    N, G, Q, n = 3, 2, 2, 64
+    P = N * G * Q
+    topo = la.la_topology_create(N, G, Q)
+    x = synth.order_sensitive_f32(P, n)
+    sched = la.la_schedule_build(topo, "lane_multiproc", n, "float32", ONE)
+    got = run_tables(sched, x)
+    flat = x[0].copy()
+    for r in range(1, P):
+        flat = flat + x[r]
+    assert not np.array_equal(got[0].view(np.uint32), flat.view(np.uint32))
+    xb = synth.to_bf16_bits(synth.make_inputs(P, n, "normal", seed=5))
+    sb = la.la_schedule_build(topo, "lane_multiproc", n, "bfloat16", ONE)
+    gotb = run_tables(sb, xb)
+    wide = (xb.astype(np.uint32) << 16).view(np.float32)
+    node = [sum_f32(wide[w * G * Q:(w + 1) * G * Q]) for w in range(N)]
+    unrounded = bf16_narrow(np.ascontiguousarray(sum_f32(np.stack(node))))
+    assert not np.array_equal(gotb[0], unrounded)
+
+
+def sum_f32(rows):
+    acc = rows[0].copy()
+    for r in rows[1:]:
+        acc = acc + r
+    return acc
+
+
+def test_single_launch_bytes_are_the_lower_bound():
+    n, e = 1 << 20, 4
+    t = la.la_topology_create(4, 4, 1)
+    one = la.la_schedule_build(t, "lane", n, "float32", ONE)
+    assert one.num_steps == 1
+    assert totals(one) == (16 * n * e, 16 * n * e)      # every input read once, every output written once
 
 
 # ----------------------------------------------------------------------------- stand-alone halves
