@@ -20,8 +20,10 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
-# (source, object name, extra flags): kernels.hip is built once per element type
-UNITS = [("kernels.hip", f"kernels_dtype{d}.o", [f"-DLA_KERNEL_DTYPE={d}"]) for d in range(5)] + [
+# (source, object name, extra flags): kernels.hip is built once per element type and launch-shape
+# family; the largest units come first so that the pool stays busy to the end
+UNITS = [("kernels.hip", f"kernels_dtype{d}_shape{f}.o", [f"-DLA_KERNEL_DTYPE={d}", f"-DLA_KERNEL_SHAPE={f}"])
+         for f in (2, 0, 1) for d in (2, 3, 4, 1, 0)] + [
     ("dispatch.cpp", "dispatch.o", []), ("runtime.cpp", "runtime.o", []), ("schedule.cpp", "schedule.o", [])]
 
 

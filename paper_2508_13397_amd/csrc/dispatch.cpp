@@ -1,14 +1,36 @@
-// Picks the kernel family of an element type; the families are built from kernels.hip, one
-// translation unit per type.
+// Picks the kernel family of an element type and launch shape; the families are built from
+// kernels.hip, one translation unit each.
 #include "la_internal.hpp"
 
 namespace la {
 
-la_status_t launch_step_i32(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream);
-la_status_t launch_step_f32(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream);
-la_status_t launch_step_bf16(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream);
-la_status_t launch_step_f16(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream);
-la_status_t launch_step_f64(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream);
+// launch_family_<dtype>_<family>: one per translation unit built from kernels.hip
+#define LA_DECLARE_FAMILIES(d)                                                                          \
+    la_status_t launch_family_##d##_0(const StepTable&, const Tuning&, uint32_t blocks, void* stream); \
+    la_status_t launch_family_##d##_1(const StepTable&, const Tuning&, uint32_t blocks, void* stream); \
+    la_status_t launch_family_##d##_2(const StepTable&, const Tuning&, uint32_t blocks, void* stream);
+LA_DECLARE_FAMILIES(0)
+LA_DECLARE_FAMILIES(1)
+LA_DECLARE_FAMILIES(2)
+LA_DECLARE_FAMILIES(3)
+LA_DECLARE_FAMILIES(4)
+#undef LA_DECLARE_FAMILIES
+
+namespace {
+using FamilyFn = la_status_t (*)(const StepTable&, const Tuning&, uint32_t, void*);
+#define LA_FAMILY_ROW(d) {launch_family_##d##_0, launch_family_##d##_1, launch_family_##d##_2}
+const FamilyFn kFamilies[5][3] = {LA_FAMILY_ROW(0), LA_FAMILY_ROW(1), LA_FAMILY_ROW(2), LA_FAMILY_ROW(3), LA_FAMILY_ROW(4)};
+#undef LA_FAMILY_ROW
+
+// 0: 256 lanes x {1, 2, 4} vectors; 1: 1024 x {1, 2}; 2: 1024 x {4, 8}; -1: no such kernel
+int family_of(const Tuning& tune)
+{
+    const int u = tune.unroll;
+    if (tune.block == 256) return (u == 1 || u == 2 || u == 4) ? 0 : -1;
+    if (tune.block == 1024) return (u == 1 || u == 2) ? 1 : (u == 4 || u == 8) ? 2 : -1;
+    return -1;
+}
+} // namespace
 
 uint32_t tiles_for(uint64_t max_units, const Tuning& tune)
 {
@@ -27,13 +49,10 @@ la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune
     if (!known_op((int)t.op)) return fail(LA_ERR_UNSUPPORTED, "unknown operation %u", t.op);
     const uint64_t blocks = (uint64_t)t.num_segments * t.tiles_per_seg;
     if (blocks > 0x7fffffffull) return fail(LA_ERR_INVALID_ARG, "step needs %llu workgroups", (unsigned long long)blocks);
-    switch (dtype) {
-    case LA_I32: return launch_step_i32(t, tune, (uint32_t)blocks, hip_stream);
-    case LA_F32: return launch_step_f32(t, tune, (uint32_t)blocks, hip_stream);
-    case LA_BF16: return launch_step_bf16(t, tune, (uint32_t)blocks, hip_stream);
-    case LA_F16: return launch_step_f16(t, tune, (uint32_t)blocks, hip_stream);
-    case LA_F64: return launch_step_f64(t, tune, (uint32_t)blocks, hip_stream);
-    }
+    const int family = family_of(tune);
+    if (family < 0)
+        return fail(LA_ERR_INVALID_ARG, "unsupported launch shape: %d lanes x %d vectors", tune.block, tune.unroll);
+    if ((int)dtype >= 0 && (int)dtype < 5) return kFamilies[(int)dtype][family](t, tune, (uint32_t)blocks, hip_stream);
     return fail(LA_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
 }
 

@@ -485,61 +485,68 @@ la_status_t launch_policy(const StepTable& t, int policy, dim3 grid, hipStream_t
     return LA_OK;
 }
 
-template <typename T, int BLOCK>
-la_status_t launch_unroll(const StepTable& t, const Tuning& tune, dim3 grid, hipStream_t s)
-{
-    switch (tune.unroll) {
-    case 1: return launch_policy<T, 1, BLOCK>(t, tune.cache_policy, grid, s);
-    case 2: return launch_policy<T, 2, BLOCK>(t, tune.cache_policy, grid, s);
-    case 4: return launch_policy<T, 4, BLOCK>(t, tune.cache_policy, grid, s);
-    case 8: // 128 KiB tiles: workgroups of 1024 lanes only
-        if constexpr (BLOCK == 1024) return launch_policy<T, 8, BLOCK>(t, tune.cache_policy, grid, s);
-        break;
-    }
-    return fail(LA_ERR_INVALID_ARG, "unsupported unroll %d for workgroups of %d lanes", tune.unroll, BLOCK);
-}
+// This file is compiled once per element type and launch-shape family
+// (-DLA_KERNEL_DTYPE=<la_dtype_t value> -DLA_KERNEL_SHAPE=<0..2>), so that the instances build in
+// parallel; launch_step in dispatch.cpp picks the family.  Families: 0 = workgroups of 256 lanes
+// (1, 2, 4 vectors per lane), 1 = 1024 lanes with 1 or 2 vectors, 2 = 1024 lanes with 4 or 8.
+#if !defined(LA_KERNEL_DTYPE) || !defined(LA_KERNEL_SHAPE)
+#error "compile kernels.hip with -DLA_KERNEL_DTYPE=0..4 -DLA_KERNEL_SHAPE=0..2"
+#endif
 
-template <typename T>
-la_status_t launch_block(const StepTable& t, const Tuning& tune, dim3 grid, hipStream_t s)
+#if LA_KERNEL_DTYPE == 0
+using ElemTraits = I32;
+#elif LA_KERNEL_DTYPE == 1
+using ElemTraits = F32;
+#elif LA_KERNEL_DTYPE == 2
+using ElemTraits = BF16;
+#elif LA_KERNEL_DTYPE == 3
+using ElemTraits = F16;
+#elif LA_KERNEL_DTYPE == 4
+using ElemTraits = F64;
+#else
+#error "LA_KERNEL_DTYPE must be 0..4"
+#endif
+
+la_status_t launch_family(const StepTable& t, const Tuning& tune, dim3 grid, hipStream_t s)
 {
-    switch (tune.block) {
-    case 256: return launch_unroll<T, 256>(t, tune, grid, s);
-    case 1024: return launch_unroll<T, 1024>(t, tune, grid, s);
+    using T = ElemTraits;
+#if LA_KERNEL_SHAPE == 0
+    if (tune.block == 256) {
+        switch (tune.unroll) {
+        case 1: return launch_policy<T, 1, 256>(t, tune.cache_policy, grid, s);
+        case 2: return launch_policy<T, 2, 256>(t, tune.cache_policy, grid, s);
+        case 4: return launch_policy<T, 4, 256>(t, tune.cache_policy, grid, s);
+        }
     }
-    return fail(LA_ERR_INVALID_ARG, "unsupported block size %d", tune.block);
+#elif LA_KERNEL_SHAPE == 1
+    if (tune.block == 1024) {
+        switch (tune.unroll) {
+        case 1: return launch_policy<T, 1, 1024>(t, tune.cache_policy, grid, s);
+        case 2: return launch_policy<T, 2, 1024>(t, tune.cache_policy, grid, s);
+        }
+    }
+#elif LA_KERNEL_SHAPE == 2
+    if (tune.block == 1024) {
+        switch (tune.unroll) {
+        case 4: return launch_policy<T, 4, 1024>(t, tune.cache_policy, grid, s);
+        case 8: return launch_policy<T, 8, 1024>(t, tune.cache_policy, grid, s); // 128 KiB tiles
+        }
+    }
+#else
+#error "LA_KERNEL_SHAPE must be 0..2"
+#endif
+    return fail(LA_ERR_INVALID_ARG, "internal: %d lanes x %d vectors is not in kernel family %d", tune.block,
+                tune.unroll, (int)LA_KERNEL_SHAPE);
 }
 
 } // namespace
 
-// This file is compiled once per element type (-DLA_KERNEL_DTYPE=<la_dtype_t value>), so that
-// the instances of the five types build in parallel; launch_step in dispatch.cpp picks one.
-#if LA_KERNEL_DTYPE == 0
-la_status_t launch_step_i32(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream)
+#define LA_CONCAT3(a, b, c) a##b##_##c
+#define LA_FAMILY_NAME(d, f) LA_CONCAT3(launch_family_, d, f)
+la_status_t LA_FAMILY_NAME(LA_KERNEL_DTYPE, LA_KERNEL_SHAPE)(const StepTable& t, const Tuning& tune, uint32_t blocks,
+                                                             void* stream)
 {
-    return launch_block<I32>(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
+    return launch_family(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
 }
-#elif LA_KERNEL_DTYPE == 1
-la_status_t launch_step_f32(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream)
-{
-    return launch_block<F32>(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
-}
-#elif LA_KERNEL_DTYPE == 2
-la_status_t launch_step_bf16(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream)
-{
-    return launch_block<BF16>(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
-}
-#elif LA_KERNEL_DTYPE == 3
-la_status_t launch_step_f16(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream)
-{
-    return launch_block<F16>(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
-}
-#elif LA_KERNEL_DTYPE == 4
-la_status_t launch_step_f64(const StepTable& t, const Tuning& tune, uint32_t blocks, void* stream)
-{
-    return launch_block<F64>(t, tune, dim3(blocks), static_cast<hipStream_t>(stream));
-}
-#else
-#error "compile kernels.hip with -DLA_KERNEL_DTYPE=0..4"
-#endif
 
 } // namespace la
