@@ -1,6 +1,8 @@
 // Topology and schedule generator: turns (nodes, GPUs per node, processes per GPU) into the
 // per-step segment tables of Algorithm 1 (ring_allreduce) and Algorithm 2 (lane_allreduce, also
-// in its multiple-processes-per-GPU form).  Host code only.
+// in its multiple-processes-per-GPU form), of the shared-buffer model's standard and multi-lane
+// approaches, and of recursive doubling and Rabenseifner's algorithm (Background section); plus
+// the passes that derive the staged, out-of-place, stand-alone-half and fused forms.  Host code only.
 #include <algorithm>
 #include <cstdio>
 #include <cstring>

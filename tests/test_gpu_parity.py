@@ -787,6 +787,31 @@ def full_size_case(oracle, topo, algo, n, dist, flags=la.LA_SCHED_DEFAULT, tol=T
     assert np.array_equal(bits(ref[P - 1]), bits(ref[0]))
 
 
+@pytest.mark.parametrize("algo,topo", [("lane", (2, 1, 1)), ("ring", (1, 2, 1)), ("lane_multiproc", (1, 1, 2))])
+def test_buffers_beyond_4_GiB_use_64_bit_offsets(oracle, algo, topo):
+    """More than 2^32 bytes per rank buffer: segment offsets, tile offsets and lengths must not
+    pass through 32 bits anywhere (int32 data, wrapping sums: bit-exact against the oracle)."""
+    n = (1 << 30) + 12345
+    x = np.empty((2, n), dtype=np.int32)
+    base = np.arange(n, dtype=np.uint32)
+    np.multiply(base, np.uint32(2654435761), out=x[0].view(np.uint32))
+    np.multiply(base, np.uint32(40503), out=x[1].view(np.uint32))
+    x[1] += 7
+    del base
+    sched = la.la_schedule_build(la.la_topology_create(*topo), algo, n, "int32")
+    bufs = [to_dev(x[r]) for r in range(2)]
+    la.allreduce_tensors(sched, bufs)
+    torch.cuda.synchronize()
+    assert torch.equal(bufs[0], bufs[1])
+    got0 = to_host(bufs[0])
+    del bufs
+    torch.cuda.empty_cache()
+    want = (x[0].view(np.uint32) + x[1].view(np.uint32)).view(np.int32)   # two operands: the definition itself
+    assert np.array_equal(got0, want)
+    ref = oracle.allreduce(algo, *topo, x, in_place=True)
+    assert np.array_equal(got0, ref[0]) and np.array_equal(ref[1], ref[0])
+
+
 def test_config2_lane_16_ranks_16Mi_fp32(oracle):
     full_size_case(oracle, (4, 4, 1), "lane", 1 << 24, "normal")
 
