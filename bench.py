@@ -27,6 +27,13 @@ MEASURED_TRAFFIC = {
     ("c2", "lane", 0, "S1"): 1342241997,
     ("c2", "lane", 0, "S2"): 536937472,
     ("c2", "lane", 0, "S3"): 1074858496,
+    # profiles/seg_reduce_kernel_c3_c4_c5.md
+    ("c3", "lane_multiproc", 0, "S1"): 2147856589 + 134217728,
+    ("c3", "lane_multiproc", 0, "S3"): 134572237 + 2015258931,
+    ("c4", "lane_multiproc", 0, "S1"): 4295142195 + 536914432,
+    ("c4", "lane_multiproc", 0, "S3"): 537037005 + 3758096384,
+    ("c5", "lane_multiproc", 0, "S1"): 4296499405 + 134217728,
+    ("c5", "lane_multiproc", 0, "S3"): 135162470 + 4164543232,
 }
 
 CONFIGS = {
