@@ -33,7 +33,7 @@ MEASURED_TRAFFIC = {
     ("c4", "lane_multiproc", 0, "S1"): 4295142195 + 536914432,
     ("c4", "lane_multiproc", 0, "S3"): 537037005 + 3758096384,
     ("c5", "lane_multiproc", 0, "S1"): 4296499405 + 134217728,
-    ("c5", "lane_multiproc", 0, "S3"): 135162470 + 4164543232,
+    ("c5", "lane_multiproc", 0, "S3"): 135162470 + 4164543181,
 }
 
 CONFIGS = {
