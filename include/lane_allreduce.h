@@ -283,7 +283,7 @@ const char* la_last_error(void);
  *                 steps with several destinations and c for copy / broadcast steps.
  *   "block"       lanes per workgroup: 256, 1024; 0 = automatic
  *   "graph"       1: la_allreduce_emulated replays the schedule as one HIP graph of kernel nodes,
- *                 0: it launches step by step, -1 (default): graph for schedules of 8+ launches
+ *                 0: it launches step by step, -1 (default): graph for schedules of 16+ launches
  * la_tuning_set returns LA_ERR_INVALID_ARG for an unknown key or value; la_tuning_get returns
  * the current setting, or -2 for an unknown key. */
 la_status_t la_tuning_set(const char* key, int value);
