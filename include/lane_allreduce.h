@@ -229,10 +229,12 @@ la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_
  *   n, dtype    must equal the values the schedule was built with.
  *   hip_stream  a hipStream_t (NULL = the default stream).  The call enqueues one kernel per
  *               step and returns without synchronising.
- * A schedule caches the device addresses it was last run with; a call with other buffers waits
- * for the schedule's previous work before rebinding.  Schedules with many launches (the ring
- * forms) are recorded once per binding into a HIP graph of kernel nodes and replayed.  Calls on one schedule must come from one
- * thread at a time.
+ * A schedule remembers the last 8 buffer sets it was run with (1 if it owns a staging area) and
+ * keeps their resolved tables on the device; a call with a set it does not remember uploads
+ * tables with a synchronous copy, after waiting for the work of the set it forgets in exchange.
+ * Schedules of 16 or more launches (the ring forms) are recorded once per buffer set into a HIP
+ * graph of kernel nodes and replayed.  Calls on one schedule are serialised by the library;
+ * different schedules can be used from different host threads at the same time.
  * int32 wraps; fp32 adds are IEEE, in the fixed operand order of the tables; bf16 operands are
  * widened to fp32, summed in fp32 and rounded to nearest-even once per reduce step.
  */

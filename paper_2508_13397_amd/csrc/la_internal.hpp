@@ -124,7 +124,9 @@ struct la_schedule {
     std::vector<std::vector<la::Part>> owned; // per buffer: ranges it holds fully reduced between the halves
     // device-side state, created by the first run
     mutable std::mutex mu;
-    mutable la_binding* bound = nullptr;
+    // the buffer sets the schedule has been run on lately, most recent first (a few, so that a
+    // caller that alternates between buffer sets does not re-upload tables on every call)
+    mutable std::vector<la_binding*> bound;
 };
 
 namespace la {

@@ -142,6 +142,7 @@ struct la_binding {
     Tuning requested;           // the process-wide setting the launch shapes were derived from
     std::vector<Tuning> shape;  // per step
     void* tables = nullptr;     // one device allocation holding every step's tables
+    size_t tables_bytes = 0;
     void* staging = nullptr;    // library-owned staging area (LA_SCHED_STAGED)
     hipEvent_t last_use = nullptr;
     bool used = false;
@@ -318,28 +319,47 @@ la_status_t check_buffers(const la_schedule& s, void* const* bufs, const void* c
 // captures, across all schedules of the process.
 std::mutex g_device_mu;
 
-// Make sched.bound describe `addr` on the current device with the current tile shape.
+constexpr size_t MAX_BINDINGS = 8;
+
+// Make sched.bound.front() describe `addr` on the current device with the current tile shape.
 la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning& tune)
 {
     int dev = -1;
     LA_HIP(hipGetDevice(&dev));
-    la_binding* b = s.bound;
     const int P = s.nbuf;
     const std::vector<uint64_t> key = addr; // caller addresses only: the staging slot is still 0
-    if (b && b->device == dev && b->requested == tune && b->bufs == key) return LA_OK;
+    for (size_t i = 0; i < s.bound.size(); ++i) {
+        la_binding* c = s.bound[i];
+        if (c->device == dev && c->requested == tune && c->bufs == key) {
+            if (i) std::rotate(s.bound.begin(), s.bound.begin() + i, s.bound.begin() + i + 1); // to the front
+            return LA_OK;
+        }
+    }
     std::lock_guard<std::mutex> device_lock(g_device_mu); // not while another schedule records its graph
-    if (b && b->used) LA_HIP(hipEventSynchronize(b->last_use)); // earlier work still reads the tables
-    if (b && b->device != dev) {
-        release_binding(b);
-        s.bound = b = nullptr;
+    la_binding* b = nullptr;
+    // a staged schedule owns a staging area per binding, which can be large: keep one
+    const size_t keep = s.staging_elems ? 1 : MAX_BINDINGS;
+    if (s.bound.size() >= keep) {
+        // recycle the least recently used one (its allocations are reused when it is on this device)
+        b = s.bound.back();
+        s.bound.pop_back();
+        if (b->used) (void)hipEventSynchronize(b->last_use); // earlier work still reads its tables
+        if (b->device != dev) {
+            release_binding(b);
+            b = nullptr;
+        }
     }
     if (!b) {
         b = new (std::nothrow) la_binding;
         if (!b) return fail(LA_ERR_OUT_OF_MEMORY, "out of host memory");
         b->device = dev;
-        s.bound = b;
-        LA_HIP(hipEventCreateWithFlags(&b->last_use, hipEventDisableTiming));
+        if (hipEventCreateWithFlags(&b->last_use, hipEventDisableTiming) != hipSuccess) {
+            delete b;
+            return fail(LA_ERR_DEVICE, "hipEventCreate failed");
+        }
     }
+    s.bound.insert(s.bound.begin(), b);
+    b->bufs.clear(); // not a match for anything until it is complete
     const size_t e = dtype_size(s.dtype);
     if (s.staging_elems && !b->staging) {
         if (hipMalloc(&b->staging, s.staging_elems * e) != hipSuccess) {
@@ -356,14 +376,16 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     } catch (const std::bad_alloc&) {
         return fail(LA_ERR_OUT_OF_MEMORY, "out of host memory");
     }
-    if (b->tables) {
+    if (b->tables && b->tables_bytes != ht.blob.size()) {
         LA_HIP(hipFree(b->tables));
         b->tables = nullptr;
     }
-    b->bufs.clear();
-    if (hipMalloc(&b->tables, ht.blob.size()) != hipSuccess) {
-        b->tables = nullptr;
-        return fail(LA_ERR_OUT_OF_MEMORY, "cannot allocate %zu bytes of device tables", ht.blob.size());
+    if (!b->tables) {
+        if (hipMalloc(&b->tables, ht.blob.size()) != hipSuccess) {
+            b->tables = nullptr;
+            return fail(LA_ERR_OUT_OF_MEMORY, "cannot allocate %zu bytes of device tables", ht.blob.size());
+        }
+        b->tables_bytes = ht.blob.size();
     }
     LA_HIP(hipMemcpy(b->tables, ht.blob.data(), ht.blob.size(), hipMemcpyHostToDevice));
     relocate(ht.view, b->tables);
@@ -421,7 +443,7 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void*
     const Tuning tune = current_tuning();
     st = bind(*sched, addr, tune);
     if (st != LA_OK) return st;
-    la_binding* b = sched->bound;
+    la_binding* b = sched->bound.front();
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int mode = g_graph.load();
     const bool whole = first == 0 && last == (int)sched->steps.size();

@@ -913,7 +913,7 @@ la_status_t la_schedule_build(const la_topology_t* topo, la_algo_t algo, size_t 
 la_status_t la_schedule_destroy(la_schedule_t* sched)
 {
     if (!sched) return LA_OK;
-    release_binding(sched->bound);
+    for (la_binding* b : sched->bound) release_binding(b);
     delete sched;
     return LA_OK;
 }

@@ -282,6 +282,32 @@ def test_side_stream_rebinding_and_repeated_calls(oracle):
     assert np.array_equal(bits(np.stack([to_host(v) for v in b])), bits(oracle.allreduce("lane_multiproc", *topo, rolled)))
 
 
+@pytest.mark.parametrize("flags", [0, la.LA_SCHED_STAGED])
+def test_one_schedule_many_buffer_sets(oracle, flags):
+    """A schedule remembers the last few buffer sets it ran on (one, when it owns a staging area):
+    alternate between three sets, then cycle through ten so that remembered ones are recycled."""
+    topo, n = (2, 2, 2), 30011
+    P = 8
+    sched = la.la_schedule_build(la.la_topology_create(*topo), "lane_multiproc", n, "float32", flags)
+    xs = [make(P, n, "f32order", seed=100 + i) for i in range(10)]
+    refs = [oracle.allreduce("lane_multiproc", *topo, x) for x in xs]
+    sets = [[to_dev(x[r]) for r in range(P)] for x in xs]
+    state = list(xs)
+    for rnd in range(3):
+        for i in (0, 1, 2, 0, 2, 1):
+            la.allreduce_tensors(sched, sets[i])
+            state[i] = oracle.allreduce("lane_multiproc", *topo, state[i])
+    for rnd in range(2):
+        for i in range(10):
+            la.allreduce_tensors(sched, sets[i])
+            state[i] = oracle.allreduce("lane_multiproc", *topo, state[i])
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(state[9]), bits(oracle.allreduce("lane_multiproc", *topo, refs[9])))
+    for i in range(10):
+        got = np.stack([to_host(b) for b in sets[i]])
+        assert np.array_equal(bits(got), bits(state[i])), i
+
+
 def test_two_host_threads_with_their_own_schedules_and_streams(oracle):
     """Handles are independent: two host threads, each with its own schedule, buffers and stream,
     call the library at the same time (ctypes releases the interpreter lock during the call);
