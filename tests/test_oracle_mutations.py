@@ -156,7 +156,10 @@ def test_planted_mistake_is_caught(tmp_path, name, old, new):
         "        sys.exit(3)\n"
         "sys.exit(0)\n"
     ) % ([os.path.dirname(os.path.dirname(SRC)), os.path.dirname(__file__)], lib)
-    rc = subprocess.run([sys.executable, "-c", code], capture_output=True).returncode
+    try:
+        rc = subprocess.run([sys.executable, "-c", code], capture_output=True, timeout=300).returncode
+    except subprocess.TimeoutExpired:
+        rc = 124  # a build that corrupts memory may also hang: the child is killed, the mistake is noticed
     assert rc != 0, f"no pin notices the planted mistake {name!r}"
 
 
