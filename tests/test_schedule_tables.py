@@ -532,6 +532,62 @@ def test_single_launch_bytes_are_the_lower_bound():
     assert totals(one) == (16 * n * e, 16 * n * e)      # every input read once, every output written once
 
 
+# ----------------------------------------------------------------------------- random flag combinations
+
+def test_random_flag_combinations_either_refused_or_equal_to_the_oracle(oracle):
+    """Seeded sweep over algorithms x flag subsets x topologies x lengths: a combination is either
+    refused with an argument error, or its tables reproduce the oracle bit for bit (fp32 and bf16
+    order-sensitive inputs, wrapping int32).  Guards the passes that are layered on one another (staging,
+    out-of-place, shared buffers, the fused forms) against combinations no other test names."""
+    rng = np.random.default_rng(20250813)
+    bits_pool = [la.LA_SCHED_P2P_GATHER, la.LA_SCHED_STAGED, la.LA_SCHED_INNER_RING, SHARED, la.LA_SCHED_OUT_OF_PLACE,
+                 la.LA_SCHED_FUSED_GATHER, la.LA_SCHED_SINGLE_LAUNCH]
+    algos = ["ring", "lane", "lane_multiproc", "recursive_doubling", "rabenseifner"]
+    ran = refused = 0
+    seen = set()
+    for case in range(1200):
+        algo = algos[rng.integers(len(algos))]
+        flags = 0
+        for b in bits_pool:
+            if rng.random() < 0.3:
+                flags |= b
+        N, G, Q = (int(v) for v in rng.integers(1, 5, size=3))
+        if algo in ("recursive_doubling", "rabenseifner"):
+            N, G, Q = (int(v) for v in 2 ** rng.integers(0, 3, size=3))
+        n = int(rng.integers(1, 70))
+        topo = la.la_topology_create(N, G, Q)
+        dt = ("float32", "bfloat16", "int32")[case % 3]
+        try:
+            sched = la.la_schedule_build(topo, algo, n, dt, flags)
+        except la.LaError as err:
+            assert err.status in (la.LA_ERR_INVALID_ARG, la.LA_ERR_UNSUPPORTED), (algo, flags)
+            refused += 1
+            continue
+        B = sched.num_buffers
+        assert B == (N * G if flags & SHARED else N * G * Q)
+        x = synth.order_sensitive_f32(B, n)
+        if dt == "bfloat16":
+            x = synth.to_bf16_bits(x * np.float32(2.0 ** -20))
+        elif dt == "int32":
+            x = rng.integers(-(1 << 31), 1 << 31, size=(B, n), dtype=np.int64).astype(np.int32)
+        if flags & SHARED:
+            name, Qo = ("lane_multiproc", 1) if algo == "lane" else (algo, Q)
+            ref = oracle.allreduce(name, N, G, Qo, x, shared=True)
+        else:
+            # the point-to-point gather and the inner ring are ignored where there is no inter-node stage
+            lane = algo in ("lane", "lane_multiproc")
+            ref = oracle.allreduce(oracle_name(algo, flags) if lane else algo, N, G, Q, x)
+        if flags & la.LA_SCHED_OUT_OF_PLACE:
+            got, send = run_tables_out_of_place(sched, x)
+            assert np.array_equal(send.view(np.uint8), x.view(np.uint8))
+        else:
+            got = run_tables(sched, x)
+        assert np.array_equal(got.view(np.uint8), ref.view(np.uint8)), (algo, flags, N, G, Q, n)
+        ran += 1
+        seen.add((algo, flags))
+    assert ran >= 450 and refused >= 90 and len(seen) >= 100, (ran, refused, len(seen))
+
+
 # ----------------------------------------------------------------------------- stand-alone halves
 
 RS, AG = la.LA_SCHED_ONLY_REDUCE_SCATTER, la.LA_SCHED_ONLY_ALLGATHER
