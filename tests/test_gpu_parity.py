@@ -788,6 +788,59 @@ def test_reduce_segments_many_segments_and_misaligned_sources(oracle):
     assert np.array_equal(bits(to_host(dst)), bits(ref))
 
 
+# ------------------------------------------------------------------------------ random combinations
+
+def test_random_flag_combinations_on_the_gpu(oracle):
+    """Seeded sweep: algorithm x flag subset x topology x length x type; whatever the library
+    accepts must equal the oracle bit for bit, in place or out of place."""
+    rng = np.random.default_rng(813397)
+    pool = [la.LA_SCHED_P2P_GATHER, la.LA_SCHED_STAGED, la.LA_SCHED_INNER_RING, la.LA_SCHED_SHARED_BUFFERS,
+            la.LA_SCHED_OUT_OF_PLACE, la.LA_SCHED_FUSED_GATHER, la.LA_SCHED_SINGLE_LAUNCH]
+    algos = ["ring", "lane", "lane_multiproc", "recursive_doubling", "rabenseifner"]
+    ran = 0
+    for case in range(900):
+        algo = algos[rng.integers(len(algos))]
+        flags = 0
+        for b in pool:
+            if rng.random() < 0.3:
+                flags |= b
+        N, G, Q = (int(v) for v in rng.integers(1, 4, size=3))
+        if algo in ("recursive_doubling", "rabenseifner"):
+            N, G, Q = (int(v) for v in 2 ** rng.integers(0, 3, size=3))
+        n = int(rng.choice([1, 7, 255, 4099, 40961, 150001]))
+        kind = ("f32order", "bf16", "i32wrap")[case % 3]
+        topo = la.la_topology_create(N, G, Q)
+        try:
+            sched = la.la_schedule_build(topo, algo, n, NAME[make(1, 1, kind).dtype], flags)
+        except la.LaError as err:
+            assert err.status in (la.LA_ERR_INVALID_ARG, la.LA_ERR_UNSUPPORTED)
+            continue
+        B = sched.num_buffers
+        x = make(B, n, kind, seed=case)
+        print("random case", case, algo, flags, (N, G, Q), n, kind, flush=True)
+        if flags & la.LA_SCHED_SHARED_BUFFERS:
+            name, Qo = ("lane_multiproc", 1) if algo == "lane" else (algo, Q)
+            ref = oracle.allreduce(name, N, G, Qo, x, shared=True)
+        else:
+            ref = oracle.allreduce(oracle_name(algo, flags) if algo.startswith("lane") else algo, N, G, Q, x)
+        if flags & la.LA_SCHED_OUT_OF_PLACE:
+            send = [to_dev(x[r]) for r in range(B)]
+            recv = [torch.full_like(send[r], 3) for r in range(B)]
+            la.la_allreduce_emulated_out_of_place(sched, [t.data_ptr() for t in send], [t.data_ptr() for t in recv], n,
+                                                  NAME[x.dtype], la.LA_SUM, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(np.stack([to_host(t) for t in send])), bits(x))
+            got = np.stack([to_host(t) for t in recv])
+        else:
+            bufs = [to_dev(x[r]) for r in range(B)]
+            la.allreduce_tensors(sched, bufs)
+            torch.cuda.synchronize()
+            got = np.stack([to_host(t) for t in bufs])
+        assert np.array_equal(bits(got), bits(ref)), (case, algo, flags, (N, G, Q), n, kind)
+        ran += 1
+    assert ran >= 350, ran
+
+
 # ------------------------------------------------------------------------------ full-size configs
 
 def full_size_case(oracle, topo, algo, n, dist, flags=la.LA_SCHED_DEFAULT, tol=True):
