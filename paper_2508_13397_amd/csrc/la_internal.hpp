@@ -79,7 +79,7 @@ struct StepTable {
 struct Tuning {
     int unroll = 0;       // 16-byte vectors per lane and operand: 1, 2, 4, 8
     int cache_policy = -1; // 0..7, see Policy<> in kernels.hip
-    int block = 0;        // lanes per workgroup: 256, 512, 1024
+    int block = 0;        // lanes per workgroup: 256, 1024
     bool operator==(const Tuning& o) const
     {
         return unroll == o.unroll && block == o.block && cache_policy == o.cache_policy;
