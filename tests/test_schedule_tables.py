@@ -36,6 +36,43 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, name) is not None
 
 
+def test_binding_fails_loudly_when_the_library_is_not_built():
+    """No fallback: with the shared library absent every entry point of the binding raises."""
+    import subprocess
+    import sys
+
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "import paper_2508_13397_amd.binding as b\n"
+        "b.LIB_PATH = b.LIB_PATH + '.absent'\n"
+        "import paper_2508_13397_amd as la\n"
+        "for call in (lambda: la.lib(), lambda: la.la_topology_create(2, 2, 1), lambda: la.la_status_string(0)):\n"
+        "    try:\n"
+        "        call()\n"
+        "    except ImportError as e:\n"
+        "        assert 'no CPU fallback' in str(e)\n"
+        "    else:\n"
+        "        sys.exit(5)\n"
+        "assert 'oracle' not in sys.modules\n"
+        "sys.exit(0)\n"
+    ) % ROOT
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr[-1500:]
+
+
+def test_product_package_does_not_import_the_oracle():
+    """the oracle is test infrastructure: nothing under the package, nor the library's sources,
+    names it"""
+    pkg = os.path.join(ROOT, "paper_2508_13397_amd")
+    for base, _, files in os.walk(pkg):
+        if "_build" in base or "__pycache__" in base:
+            continue
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hpp", ".hip", ".h")):
+                text = open(os.path.join(base, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "la_oracle" not in text, f
+
+
 def test_status_strings():
     assert la.la_status_string(la.LA_OK) == "LA_OK"
     assert la.la_status_string(la.LA_ERR_INVALID_ARG) == "LA_ERR_INVALID_ARG"
