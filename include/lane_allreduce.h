@@ -70,7 +70,8 @@ enum {
     /* All-gather stages as one copy segment per (source, destination) pair, and the inter-node
      * all-reduce as two steps (reduce-scatter of pieces, then all-gather of pieces).  Without
      * it a reduced piece is written to all its destinations by the launch that produces or
-     * first reads it (multi-destination store), so it is read from HBM once. */
+     * first reads it (multi-destination store), so it is read from HBM once.  Schedules without
+     * an all-gather of that kind (ring, recursive doubling, Rabenseifner) ignore the flag. */
     LA_SCHED_P2P_GATHER = 1u,
     /* Staged exchange: before every reduce step the incoming segments are first copied into a
      * contiguous staging area owned by the library ("the message"), and the reduce reads them
@@ -81,7 +82,8 @@ enum {
     /* Lane schedules only: the inter-node all-reduce of every part is Algorithm 1 run on the lane
      * communicator (the variant of the Results section "where the ring algorithm is used in the
      * inter-node stage of the multi-lane all-reduce"): 2(N-1) launches, each one ring iteration
-     * of all lane communicators, instead of the direct N-way exchange.  Ignored by LA_ALGO_RING. */
+     * of all lane communicators, instead of the direct N-way exchange.  Ignored by the algorithms
+     * that have no inter-node stage (ring, recursive doubling, Rabenseifner). */
     LA_SCHED_INNER_RING = 4u,
     /* The shared-buffer model of "Multiple Processes Per GPU": one buffer per GPU (bufs holds
      * nodes * gpus_per_node pointers, index node * gpus_per_node + gpu); the procs_per_gpu
@@ -118,15 +120,16 @@ enum {
      * each reduced piece to all N * R rank buffers (k = N, m = N * R; with one node the intra-node
      * reduce does it: k = R, m = R).  Same sums in the same order, so the result is bit-identical
      * to the unfused schedule; the launch that re-reads every owner's part to copy it is gone
-     * (N * n elements less to read; the writes are the same).  An emulation-level fusion: between real ranks the
-     * two all-gathers use different networks.  Excludes P2P_GATHER, INNER_RING and the halves. */
+     * (N * n elements less to read; the writes are the same).  An emulation-level fusion: between
+     * real ranks the two all-gathers use different networks.  Excludes P2P_GATHER, INNER_RING and
+     * the halves. */
     LA_SCHED_FUSED_GATHER = 128u,
     /* Lane schedules: the whole of Algorithm 2 as ONE launch.  Piece v of part j is computed as a
      * two-level sum straight from the inputs: for every node, its R rank buffers in ascending
      * node-local index (what MPI_Reduce_scatter on the node group leaves at the owner, rounded to
      * the element type as that result is when it is stored), then the node results in ascending
      * node order (the lane all-reduce); the result is stored to all N * R rank buffers (both
-     * all-gathers).  k = m = N * R, la_schedule_step_group() = R.  Bit-identical to the staged
+     * all-gathers).  k = m = N * R, la_schedule_step_group() = R.  Bit-identical to the three-stage
      * schedule; every input is read once and every output written once, the lower bound of the
      * definition.  Like LA_SCHED_FUSED_GATHER a fusion of the emulation, not of the algorithm.
      * Combines only with LA_SCHED_SHARED_BUFFERS and LA_SCHED_OUT_OF_PLACE. */
