@@ -73,6 +73,36 @@ def test_product_package_does_not_import_the_oracle():
                 assert "import oracle" not in text and "from oracle" not in text and "la_oracle" not in text, f
 
 
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: the header compiles as strict C99 (and as C++), and a C program
+    that uses only host-side calls links against the shared library and runs without a GPU."""
+    import subprocess
+
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "consumer.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "lane_allreduce.h"\n'
+        "int main(void) {\n"
+        "    la_topology_t* t = 0; la_schedule_t* s = 0; size_t rd = 0, wr = 0; int k = 0, m = 0;\n"
+        "    if (la_topology_create(4, 4, 1, &t) != LA_OK || la_topology_num_ranks(t) != 16) return 1;\n"
+        "    if (la_schedule_build(t, LA_ALGO_LANE, 1u << 20, LA_F32, &s) != LA_OK) return 2;\n"
+        "    if (la_schedule_num_steps(s) != 3) return 3;\n"
+        "    if (la_schedule_step_info(s, 0, 0, 0, 0, 0, &k, &m, &rd, &wr) != LA_OK || k != 4 || m != 1) return 4;\n"
+        "    if (rd != (size_t)16 << 22 || wr != (size_t)4 << 22) return 5;\n"
+        '    if (la_schedule_build(t, LA_ALGO_LANE, 0, LA_F32, &s) != LA_ERR_INVALID_ARG || !la_last_error()[0]) return 6;\n'
+        '    printf("%s\\n", la_status_string(LA_OK));\n'
+        "    return la_schedule_destroy(s) == LA_OK && la_topology_destroy(t) == LA_OK ? 0 : 7;\n"
+        "}\n")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    subprocess.run(["g++", "-std=c++11", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)], check=True)
+    exe = str(tmp_path / "consumer")
+    libdir = os.path.join(ROOT, "paper_2508_13397_amd")
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", exe, "-L", libdir, "-llaneallreduce",
+                    "-Wl,-rpath," + libdir], check=True)
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.strip() == "LA_OK", (r.returncode, r.stdout, r.stderr[-500:])
+
+
 def test_status_strings():
     assert la.la_status_string(la.LA_OK) == "LA_OK"
     assert la.la_status_string(la.LA_ERR_INVALID_ARG) == "LA_ERR_INVALID_ARG"
