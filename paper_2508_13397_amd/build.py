@@ -57,6 +57,20 @@ def build(force: bool = True, verbose: bool = False, jobs: int = 8) -> str:
     return LIB
 
 
+def build_consumer(verbose: bool = False) -> str:
+    """tests/consumer/consumer.exe: a HIP host program that uses the library through its C header
+    only (no Python, no torch in the process); the GPU tests run it."""
+    src = os.path.join(ROOT, "tests", "consumer", "consumer.cpp")
+    exe = os.path.join(ROOT, "tests", "consumer", "consumer.exe")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), src, "-o", exe,
+           "-L", HERE, "-llaneallreduce", "-Wl,-rpath,$ORIGIN/../../paper_2508_13397_amd"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 if __name__ == "__main__":
     build(force=True, verbose="-q" not in sys.argv)
+    build_consumer(verbose="-q" not in sys.argv)
     print(LIB)

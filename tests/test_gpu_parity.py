@@ -89,6 +89,20 @@ def check_tolerance(oracle, x, got0):
     assert np.all(err <= tol * mag), f"max err/mag = {np.max(err / np.maximum(mag, 1e-300)):.3e}"
 
 
+def test_c_abi_consumer_without_python_or_torch():
+    """tests/consumer/consumer.exe (built by build()) allocates with HIP, calls the library
+    through the C header alone and checks int32 all-reduces of seven schedules against the
+    definition."""
+    import os
+    import subprocess
+
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "consumer", "consumer.exe")
+    assert os.path.exists(exe), "run __graft_entry__.build() first: tests/consumer/consumer.exe is missing"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.strip().endswith("all ok"), (r.returncode, r.stdout[-1500:], r.stderr[-1500:])
+
+
+# ------------------------------------------------------------------------------ config 1
 # ------------------------------------------------------------------------------ config 1
 
 @pytest.mark.parametrize("kind", ["i32", "f32"])
