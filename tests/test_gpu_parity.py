@@ -772,6 +772,51 @@ def test_paper_size_8_nodes_4_gpus_16_procs_128Mi_fp32(oracle, algo, extra):
     assert np.array_equal(bits(got0), bits(ref[0]))
 
 
+def test_largest_paper_topology_128_buffers_of_1_GiB(oracle):
+    """32 nodes x 4 GPUs (the largest node count of the Results section) at 2^28 elements per GPU
+    buffer, 16 processes per GPU: 128 GiB resident in one GPU's HBM.  Too large for the schedule
+    oracle on the host, so: int32 data generated on the device from per-buffer seeds, every buffer
+    must end bit-equal to buffer 0, and 200,000 sampled columns (plus both ends of every slice
+    boundary region) must equal the definition, the wrapping sum, computed by the oracle from the
+    inputs of those columns."""
+    N, G, Q, n = 32, 4, 16, 1 << 28
+    B = N * G
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < (B * n * 4) * 1.05:
+        pytest.skip("needs 135 GiB of free device memory")
+    idx = np.unique(np.concatenate([np.arange(0, 2048), np.arange(n - 2048, n), np.arange(n // 2 - 1024, n // 2 + 1024),
+                                    np.random.default_rng(3).integers(0, n, 200000)]))
+    didx = torch.from_numpy(idx).cuda()
+
+    def inputs():
+        out = []
+        for b in range(B):
+            g = torch.Generator(device="cuda")
+            g.manual_seed(synth.BASE_SEED + b)
+            out.append(torch.randint(-(1 << 31), (1 << 31) - 1, (n,), dtype=torch.int32, device="cuda", generator=g))
+        return out
+
+    want = None
+    for algo, flags in (("lane_multiproc", SHARED), ("lane_multiproc", SHARED | la.LA_SCHED_FUSED_GATHER), ("ring", SHARED)):
+        work = inputs()
+        cols = np.stack([t[didx].cpu().numpy() for t in work])
+        if want is None:
+            want = oracle.definition_sum(cols)
+        else:
+            assert np.array_equal(oracle.definition_sum(cols), want)   # the same inputs again
+        sched = la.la_schedule_build(la.la_topology_create(N, G, Q), algo, n, "int32", flags)
+        print("running", algo, flags, flush=True)
+        la.allreduce_tensors(sched, work)
+        torch.cuda.synchronize()
+        for b in range(1, B):
+            assert torch.equal(work[b], work[0]), (algo, flags, b)
+        got = work[0][didx].cpu().numpy()
+        assert np.array_equal(got, want), (algo, flags)
+        del work, sched
+        torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("kind", ["i32wrap", "f32order", "bf16"])
 def test_reduce_segments_matches_oracle(oracle, kind):
     n = 200000
