@@ -776,9 +776,9 @@ def test_largest_paper_topology_128_buffers_of_1_GiB(oracle):
     """32 nodes x 4 GPUs (the largest node count of the Results section) at 2^28 elements per GPU
     buffer, 16 processes per GPU: 128 GiB resident in one GPU's HBM.  Too large for the schedule
     oracle on the host, so: int32 data generated on the device from per-buffer seeds, every buffer
-    must end bit-equal to buffer 0, and 200,000 sampled columns (plus both ends of every slice
-    boundary region) must equal the definition, the wrapping sum, computed by the oracle from the
-    inputs of those columns."""
+    must end bit-equal to buffer 0, and 200,000 sampled columns (plus the ends and the middle of
+    the buffer) must equal the definition, the wrapping sum, computed by the oracle from the inputs
+    of those columns; then fp32 data against the schedule oracle on the sampled columns."""
     N, G, Q, n = 32, 4, 16, 1 << 28
     B = N * G
     torch.cuda.empty_cache()
@@ -813,6 +813,33 @@ def test_largest_paper_topology_128_buffers_of_1_GiB(oracle):
             assert torch.equal(work[b], work[0]), (algo, flags, b)
         got = work[0][didx].cpu().numpy()
         assert np.array_equal(got, want), (algo, flags)
+        del work, sched
+        torch.cuda.empty_cache()
+
+    # fp32, bit for bit: in Algorithm 2 the order in which an element is summed (the GPUs of a node
+    # in ascending order, then the nodes in ascending order) does not depend on where the element
+    # lies in the buffer, so the schedule oracle run on the sampled columns alone gives the bits
+    # every sampled element must have.
+    def finputs():
+        out = []
+        for b in range(B):
+            g = torch.Generator(device="cuda")
+            g.manual_seed(synth.BASE_SEED + 1000 + b)
+            out.append(torch.rand(n, dtype=torch.float32, device="cuda", generator=g).mul_(2.0).sub_(1.0))
+        return out
+
+    for flags in (SHARED, SHARED | la.LA_SCHED_SINGLE_LAUNCH):
+        work = finputs()
+        cols = np.stack([t[didx].cpu().numpy() for t in work])
+        ref = oracle.allreduce("lane_multiproc", N, G, Q, cols, shared=True)
+        sched = la.la_schedule_build(la.la_topology_create(N, G, Q), "lane_multiproc", n, "float32", flags)
+        print("running fp32", flags, flush=True)
+        la.allreduce_tensors(sched, work)
+        torch.cuda.synchronize()
+        for b in range(1, B):
+            assert torch.equal(work[b].view(torch.int32), work[0].view(torch.int32)), (flags, b)
+        got = work[0][didx].cpu().numpy()
+        assert np.array_equal(bits(got), bits(ref[0])), flags
         del work, sched
         torch.cuda.empty_cache()
 
