@@ -769,6 +769,16 @@ def test_halves_shapes_and_bytes():
     assert ring_rs.num_steps == ring_ag.num_steps == P - 1
     assert {x["stage_name"] for x in ring_rs.steps()} == {"ring-RS"} and {x["stage_name"] for x in ring_ag.steps()} == {"ring-AG"}
     lane = la.la_schedule_build(t, "lane", n, "float32", RS)
+    # the C call reports the count whatever the capacity and writes at most `capacity` pairs
+    import ctypes
+    sh = la.la_schedule_build(t, "lane_multiproc", n, "float32", RS | SHARED)     # 2 processes: 2 ranges per buffer
+    offs, lens = (ctypes.c_uint64 * 4)(9, 9, 9, 9), (ctypes.c_uint64 * 4)(9, 9, 9, 9)
+    L = la.lib()
+    assert L.la_schedule_owned_ranges(sh.handle, 0, 0, None, None) == 2
+    assert L.la_schedule_owned_ranges(sh.handle, 0, 1, offs, lens) == 2 and (offs[1], lens[1]) == (9, 9) and lens[0] == n // 32
+    assert L.la_schedule_owned_ranges(sh.handle, 0, 4, offs, lens) == 2 and offs[1] == n // 2 and offs[2] == 9
+    assert L.la_schedule_owned_ranges(sh.handle, 99, 4, offs, lens) == -1 and L.la_schedule_owned_ranges(None, 0, 0, None, None) == -1
+    assert L.la_schedule_step_group(sh.handle, 0) == 4 and L.la_schedule_step_group(sh.handle, 9) == -1
     assert [lane.owned_ranges(r) for r in (1, 3, 5)] == [[], [], []]           # only the leader of a GPU owns data
     assert lane.owned_ranges(2) == [(n // 4, n // 16)]
 
