@@ -131,6 +131,13 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
         while (t.unroll > 1 && (uint64_t)t.block * t.unroll > longest_units) t.unroll /= 2;
     if (req.block <= 0)
         if (t.block > 256 && (uint64_t)t.block * t.unroll > longest_units) t.block = 256;
+    // ... nor so long that the step has fewer workgroups than the GPU has compute units
+    const uint64_t vectors = bytes_per_operand / 16;
+    constexpr uint64_t COMPUTE_UNITS = 256;
+    if (req.unroll <= 0)
+        while (t.unroll > 1 && vectors / ((uint64_t)t.block * t.unroll) < COMPUTE_UNITS) t.unroll /= 2;
+    if (req.block <= 0)
+        if (t.block > 256 && vectors / ((uint64_t)t.block * t.unroll) < COMPUTE_UNITS) t.block = 256;
     if (t.unroll == 8 && t.block != 1024) t.unroll = 4; // 128 KiB tiles exist for 1024 lanes only
     return t;
 }
