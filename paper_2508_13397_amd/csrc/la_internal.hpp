@@ -57,7 +57,8 @@ struct Step {
 // Per-segment record the kernels read.
 struct SegInfo {
     uint64_t len;        // elements
-    uint32_t head;       // elements before the first 16-byte boundary (vector path only)
+    uint32_t head;       // elements before the vector body: up to the first 16-byte, or if all operands
+                         // agree modulo 128 bytes the first 128-byte boundary (vector path only)
     uint32_t vec_ok;     // 1: all operands of the segment share the address modulo 16
     uint64_t alias_mask; // bit t: source t (t < 64) is also a destination of the segment
 };
