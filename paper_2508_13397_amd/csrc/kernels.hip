@@ -312,6 +312,50 @@ __device__ inline void reduce_one(table_u64 sp, table_u64 dp, uint32_t k, uint32
     for (uint32_t d = 0; d < m; ++d) reinterpret_cast<elem*>(dp[d])[e] = r;
 }
 
+// 16 bytes at an address that is only aligned to the element size: the segments whose operands
+// disagree modulo 16 bytes (views at different odd offsets).  The packed type tells the compiler
+// the true alignment; it emits one global 128-bit access, which the memory system splits where it
+// straddles a line.
+template <int ALIGN>
+struct __attribute__((packed, aligned(ALIGN))) Unaligned16 {
+    u32x4 v;
+};
+
+#define LA_GLOBAL __attribute__((address_space(1)))
+
+template <int ALIGN>
+__device__ inline u32x4 load16_unaligned(uint64_t addr)
+{
+    return ((const LA_GLOBAL Unaligned16<ALIGN>*)addr)->v;
+}
+
+template <int ALIGN>
+__device__ inline void store16_unaligned(uint64_t addr, u32x4 v)
+{
+    ((LA_GLOBAL Unaligned16<ALIGN>*)addr)->v = v;
+}
+
+// One 16-byte vector of one segment from operands of any alignment, all k operands in order.
+template <typename T>
+__device__ inline void reduce_vector_unaligned(table_u64 sp, table_u64 dp, uint32_t k, uint32_t m, uint32_t group,
+                                               uint64_t byte_off, uint32_t op)
+{
+    constexpr int A = (int)sizeof(typename T::elem);
+    typename T::Acc total;
+    for (uint32_t t0 = 0; t0 < k; t0 += group) { // one run when group == k
+        const uint32_t t1 = t0 + group < k ? t0 + group : k;
+        typename T::Acc a = T::widen(load16_unaligned<A>(sp[t0] + byte_off));
+#pragma unroll 4
+        for (uint32_t t = t0 + 1; t < t1; ++t) T::add(a, load16_unaligned<A>(sp[t] + byte_off), op);
+        if (t0 == 0)
+            total = T::widen(T::narrow(a));
+        else
+            T::add(total, T::narrow(a), op);
+    }
+    const u32x4 r = T::narrow(total);
+    for (uint32_t d = 0; d < m; ++d) store16_unaligned<A>(dp[d] + byte_off, r);
+}
+
 // ---- the kernel -------------------------------------------------------------------------------
 
 // Kernel modes.  The sum has instances of its own with the paper's operation compiled in; the
@@ -395,11 +439,14 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     constexpr uint64_t TILE = (uint64_t)BLOCK * U; // vectors per tile
 
     if (!si.vec_ok) {
-        // operands disagree on their 16-byte phase: element-wise, still coalesced
-        const uint64_t lo = (uint64_t)tile * TILE * T::VEC;
-        uint64_t hi = lo + TILE * T::VEC;
-        if (hi > si.len) hi = si.len;
-        for (uint64_t e = lo + tid; e < hi; e += BLOCK) reduce_one<T>(sp, dp, k, m, group, e, op);
+        // operands disagree on their 16-byte phase: 16-byte vectors counted from the start of the
+        // segment, every access unaligned; the last len % VEC elements one per lane
+        const uint64_t whole = si.len / T::VEC;
+        const uint64_t v_lo = (uint64_t)tile * TILE;
+        uint64_t v_hi = v_lo + TILE;
+        if (v_hi > whole) v_hi = whole;
+        for (uint64_t v = v_lo + tid; v < v_hi; v += BLOCK) reduce_vector_unaligned<T>(sp, dp, k, m, group, v * 16u, op);
+        if (tile == 0 && tid < si.len - whole * T::VEC) reduce_one<T>(sp, dp, k, m, group, whole * T::VEC + tid, op);
         return;
     }
 
