@@ -293,8 +293,7 @@ __device__ inline const LA_CONSTANT X* as_table(const X* p)
 }
 
 // One element of one segment, all k operands in order: the slow lanes (segment heads and
-// tails that do not fill a 16-byte vector, and segments whose operands are not congruent
-// modulo 16 bytes).
+// tails that do not fill a 16-byte vector).
 template <typename T>
 __device__ inline void reduce_one(table_u64 sp, table_u64 dp, uint32_t k, uint32_t m, uint32_t group, uint64_t e,
                                   uint32_t op)
