@@ -63,6 +63,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c2", choices=sorted(CONFIGS))
     ap.add_argument("--algo", default=None, choices=["ring", "lane", "lane_multiproc"])
+    ap.add_argument("--n", type=int, default=None, help="elements per rank buffer, instead of the configuration's")
     ap.add_argument("--flags", type=int, default=0, help="LA_SCHED_* bits: 1 = point-to-point gather, 2 = staged")
     ap.add_argument("--unroll", type=int, default=None)
     ap.add_argument("--cache-policy", type=int, default=None)
@@ -220,7 +221,10 @@ def main():
         sys.exit(3)
     la.lib()
     torch.cuda.set_device(0)
-    cfg = CONFIGS[args.config]
+    cfg = dict(CONFIGS[args.config])
+    if args.n is not None:
+        cfg["n"] = args.n
+        cfg["name"] += f" [n overridden: {args.n}]"
     algo = args.algo or cfg["algo"]
     if args.unroll is not None:
         la.la_tuning_set("unroll", args.unroll)
