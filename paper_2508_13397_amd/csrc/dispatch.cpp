@@ -41,7 +41,8 @@ uint32_t tiles_for(uint64_t max_units, const Tuning& tune)
 
 // The caller guarantees: tables are device-resident and hold num_segments * k (resp. m)
 // pointers; every pointer range [ptr, ptr + len*esize) is valid device memory;
-// tiles_per_seg == tiles_for(longest segment in vectors, tune).
+// tiles_per_seg covers the longest segment in tiles of tune.block * tune.unroll vectors (counted
+// from the tile boundary before its start when t.tiling is TILING_ALIGNED).
 la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream)
 {
     if (t.num_segments == 0) return LA_OK;

@@ -63,6 +63,14 @@ struct SegInfo {
     uint64_t alias_mask; // bit t: source t (t < 64) is also a destination of the segment
 };
 
+// How the kernel cuts the 16-byte vectors of a segment into tiles of at most block * unroll.
+enum : uint32_t {
+    TILING_PLAIN = 0,   // full tiles from the segment's start, the last one ragged
+    TILING_ALIGNED = 1, // a short first tile, so that the others start where destination 0's address is a
+                        // multiple of the tile size
+    TILING_EQUAL = 2,   // as few tiles as TILING_PLAIN, all of one size (a multiple of 128 bytes)
+};
+
 // Device view of one step, passed to the kernels by value.
 struct StepTable {
     const SegInfo* seg;      // [S]
@@ -73,6 +81,7 @@ struct StepTable {
     uint32_t num_segments;
     uint32_t op = 0;         // la_op_t of the launch
     uint32_t group = 0;      // 0 or k: one level; else sources per first-level run
+    uint32_t tiling = 0;     // TILING_*: how a segment's vectors are cut into workgroup tiles
 };
 
 // Launch shape of one step.  In the process-wide setting 0 (unroll, block) and -1 (cache_policy)

@@ -202,6 +202,42 @@ def test_buffers_not_aligned_to_16_bytes(oracle, kind, offsets):
             assert not h[:shift[r]].any() and not h[shift[r] + n:].any()
 
 
+@pytest.mark.parametrize("kind", ["i32wrap", "f32order", "bf16"])
+@pytest.mark.parametrize("shape", [(0, 0), (1024, 8), (1024, 4), (256, 4)])
+def test_long_segments_that_start_between_tile_boundaries(oracle, kind, shape):
+    """Segments of 8 and more tiles at arbitrary offsets: the launch cuts its tiles at absolute multiples
+    of the tile size, with a short first tile per segment.  Same bits as the oracle, guards untouched."""
+    block, unroll = shape
+    cases = (("lane", (2, 2, 1), 2400011, 5), ("lane_multiproc", (2, 2, 2), 2500009, 0), ("ring", (1, 4, 1), 4700021, 9),
+             ("lane_multiproc", (3, 2, 2), 3100003, 4100))
+    try:
+        la.la_tuning_set("unroll", unroll)
+        la.la_tuning_set("block", block)
+        for algo, topo, n, shift in cases:
+            P = topo[0] * topo[1] * topo[2]
+            x = make(P, n, kind, seed=n)
+            pad = 8192
+            big = []
+            for r in range(P):
+                host = np.zeros(n + 2 * pad, x.dtype)
+                host[shift:shift + n] = x[r]
+                big.append(to_dev(host))
+            views = [big[r][shift:shift + n] for r in range(P)]
+            t = la.la_topology_create(*topo)
+            sched = la.la_schedule_build(t, algo, n, NAME[x.dtype])
+            la.allreduce_tensors(sched, views)
+            torch.cuda.synchronize()
+            got = np.stack([to_host(v) for v in views])
+            ref = oracle.allreduce(algo, *topo, x)
+            assert np.array_equal(bits(got), bits(ref)), (algo, kind, shape)
+            for r in range(P):
+                h = to_host(big[r])
+                assert not h[:shift].any() and not h[shift + n:].any(), (algo, kind, shape, r)
+    finally:
+        la.la_tuning_set("unroll", 0)
+        la.la_tuning_set("block", 0)
+
+
 # ------------------------------------------------------------------------------ special values
 
 def test_fp32_special_values_and_denormals(oracle):
