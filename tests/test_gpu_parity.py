@@ -238,6 +238,44 @@ def test_long_segments_that_start_between_tile_boundaries(oracle, kind, shape):
         la.la_tuning_set("block", 0)
 
 
+def test_random_lengths_shifts_and_shapes_cover_every_tiling(oracle):
+    """Seeded sweep of buffer lengths, view offsets and launch shapes, so that segments of under one to
+    several hundred tiles start anywhere relative to the tile boundaries in memory (plain, equal and
+    aligned tilings, with and without heads and tails).  int32 with wrap-around: bit-exact, guards untouched."""
+    rng = np.random.default_rng(20250813)
+    topos = [("lane", (2, 2, 1)), ("lane_multiproc", (2, 2, 2)), ("ring", (1, 3, 1)), ("lane_multiproc", (3, 1, 2)),
+             ("rabenseifner", (2, 2, 1)), ("lane", (1, 4, 1))]
+    shapes = [(0, 0), (256, 1), (256, 4), (1024, 1), (1024, 8)]
+    try:
+        for case in range(48):
+            algo, topo = topos[int(rng.integers(len(topos)))]
+            block, unroll = shapes[int(rng.integers(len(shapes)))]
+            n = int(rng.integers(20_000, 2_500_000))
+            shift = int(rng.integers(0, 40_000)) if case % 3 else int(rng.integers(0, 64)) * 1024
+            P = topo[0] * topo[1] * topo[2]
+            x = make(P, n, "i32wrap", seed=case)
+            tag = (case, algo, topo, n, shift, block, unroll)
+            la.la_tuning_set("unroll", unroll)
+            la.la_tuning_set("block", block)
+            big = []
+            for r in range(P):
+                host = np.zeros(n + shift + 4096, x.dtype)
+                host[shift:shift + n] = x[r]
+                big.append(to_dev(host))
+            views = [big[r][shift:shift + n] for r in range(P)]
+            sched = la.la_schedule_build(la.la_topology_create(*topo), algo, n, "int32")
+            la.allreduce_tensors(sched, views)
+            torch.cuda.synchronize()
+            ref = oracle.allreduce(algo, *topo, x)
+            for r in range(P):
+                h = to_host(big[r])
+                assert np.array_equal(h[shift:shift + n], ref[r]), tag + (r,)
+                assert not h[:shift].any() and not h[shift + n:].any(), tag + (r,)
+    finally:
+        la.la_tuning_set("unroll", 0)
+        la.la_tuning_set("block", 0)
+
+
 # ------------------------------------------------------------------------------ special values
 
 def test_fp32_special_values_and_denormals(oracle):
