@@ -53,6 +53,7 @@ Tuning current_tuning()
 //    scope-1 stores.  With many more destinations than sources (LA_SCHED_FUSED_GATHER) the step
 //    behaves like a broadcast and takes its shape: 128 KiB tiles, streaming stores.
 constexpr uint64_t LAST_LEVEL_CACHE_BYTES = 256ull << 20;
+constexpr uint64_t L2_TOTAL_BYTES = 32ull << 20; // 8 XCDs x 4 MiB
 
 Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longest_units, uint64_t bytes_per_operand,
                       bool all_inputs, size_t esize)
@@ -81,16 +82,26 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
         }
     } else if (k == 1) {
         cls = 2;
+        // A broadcast whose copies all fit the last-level cache stores them scope-1, so that whoever
+        // reads them next finds them there (the next all-reduce's first step: 16 to 1024 ranks, 64 to
+        // 384 MiB in all, -3 to -12 % time against non-temporal stores; from 512 MiB on non-temporal
+        // stores win again by 1 to 5 %, and so they do, by 5 to 10 %, when everything fits the L2s).
+        // Segments under 64 KiB do not take non-temporal stores well at any size measured (1024
+        // ranks, 16 and 32 KiB segments, 0.5 and 1 GiB in all: -7 to -10 % time with scope-1).
+        const uint64_t written = (uint64_t)m * bytes_per_operand;
+        const bool beyond_l2 = written > L2_TOTAL_BYTES + L2_TOTAL_BYTES / 4;
+        const bool keep = beyond_l2 && (written <= LAST_LEVEL_CACHE_BYTES + LAST_LEVEL_CACHE_BYTES / 2 ||
+                                        longest_units < 4096);
         if (m == 1) {
             t.cache_policy = 6;
             t.block = fits ? 256 : 1024;
             t.unroll = 4;
         } else if (m <= 4) {
-            t.cache_policy = fits ? 4 : 7;
+            t.cache_policy = keep ? 7 : fits ? 4 : 7;
             t.block = fits ? 256 : 1024;
             t.unroll = fits ? 1 : 4;
         } else {
-            t.cache_policy = fits ? 4 : 7;
+            t.cache_policy = keep ? 7 : fits ? 4 : 7;
             t.block = 1024;
             t.unroll = 8;
         }
