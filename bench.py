@@ -24,16 +24,16 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # file (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors calibrated on the ring's plain-copy launches
 # of known size; profiles/seg_reduce_kernel_c2_lane_pmc.md).  Keyed by (config, algo, flags, stage).
 MEASURED_TRAFFIC = {
-    ("c2", "lane", 0, "S1"): 1342241997,
-    ("c2", "lane", 0, "S2"): 536937472,
-    ("c2", "lane", 0, "S3"): 1074858496,
+    ("c2", "lane", 0, "S1"): 1342275335,
+    ("c2", "lane", 0, "S2"): 268536832 + 268435456,
+    ("c2", "lane", 0, "S3"): 268528943 + 806451130,
     # profiles/seg_reduce_kernel_c3_c4_c5.md
-    ("c3", "lane_multiproc", 0, "S1"): 2147856589 + 134217728,
-    ("c3", "lane_multiproc", 0, "S3"): 134572237 + 2015258931,
-    ("c4", "lane_multiproc", 0, "S1"): 4295142195 + 536914432,
-    ("c4", "lane_multiproc", 0, "S3"): 537037005 + 3758096384,
-    ("c5", "lane_multiproc", 0, "S1"): 4296499405 + 134217728,
-    ("c5", "lane_multiproc", 0, "S3"): 135162470 + 4164543181,
+    ("c3", "lane_multiproc", 0, "S1"): 2147883217 + 134217728,
+    ("c3", "lane_multiproc", 0, "S3"): 134614831 + 2015247639,
+    ("c4", "lane_multiproc", 0, "S1"): 4295185664 + 536930851,
+    ("c4", "lane_multiproc", 0, "S3"): 537058211 + 3758096384,
+    ("c5", "lane_multiproc", 0, "S1"): 4296526196 + 134217728,
+    ("c5", "lane_multiproc", 0, "S3"): 135197475 + 4164481978,
 }
 
 CONFIGS = {
