@@ -458,7 +458,8 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
         uint64_t v_hi = v_lo + TILE;
         if (v_hi > whole) v_hi = whole;
         for (uint64_t v = v_lo + tid; v < v_hi; v += BLOCK) reduce_vector_unaligned<T>(sp, dp, k, m, group, v * 16u, op);
-        if (tile == 0 && tid < si.len - whole * T::VEC) reduce_one<T>(sp, dp, k, m, group, whole * T::VEC + tid, op);
+        const uint32_t rtid = BLOCK - 1 - tid; // the last lanes: see below
+        if (tile == 0 && rtid < si.len - whole * T::VEC) reduce_one<T>(sp, dp, k, m, group, whole * T::VEC + rtid, op);
         return;
     }
 
@@ -466,9 +467,12 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     const uint64_t nvec = body / T::VEC;       // whole vectors
     const uint32_t tail = (uint32_t)(body % T::VEC);
 
-    if (tile == 0 && tid < si.head + tail) {
-        // the few elements before the first and after the last whole vector
-        const uint64_t e = tid < si.head ? tid : si.head + nvec * T::VEC + (tid - si.head);
+    // The few elements before the first and after the last whole vector go to the last lanes of
+    // the segment's first workgroup: in a short segment the vectors keep the first waves busy, and
+    // the two chains of memory latencies then run side by side on different SIMDs.
+    const uint32_t rtid = BLOCK - 1 - tid;
+    if (tile == 0 && rtid < si.head + tail) {
+        const uint64_t e = rtid < si.head ? rtid : si.head + nvec * T::VEC + (rtid - si.head);
         reduce_one<T>(sp, dp, k, m, group, e, op);
     }
 
