@@ -90,8 +90,10 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
         // ranks, 16 and 32 KiB segments, 0.5 and 1 GiB in all: -7 to -10 % time with scope-1).
         const uint64_t written = (uint64_t)m * bytes_per_operand;
         const bool beyond_l2 = written > L2_TOTAL_BYTES + L2_TOTAL_BYTES / 4;
-        const bool keep = beyond_l2 && (written <= LAST_LEVEL_CACHE_BYTES + LAST_LEVEL_CACHE_BYTES / 2 ||
-                                        longest_units < 4096);
+        // (up to 4 copies: 288 MiB written still gains 2 %, 336 MiB loses 1.5 %, 384 MiB loses 7 %;
+        // 15 and 31 copies: 360 MiB gains 8 %, 480 MiB still 3 %)
+        const uint64_t most = LAST_LEVEL_CACHE_BYTES + LAST_LEVEL_CACHE_BYTES / (m <= 4 ? 8 : 2);
+        const bool keep = beyond_l2 && (written <= most || longest_units < 4096);
         if (m == 1) {
             t.cache_policy = 6;
             t.block = fits ? 256 : 1024;
