@@ -42,13 +42,14 @@ uint32_t tiles_for(uint64_t max_units, const Tuning& tune)
 // The caller guarantees: tables are device-resident and hold num_segments * k (resp. m)
 // pointers; every pointer range [ptr, ptr + len*esize) is valid device memory;
 // tiles_per_seg covers the longest segment in tiles of tune.block * tune.unroll vectors (counted
-// from the tile boundary before its start when t.tiling is TILING_ALIGNED).
+// from the tile boundary before its start when t.tiling is TILING_ALIGNED); edge_blocks is 0 or
+// covers every segment with EDGE_LANES lanes each.
 la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream)
 {
     if (t.num_segments == 0) return LA_OK;
     if (t.k < 1 || t.m < 1) return fail(LA_ERR_INVALID_ARG, "internal: step with k=%u m=%u", t.k, t.m);
     if (!known_op((int)t.op)) return fail(LA_ERR_UNSUPPORTED, "unknown operation %u", t.op);
-    const uint64_t blocks = (uint64_t)t.num_segments * t.tiles_per_seg;
+    const uint64_t blocks = (uint64_t)t.edge_blocks + (uint64_t)t.num_segments * t.tiles_per_seg;
     if (blocks > 0x7fffffffull) return fail(LA_ERR_INVALID_ARG, "step needs %llu workgroups", (unsigned long long)blocks);
     const int family = family_of(tune);
     if (family < 0)

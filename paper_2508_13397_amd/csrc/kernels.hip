@@ -10,7 +10,8 @@
 // around 16-byte coalesced accesses with many independent loads in flight per lane; no LDS and
 // no matrix cores.  A workgroup of BLOCK lanes owns a tile of UNROLL*BLOCK vectors of one segment;
 // consecutive workgroups own consecutive tiles, so the eight XCDs (which receive workgroups
-// round-robin) stream disjoint, adjacent 4-128 KiB pieces of the same operand rows at once.
+// round-robin) stream disjoint, adjacent 4-128 KiB pieces of the same operand rows at once.  The
+// elements outside a segment's whole vectors go to a few edge workgroups at the front of the grid.
 #include <hip/hip_runtime.h>
 
 #include "la_internal.hpp"
@@ -435,10 +436,36 @@ template <typename T, int U, int POLICY, int BLOCK, int MODE>
 __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
 {
     using P = Policy<POLICY>;
-    const uint32_t seg = blockIdx.x / tab.tiles_per_seg;
-    const uint32_t tile = blockIdx.x - seg * tab.tiles_per_seg;
     const uint32_t k = tab.k, m = tab.m, op = MODE == MODE_SUM ? (uint32_t)LA_SUM : tab.op;
     const uint32_t group = MODE == MODE_GROUPED ? tab.group : k;
+    const uint32_t tid = threadIdx.x;
+
+    if (blockIdx.x < tab.edge_blocks) {
+        // Edge workgroup: the elements outside the whole vectors of BLOCK / EDGE_LANES segments,
+        // one per lane.  Each is a chain of memory latencies (k loads, a few at a time); in
+        // workgroups of their own these chains run beside the tiles instead of prolonging every
+        // segment's first tile (128 ranks, 1.4 and 2.8 MiB each: 9 and 6 % of the all-reduce).
+        static_assert(128 / sizeof(typename T::elem) - 1 + T::VEC - 1 <= EDGE_LANES, "head + tail lanes");
+        const uint32_t seg = __builtin_amdgcn_readfirstlane(blockIdx.x * (BLOCK / EDGE_LANES) + tid / EDGE_LANES);
+        if (seg >= tab.num_segments) return;
+        const uint32_t l = tid % EDGE_LANES;
+        const table_seg sg = as_table(tab.seg) + seg;
+        const uint64_t len = sg->len;
+        const uint32_t head = sg->head;
+        const table_u64 sp = as_table(tab.src_ptr) + (uint64_t)seg * k;
+        const table_u64 dp = as_table(tab.dst_ptr) + (uint64_t)seg * m;
+        // without a vector phase common to all operands the vectors count from the segment's start (head 0)
+        const uint64_t whole = (len - head) / T::VEC;
+        const uint32_t tail = (uint32_t)((len - head) % T::VEC);
+        if (l < head + tail) {
+            const uint64_t e = l < head ? l : head + whole * T::VEC + (l - head);
+            reduce_one<T>(sp, dp, k, m, group, e, op);
+        }
+        return;
+    }
+    const uint32_t tile_block = blockIdx.x - tab.edge_blocks;
+    const uint32_t seg = tile_block / tab.tiles_per_seg;
+    const uint32_t tile = tile_block - seg * tab.tiles_per_seg;
     const table_seg sg = as_table(tab.seg) + seg;
     SegInfo si;
     si.len = sg->len;
@@ -447,34 +474,21 @@ __global__ __launch_bounds__(BLOCK) void seg_reduce_kernel(StepTable tab)
     si.alias_mask = sg->alias_mask;
     const table_u64 sp = as_table(tab.src_ptr) + (uint64_t)seg * k;
     const table_u64 dp = as_table(tab.dst_ptr) + (uint64_t)seg * m;
-    const uint32_t tid = threadIdx.x;
     constexpr uint64_t TILE = (uint64_t)BLOCK * U; // vectors per tile
 
     if (!si.vec_ok) {
         // operands disagree on their 16-byte phase: 16-byte vectors counted from the start of the
-        // segment, every access unaligned; the last len % VEC elements one per lane
+        // segment, every access unaligned (the last len % VEC elements: edge workgroups)
         const uint64_t whole = si.len / T::VEC;
         const uint64_t v_lo = (uint64_t)tile * TILE;
         uint64_t v_hi = v_lo + TILE;
         if (v_hi > whole) v_hi = whole;
         for (uint64_t v = v_lo + tid; v < v_hi; v += BLOCK) reduce_vector_unaligned<T>(sp, dp, k, m, group, v * 16u, op);
-        const uint32_t rtid = BLOCK - 1 - tid; // the last lanes: see below
-        if (tile == 0 && rtid < si.len - whole * T::VEC) reduce_one<T>(sp, dp, k, m, group, whole * T::VEC + rtid, op);
         return;
     }
 
     const uint64_t body = si.len - si.head;    // elements from the first 16-byte boundary on
-    const uint64_t nvec = body / T::VEC;       // whole vectors
-    const uint32_t tail = (uint32_t)(body % T::VEC);
-
-    // The few elements before the first and after the last whole vector go to the last lanes of
-    // the segment's first workgroup: in a short segment the vectors keep the first waves busy, and
-    // the two chains of memory latencies then run side by side on different SIMDs.
-    const uint32_t rtid = BLOCK - 1 - tid;
-    if (tile == 0 && rtid < si.head + tail) {
-        const uint64_t e = rtid < si.head ? rtid : si.head + nvec * T::VEC + (rtid - si.head);
-        reduce_one<T>(sp, dp, k, m, group, e, op);
-    }
+    const uint64_t nvec = body / T::VEC;       // whole vectors (the elements around them: edge workgroups)
 
     // Tile t covers the vectors [t*per - lead, (t+1)*per - lead) of the body.  Plain: per = TILE,
     // lead = 0.  Aligned: lead is the distance of the body's start from the previous multiple of

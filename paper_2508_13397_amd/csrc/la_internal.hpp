@@ -71,6 +71,11 @@ enum : uint32_t {
     TILING_EQUAL = 2,   // as few tiles as TILING_PLAIN, all of one size (a multiple of 128 bytes)
 };
 
+// The elements of a segment before its first and after its last whole 16-byte vector are done one
+// per lane by separate "edge" workgroups at the front of the grid, EDGE_LANES lanes per segment
+// (enough for the longest head plus tail: 63 + 7 two-byte elements).
+constexpr uint32_t EDGE_LANES = 128;
+
 // Device view of one step, passed to the kernels by value.
 struct StepTable {
     const SegInfo* seg;      // [S]
@@ -82,6 +87,7 @@ struct StepTable {
     uint32_t op = 0;         // la_op_t of the launch
     uint32_t group = 0;      // 0 or k: one level; else sources per first-level run
     uint32_t tiling = 0;     // TILING_*: how a segment's vectors are cut into workgroup tiles
+    uint32_t edge_blocks = 0; // leading workgroups that do the elements outside the whole vectors (0: there are none)
 };
 
 // Launch shape of one step.  In the process-wide setting 0 (unroll, block) and -1 (cache_policy)

@@ -89,7 +89,7 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
         // Segments under 64 KiB do not take non-temporal stores well at any size measured (1024
         // ranks, 16 and 32 KiB segments, 0.5 and 1 GiB in all: -7 to -10 % time with scope-1).
         const uint64_t written = (uint64_t)m * bytes_per_operand;
-        const bool beyond_l2 = written > L2_TOTAL_BYTES + L2_TOTAL_BYTES / 4;
+        const bool beyond_l2 = written >= L2_TOTAL_BYTES + L2_TOTAL_BYTES / 2; // 45 MiB: -9 % with scope-1, 48 MiB: +2 %
         // (up to 4 copies: 288 MiB written still gains 2 %, 336 MiB loses 1.5 %, 384 MiB loses 7 %;
         // 15 and 31 copies: 360 MiB gains 8 %, 480 MiB still 3 %)
         const uint64_t most = LAST_LEVEL_CACHE_BYTES + LAST_LEVEL_CACHE_BYTES / (m <= 4 ? 8 : 2);
@@ -259,6 +259,18 @@ uint64_t describe_segment(SegInfo& si, uint64_t len, const uint64_t* ptrs, size_
 //    same number of tiles, all of one size, gained 0 to 6 %.
 constexpr uint64_t ALIGN_MIN_TILES = 8;
 
+// Edge workgroups of a launch: enough for every segment if any segment has elements outside its
+// whole vectors, else none (buffers and partitions that are multiples of 128 bytes: the usual case).
+uint32_t plan_edges(const SegInfo* seg, size_t S, size_t esize, const Tuning& shape)
+{
+    const uint64_t vec = 16 / esize;
+    bool any = false;
+    for (size_t g = 0; g < S && !any; ++g) any = seg[g].head != 0 || (seg[g].len - seg[g].head) % vec != 0;
+    if (!any) return 0;
+    const uint64_t per_block = (uint64_t)shape.block / EDGE_LANES;
+    return (uint32_t)((S + per_block - 1) / per_block);
+}
+
 uint32_t plan_tiles(const SegInfo* seg, const uint64_t* dp, size_t S, size_t m, size_t esize, const Tuning& shape,
                     uint64_t longest, uint32_t* tiling)
 {
@@ -346,6 +358,7 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
         shapes[i] = resolve_tuning(tune, v.k, v.m, longest, step_elems * esize,
                                    p.stage == LA_STAGE_S1_S2_S3 && p.k > 1 && p.m > 1, esize);
         v.tiles_per_seg = plan_tiles(seg, dp, S, (size_t)p.m, esize, shapes[i], longest, &v.tiling);
+        v.edge_blocks = plan_edges(seg, S, esize, shapes[i]);
     }
 }
 
@@ -723,6 +736,7 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
     t.num_segments = (uint32_t)num_segments;
     const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest, (uint64_t)num_segments * seg_len * e, false, e);
     t.tiles_per_seg = plan_tiles(seg, dp, num_segments, 1, e, tune, longest, &t.tiling);
+    t.edge_blocks = plan_edges(seg, num_segments, e, tune);
     la_status_t st = launch_step(t, dtype, tune, hip_stream);
     (void)hipFreeAsync(dev, stream); // stream-ordered: freed after the kernel has run
     return st;
