@@ -255,6 +255,25 @@ la_status_t la_allreduce_emulated_out_of_place(const la_schedule_t* sched, const
  * that look at intermediate states. */
 la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* const* bufs, void* hip_stream);
 
+/* Host only, for tests and for reading the launch heuristics: how one step would be launched for
+ * buffers at the given addresses.  The addresses are never dereferenced and no device call is
+ * made.  sendbufs is NULL unless the schedule is out-of-place; staging is the address to assume
+ * for the library-owned staging area of a LA_SCHED_STAGED schedule (ignored otherwise).  Honours
+ * the la_tuning_set knobs like a real launch. */
+typedef struct la_launch_plan {
+    int block;                  /* lanes per workgroup */
+    int unroll;                 /* 16-byte vectors per lane and operand: a tile is block * unroll vectors */
+    int cache_policy;           /* 0..7, see la_tuning_set */
+    int tiling;                 /* 0: full tiles from the segment's start; 1: a short first tile, the others
+                                   start where destination 0's address is a multiple of the tile size;
+                                   2: as few tiles as 0, all of one size */
+    uint32_t tiles_per_segment; /* workgroups per segment (those beyond a short segment's end exit at once) */
+    uint32_t edge_workgroups;   /* workgroups for the elements outside the segments' whole 16-byte vectors */
+    uint64_t workgroups;        /* edge_workgroups + segments * tiles_per_segment */
+} la_launch_plan_t;
+la_status_t la_schedule_launch_plan(const la_schedule_t* sched, int step, const void* const* bufs,
+                                    const void* const* sendbufs, const void* staging, la_launch_plan_t* out);
+
 /*
  * k incoming segments summed into the owned segment (the local reduction that follows each
  * received message, "GPU-Aware All-Reduce Operations" subsection), for num_segments segments

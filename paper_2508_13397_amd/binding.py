@@ -5,7 +5,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Sequence
+from typing import Optional, Sequence
 
 import numpy as np
 
@@ -44,8 +44,16 @@ EXPORTS = (
     "la_schedule_num_buffers", "la_schedule_owned_ranges", "la_schedule_step_group",
     "la_schedule_staging_elems", "la_schedule_step_info", "la_schedule_step_table",
     "la_allreduce_emulated", "la_allreduce_emulated_out_of_place", "la_schedule_run_step", "la_reduce_segments",
+    "la_schedule_launch_plan",
     "la_status_string", "la_last_error", "la_tuning_set", "la_tuning_get",
 )
+
+
+class LaunchPlan(ctypes.Structure):
+    """la_launch_plan_t"""
+    _fields_ = [("block", ctypes.c_int), ("unroll", ctypes.c_int), ("cache_policy", ctypes.c_int),
+                ("tiling", ctypes.c_int), ("tiles_per_segment", ctypes.c_uint32),
+                ("edge_workgroups", ctypes.c_uint32), ("workgroups", ctypes.c_uint64)]
 
 
 class LaError(RuntimeError):
@@ -87,6 +95,7 @@ def lib() -> ctypes.CDLL:
     L.la_allreduce_emulated.argtypes = [vp, pp(vp), sz, i32, i32, vp]
     L.la_allreduce_emulated_out_of_place.argtypes = [vp, pp(vp), pp(vp), sz, i32, i32, vp]
     L.la_schedule_run_step.argtypes = [vp, i32, pp(vp), vp]
+    L.la_schedule_launch_plan.argtypes = [vp, i32, pp(vp), pp(vp), vp, pp(LaunchPlan)]
     L.la_reduce_segments.argtypes = [vp, pp(vp), i32, pp(sz), sz, sz, i32, i32, vp]
     L.la_status_string.argtypes = [i32]
     L.la_status_string.restype = ctypes.c_char_p
@@ -260,6 +269,16 @@ def la_allreduce_emulated_out_of_place(sched: Schedule, sendbufs: Sequence[int],
 def la_schedule_run_step(sched: Schedule, step: int, bufs: Sequence[int], stream: int = 0) -> None:
     _check(lib().la_schedule_run_step(sched.handle, int(step), _ptr_array(bufs), ctypes.c_void_p(stream)),
            "la_schedule_run_step")
+
+
+def la_schedule_launch_plan(sched: Schedule, step: int, bufs: Sequence[int], sendbufs: Optional[Sequence[int]] = None,
+                            staging: int = 0) -> dict:
+    """Host only: how `step` would be launched for buffers at these addresses (never dereferenced)."""
+    plan = LaunchPlan()
+    _check(lib().la_schedule_launch_plan(sched.handle, int(step), _ptr_array(bufs),
+                                         _ptr_array(sendbufs) if sendbufs is not None else None,
+                                         ctypes.c_void_p(staging), ctypes.byref(plan)), "la_schedule_launch_plan")
+    return {name: int(getattr(plan, name)) for name, _ in LaunchPlan._fields_}
 
 
 def la_reduce_segments(dst: int, srcs: Sequence[int], seg_offsets: Sequence[int], seg_len: int, dtype,

@@ -658,6 +658,36 @@ la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* con
     return run_steps(sched, bufs, nullptr, step, step + 1, (uint32_t)LA_SUM, hip_stream);
 }
 
+la_status_t la_schedule_launch_plan(const la_schedule_t* sched, int step, const void* const* bufs,
+                                    const void* const* sendbufs, const void* staging, la_launch_plan_t* out)
+{
+    if (!sched) return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: schedule is NULL");
+    if (!bufs) return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: bufs is NULL");
+    if (!out) return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: out is NULL");
+    if (step < 0 || step >= (int)sched->steps.size())
+        return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: step %d out of range", step);
+    std::vector<uint64_t> addr;
+    la_status_t st = check_buffers(*sched, const_cast<void* const*>(bufs), sendbufs, addr);
+    if (st != LA_OK) return st;
+    const size_t e = dtype_size(sched->dtype);
+    addr[sched->nbuf] = reinterpret_cast<uint64_t>(staging);
+    if (sched->staging_elems > 0 && (addr[sched->nbuf] == 0 || addr[sched->nbuf] % 16))
+        return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: the schedule is staged: pass a 16-byte aligned staging address");
+    const std::vector<Step> one(1, sched->steps[step]);
+    HostTables ht;
+    std::vector<Tuning> shapes;
+    resolve_tables(one, addr, e, current_tuning(), ht, shapes);
+    const StepTable& v = ht.view[0];
+    out->block = shapes[0].block;
+    out->unroll = shapes[0].unroll;
+    out->cache_policy = shapes[0].cache_policy;
+    out->tiling = (int)v.tiling;
+    out->tiles_per_segment = v.tiles_per_seg;
+    out->edge_workgroups = v.edge_blocks;
+    out->workgroups = (uint64_t)v.edge_blocks + (uint64_t)v.num_segments * v.tiles_per_seg;
+    return LA_OK;
+}
+
 la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const size_t* seg_offsets,
                                size_t num_segments, size_t seg_len, la_dtype_t dtype, la_op_t op,
                                void* hip_stream)
