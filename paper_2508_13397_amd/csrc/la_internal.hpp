@@ -106,8 +106,9 @@ Tuning current_tuning();
 // segment of `longest_units` 16-byte vectors and `bytes_per_operand` bytes summed over its
 // segments (the size of the step's result, and of its source when k == 1).  all_inputs: the step
 // is the whole all-reduce (every source an original input, every rank a destination).
+// working_set: bytes of all buffers the schedule works on (what a loop of all-reduces keeps touching).
 Tuning resolve_tuning(const Tuning& requested, uint32_t k, uint32_t m, uint64_t longest_units,
-                      uint64_t bytes_per_operand, bool all_inputs, size_t esize);
+                      uint64_t bytes_per_operand, bool all_inputs, size_t esize, uint64_t working_set);
 
 // kernels.hip
 la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream);

@@ -56,16 +56,27 @@ constexpr uint64_t LAST_LEVEL_CACHE_BYTES = 256ull << 20;
 constexpr uint64_t L2_TOTAL_BYTES = 32ull << 20; // 8 XCDs x 4 MiB
 
 Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longest_units, uint64_t bytes_per_operand,
-                      bool all_inputs, size_t esize)
+                      bool all_inputs, size_t esize, uint64_t working_set)
 {
     Tuning t;
     int cls; // step class: 0 pure reduce, 1 reduce + multi-destination store, 2 copy / broadcast
     // measured on 16 ranks: the cache-resident shapes win up to about 1.25 times the cache (a result of
     // 320 MiB: 0.575 against 0.590 ms), and lose from 1.5 times on (0.738 against 0.709 ms)
     const bool fits = bytes_per_operand <= LAST_LEVEL_CACHE_BYTES + LAST_LEVEL_CACHE_BYTES / 4;
+    // Everything the schedule touches is more than the L2s hold and fits the last-level cache (with
+    // the same margins as above): the few-operand steps then do better with ordinary loads or
+    // stores, which leave their lines where the next launch finds them.
+    const bool resident = working_set >= L2_TOTAL_BYTES + L2_TOTAL_BYTES / 2 &&
+                          working_set <= LAST_LEVEL_CACHE_BYTES + LAST_LEVEL_CACHE_BYTES / 4;
     if (k >= 2 && m == 1) {
         cls = 0;
         t.cache_policy = fits ? 6 : 3;
+        // Fan-in 2 to 4 with 64 to 256 MiB in all: NPP (results stored write-back, the operand that is
+        // overwritten loaded normally) is 3 to 14 % faster for the whole all-reduce than NNS: ring on
+        // 8 to 32 ranks (with PPS on its copy steps) -6 / -10 / -8 % at 64 / 128 / 256 MiB, lane on
+        // 4 x 4 x 1, 2 x 2 x 2, 4 x 2 x 1 and 8 x 2 x 1 -3 to -9 %, Rabenseifner -3 %.  At 32 MiB and
+        // from 384 MiB on the streaming policies win.
+        if (k < 8 && resident) t.cache_policy = 1;
         if (k >= 16) {
             t.block = 1024;
             t.unroll = 4;
@@ -95,7 +106,7 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
         const uint64_t most = LAST_LEVEL_CACHE_BYTES + LAST_LEVEL_CACHE_BYTES / (m <= 4 ? 8 : 2);
         const bool keep = beyond_l2 && (written <= most || longest_units < 4096);
         if (m == 1) {
-            t.cache_policy = 6;
+            t.cache_policy = resident ? 7 : 6;
             t.block = fits ? 256 : 1024;
             t.unroll = 4;
         } else if (m <= 4) {
@@ -307,7 +318,7 @@ struct HostTables {
 // Resolve every (buffer, offset) operand of `steps` against `base` addresses and lay the tables
 // out in one blob.  base[P] is the staging area.
 void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>& base, size_t esize, const Tuning& tune,
-                    HostTables& out, std::vector<Tuning>& shapes)
+                    uint64_t working_set, HostTables& out, std::vector<Tuning>& shapes)
 {
     uint64_t total = 0;
     std::vector<uint64_t> seg_at(steps.size()), src_at(steps.size()), dst_at(steps.size());
@@ -356,7 +367,7 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
         v.group = (uint32_t)p.group;
         v.num_segments = (uint32_t)S;
         shapes[i] = resolve_tuning(tune, v.k, v.m, longest, step_elems * esize,
-                                   p.stage == LA_STAGE_S1_S2_S3 && p.k > 1 && p.m > 1, esize);
+                                   p.stage == LA_STAGE_S1_S2_S3 && p.k > 1 && p.m > 1, esize, working_set);
         v.tiles_per_seg = plan_tiles(seg, dp, S, (size_t)p.m, esize, shapes[i], longest, &v.tiling);
         v.edge_blocks = plan_edges(seg, S, esize, shapes[i]);
     }
@@ -461,7 +472,7 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     HostTables ht;
     std::vector<Tuning> shapes;
     try {
-        resolve_tables(s.steps, addr, e, tune, ht, shapes);
+        resolve_tables(s.steps, addr, e, tune, (uint64_t)s.nbuf * s.n * e, ht, shapes);
     } catch (const std::bad_alloc&) {
         return fail(LA_ERR_OUT_OF_MEMORY, "out of host memory");
     }
@@ -676,7 +687,7 @@ la_status_t la_schedule_launch_plan(const la_schedule_t* sched, int step, const 
     const std::vector<Step> one(1, sched->steps[step]);
     HostTables ht;
     std::vector<Tuning> shapes;
-    resolve_tables(one, addr, e, current_tuning(), ht, shapes);
+    resolve_tables(one, addr, e, current_tuning(), (uint64_t)sched->nbuf * sched->n * e, ht, shapes);
     const StepTable& v = ht.view[0];
     out->block = shapes[0].block;
     out->unroll = shapes[0].unroll;
@@ -764,7 +775,8 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
     t.m = 1;
     t.op = (uint32_t)op;
     t.num_segments = (uint32_t)num_segments;
-    const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest, (uint64_t)num_segments * seg_len * e, false, e);
+    const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest, (uint64_t)num_segments * seg_len * e, false, e,
+                                       (uint64_t)(K + 1) * num_segments * seg_len * e);
     t.tiles_per_seg = plan_tiles(seg, dp, num_segments, 1, e, tune, longest, &t.tiling);
     t.edge_blocks = plan_edges(seg, num_segments, e, tune);
     la_status_t st = launch_step(t, dtype, tune, hip_stream);
