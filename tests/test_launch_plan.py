@@ -151,3 +151,20 @@ def test_plan_follows_the_tuning_knobs_and_rejects_bad_arguments():
     with pytest.raises(la.LaError):
         la.la_schedule_launch_plan(staged, 0, fake_buffers(4, 4096, 4))  # no staging address
     assert la.la_schedule_launch_plan(staged, 0, fake_buffers(4, 4096, 4), staging=BASE - (1 << 30))["workgroups"] > 0
+
+
+def test_plan_of_an_out_of_place_schedule_needs_both_buffer_sets():
+    n = 700001
+    sched = la.la_schedule_build(la.la_topology_create(2, 2, 2), "lane_multiproc", n, "bfloat16", la.LA_SCHED_OUT_OF_PLACE)
+    recv = fake_buffers(8, n, 2)
+    send = [a + (1 << 36) + 6 for a in recv]  # another region, at an odd element offset
+    with pytest.raises(la.LaError):
+        la.la_schedule_launch_plan(sched, 0, recv)
+    plans = [la.la_schedule_launch_plan(sched, i, recv, sendbufs=send) for i in range(sched.num_steps)]
+    assert all(p["workgroups"] > 0 for p in plans)
+    # the first step reads the send buffers, whose addresses disagree with the receive buffers modulo 16 bytes:
+    # no common vector phase, so the elements that do not fill a vector go to edge workgroups
+    assert plans[0]["edge_workgroups"] > 0
+    in_place = la.la_schedule_build(la.la_topology_create(2, 2, 2), "lane_multiproc", n, "bfloat16")
+    with pytest.raises(la.LaError):
+        la.la_schedule_launch_plan(in_place, 0, recv, sendbufs=send)
