@@ -54,6 +54,7 @@ Tuning current_tuning()
 //    behaves like a broadcast and takes its shape: 128 KiB tiles, streaming stores.
 constexpr uint64_t LAST_LEVEL_CACHE_BYTES = 256ull << 20;
 constexpr uint64_t L2_TOTAL_BYTES = 32ull << 20; // 8 XCDs x 4 MiB
+constexpr uint64_t SMALL_SCHEDULE_BYTES = 96ull << 20; // all buffers of a schedule together
 
 Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longest_units, uint64_t bytes_per_operand,
                       bool all_inputs, size_t esize, uint64_t working_set)
@@ -335,6 +336,18 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
     out.blob.assign(total ? total : 256, 0);
     out.view.resize(steps.size());
     shapes.resize(steps.size());
+    // Small schedules run every step in one launch shape.  Launches that follow each other with
+    // different workgroup sizes or vectors per lane cost 2.5 to 5 us per change (measured with
+    // forced shapes on 16 ranks x 1 and 4 MiB: 36.9 us with one shape, 40 to 47 with mixed ones),
+    // which long launches hide and short ones do not: 16 ranks x 1 / 2 / 4 MiB 19.4 / 26.1 / 35.4 ->
+    // 13.6 / 18.5 / 31.8 us per all-reduce, 64 ranks x 256 KiB and 1 MiB 20.5 -> 15.8 and 41.3 -> 32.7,
+    // 128 ranks x 512 KiB 30.6 -> 29.3 (one loss: 2 x 4 x 2 ranks x 4 MiB 30.4 -> 32.6).  At 80 MiB in
+    // all it still gains 5 to 19 %, at 96 MiB nothing, at 128 MiB the per-step shapes win by 1 to 2 %.
+    Tuning request = tune;
+    if (working_set <= SMALL_SCHEDULE_BYTES) {
+        if (request.block <= 0) request.block = 256;
+        if (request.unroll <= 0) request.unroll = 1;
+    }
     std::vector<uint64_t> all;
     for (size_t i = 0; i < steps.size(); ++i) {
         const Step& p = steps[i];
@@ -366,7 +379,7 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
         v.m = (uint32_t)p.m;
         v.group = (uint32_t)p.group;
         v.num_segments = (uint32_t)S;
-        shapes[i] = resolve_tuning(tune, v.k, v.m, longest, step_elems * esize,
+        shapes[i] = resolve_tuning(request, v.k, v.m, longest, step_elems * esize,
                                    p.stage == LA_STAGE_S1_S2_S3 && p.k > 1 && p.m > 1, esize, working_set);
         v.tiles_per_seg = plan_tiles(seg, dp, S, (size_t)p.m, esize, shapes[i], longest, &v.tiling);
         v.edge_blocks = plan_edges(seg, S, esize, shapes[i]);

@@ -74,7 +74,7 @@ def check_plan(sched, bufs, esize):
 
 
 @pytest.mark.parametrize("cfg,expect", [
-    (((2, 4, 1), "lane", 1 << 16, "float32"), None),
+    (((2, 4, 1), "lane", 1 << 16, "float32"), [(256, 1, 6), (256, 1, 7), (256, 1, 4)]),  # small: one shape for all steps
     (((4, 4, 1), "lane", 1 << 24, "float32"), [(1024, 1, 6), (1024, 1, 7), (256, 1, 4)]),
     (((8, 4, 4), "lane_multiproc", 1 << 22, "float32"), [(1024, 4, 6), (256, 4, 7), (1024, 8, 4)]),
     (((2, 4, 2), "lane_multiproc", 1 << 27, "bfloat16"), [(1024, 8, 3), (1024, 1, 7), (1024, 8, 7)]),
