@@ -13,6 +13,7 @@ import paper_2508_13397_amd as la
 BASE = 0x7F0000000000  # a 2 MiB aligned fake device address
 EDGE_LANES = 128
 ALIGN_MIN_TILES = 8
+SMALL_SCHEDULE_BYTES = 96 << 20
 ESIZE = {"int32": 4, "float32": 4, "bfloat16": 2, "float16": 2, "float64": 8}
 
 
@@ -122,7 +123,10 @@ def test_plans_for_random_lengths_offsets_and_flags():
         else:  # every buffer at its own odd offset: operands disagree modulo 16 bytes
             bufs = fake_buffers(P, n, e, skew=[int(x) for x in rng.integers(0, 9, size=P)])
         check_plan(sched, bufs, e)
-        seen.update(la.la_schedule_launch_plan(sched, i, bufs)["tiling"] for i in range(sched.num_steps))
+        plans = [la.la_schedule_launch_plan(sched, i, bufs) for i in range(sched.num_steps)]
+        seen.update(p["tiling"] for p in plans)
+        if P * n * e <= SMALL_SCHEDULE_BYTES:  # one launch shape for every step of a small schedule
+            assert all((p["block"], p["unroll"]) == (256, 1) for p in plans), (case, plans)
     assert seen == {0, 1, 2}
 
 
