@@ -24,9 +24,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # file (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors calibrated on the ring's plain-copy launches
 # of known size; profiles/seg_reduce_kernel_c2_lane_pmc.md).  Keyed by (config, algo, flags, stage).
 MEASURED_TRAFFIC = {
-    ("c2", "lane", 0, "S1"): 1342275335,
-    ("c2", "lane", 0, "S2"): 268536832 + 268435456,
-    ("c2", "lane", 0, "S3"): 268528943 + 806451130,
+    ("c2", "lane", 0, "S1"): 1342274596,
+    ("c2", "lane", 0, "S2"): 268528640 + 268435456,
+    ("c2", "lane", 0, "S3"): 268525917 + 806258048,
     # profiles/seg_reduce_kernel_c3_c4_c5.md
     ("c3", "lane_multiproc", 0, "S1"): 2147883217 + 134217728,
     ("c3", "lane_multiproc", 0, "S3"): 134614831 + 2015247639,
