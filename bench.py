@@ -28,12 +28,12 @@ MEASURED_TRAFFIC = {
     ("c2", "lane", 0, "S2"): 268528640 + 268435456,
     ("c2", "lane", 0, "S3"): 268525917 + 806258048,
     # profiles/seg_reduce_kernel_c3_c4_c5.md
-    ("c3", "lane_multiproc", 0, "S1"): 2147883217 + 134217728,
-    ("c3", "lane_multiproc", 0, "S3"): 134614831 + 2015247639,
-    ("c4", "lane_multiproc", 0, "S1"): 4295185664 + 536930851,
-    ("c4", "lane_multiproc", 0, "S3"): 537058211 + 3758096384,
-    ("c5", "lane_multiproc", 0, "S1"): 4296526196 + 134217728,
-    ("c5", "lane_multiproc", 0, "S3"): 135197475 + 4164481978,
+    ("c3", "lane_multiproc", 0, "S1"): 2147902929 + 134217728,
+    ("c3", "lane_multiproc", 0, "S3"): 134673303 + 2015343919,
+    ("c4", "lane_multiproc", 0, "S1"): 4295180870 + 536934330,
+    ("c4", "lane_multiproc", 0, "S3"): 537058385 + 3758096384,
+    ("c5", "lane_multiproc", 0, "S1"): 4296550633 + 134217728,
+    ("c5", "lane_multiproc", 0, "S3"): 135180544 + 4164127663,
 }
 
 CONFIGS = {
