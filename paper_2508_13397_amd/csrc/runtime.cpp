@@ -336,18 +336,16 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
     out.blob.assign(total ? total : 256, 0);
     out.view.resize(steps.size());
     shapes.resize(steps.size());
-    // Small schedules run every step in one launch shape.  Launches that follow each other with
-    // different workgroup sizes or vectors per lane cost 2.5 to 5 us per change (measured with
-    // forced shapes on 16 ranks x 1 and 4 MiB: 36.9 us with one shape, 40 to 47 with mixed ones),
-    // which long launches hide and short ones do not: 16 ranks x 1 / 2 / 4 MiB 19.4 / 26.1 / 35.4 ->
-    // 13.6 / 18.5 / 31.8 us per all-reduce, 64 ranks x 256 KiB and 1 MiB 20.5 -> 15.8 and 41.3 -> 32.7,
-    // 128 ranks x 512 KiB 30.6 -> 29.3 (one loss: 2 x 4 x 2 ranks x 4 MiB 30.4 -> 32.6).  At 80 MiB in
-    // all it still gains 5 to 19 %, at 96 MiB nothing, at 128 MiB the per-step shapes win by 1 to 2 %.
+    // Small schedules run every step with one workgroup size.  A launch whose workgroup size differs
+    // from the previous launch's starts about 1.6 us later than one of the same size (plain HIP
+    // launches of trivial dependent kernels on one stream: 2.8 us per launch with one size, 4.4 us
+    // alternating 256 and 1024 lanes; a change of the register count costs nothing), which long
+    // launches hide and short ones do not: 16 ranks x 1 / 2 / 4 MiB 19.4 / 26.1 / 35.4 -> 14.1 / 18.7 /
+    // 32.3 us per all-reduce, 64 ranks x 256 KiB and 1 MiB 20.5 -> 15.6 and 41.3 -> 33.0, 8 ranks x
+    // 4 MiB 26.0 -> 18.9.  The vectors per lane stay each step's own.  At 80 MiB in all one size still
+    // gains 5 to 19 %, at 96 MiB nothing, beyond that it is +-2 % either way.
     Tuning request = tune;
-    if (working_set <= SMALL_SCHEDULE_BYTES) {
-        if (request.block <= 0) request.block = 256;
-        if (request.unroll <= 0) request.unroll = 1;
-    }
+    if (working_set <= SMALL_SCHEDULE_BYTES && request.block <= 0) request.block = 256;
     std::vector<uint64_t> all;
     for (size_t i = 0; i < steps.size(); ++i) {
         const Step& p = steps[i];

@@ -75,7 +75,7 @@ def check_plan(sched, bufs, esize):
 
 
 @pytest.mark.parametrize("cfg,expect", [
-    (((2, 4, 1), "lane", 1 << 16, "float32"), [(256, 1, 6), (256, 1, 7), (256, 1, 4)]),  # small: one shape for all steps
+    (((2, 4, 1), "lane", 1 << 16, "float32"), [(256, 1, 6), (256, 1, 7), (256, 1, 4)]),  # small: one workgroup size for all steps
     (((4, 4, 1), "lane", 1 << 24, "float32"), [(1024, 1, 6), (1024, 1, 7), (256, 1, 4)]),
     (((8, 4, 4), "lane_multiproc", 1 << 22, "float32"), [(1024, 4, 6), (256, 4, 7), (1024, 8, 4)]),
     (((2, 4, 2), "lane_multiproc", 1 << 27, "bfloat16"), [(1024, 8, 3), (1024, 1, 7), (1024, 8, 7)]),
@@ -125,8 +125,8 @@ def test_plans_for_random_lengths_offsets_and_flags():
         check_plan(sched, bufs, e)
         plans = [la.la_schedule_launch_plan(sched, i, bufs) for i in range(sched.num_steps)]
         seen.update(p["tiling"] for p in plans)
-        if P * n * e <= SMALL_SCHEDULE_BYTES:  # one launch shape for every step of a small schedule
-            assert all((p["block"], p["unroll"]) == (256, 1) for p in plans), (case, plans)
+        if P * n * e <= SMALL_SCHEDULE_BYTES:  # one workgroup size for every step of a small schedule
+            assert all(p["block"] == 256 for p in plans), (case, plans)
     assert seen == {0, 1, 2}
 
 
