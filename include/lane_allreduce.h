@@ -297,7 +297,8 @@ const char* la_last_error(void);
 
 /* Launch-shape knobs for measurements (process-wide, read when a schedule is bound or a
  * la_reduce_segments call is made).  By default every step picks its own shape from its fan-in,
- * fan-out and segment length; a knob set to a fixed value overrides that choice for all steps.
+ * fan-out and segment length (schedules whose buffers together are at most 96 MiB keep one workgroup
+ * size for all steps); a knob set to a fixed value overrides that choice for all steps.
  *   "unroll"      16-byte vectors per lane and operand: 1, 2, 4, 8 (8: only with workgroups of
  *                 1024 lanes, else 4 is used); 0 = automatic
  *   "cache_policy" 0..7: which of {loads of pure sources, loads of sources the segment also
