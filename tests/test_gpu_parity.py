@@ -276,6 +276,41 @@ def test_random_lengths_shifts_and_shapes_cover_every_tiling(oracle):
         la.la_tuning_set("block", 0)
 
 
+@pytest.mark.parametrize("kind", ["i32wrap", "f32order", "bf16", "f16", "f64"])
+def test_longest_heads_and_tails_of_every_element_size(oracle, kind):
+    """Views that start one element past a 128-byte boundary: every segment whose start keeps that phase has the
+    longest possible head (127 bytes of elements), and lengths are chosen so that tails of every length occur.
+    The elements outside the whole vectors are done by the edge workgroups, up to 70 lanes per segment."""
+    esize = {"i32wrap": 4, "f32order": 4, "bf16": 2, "f16": 2, "f64": 8}[kind]
+    per_line = 128 // esize
+    topo, P = (2, 2, 2), 8
+    t = la.la_topology_create(*topo)
+    for n in (8 * per_line * 3 + 1, 8 * per_line * 40 + per_line - 1, 8 * per_line * 40 + 16 // esize - 1, 1, per_line, 70001):
+        if kind in ("f16", "f64"):
+            x = wide_inputs(P, n, kind, seed=n)
+        else:
+            x = make(P, n, kind, seed=n)
+        shift = per_line + 1  # one element past a line boundary of a 256-byte aligned allocation
+        big = []
+        for r in range(P):
+            host = np.zeros(n + 4 * per_line, x.dtype)
+            host[shift:shift + n] = x[r]
+            big.append(to_dev(host))
+        views = [big[r][shift:shift + n] for r in range(P)]
+        for algo, flags in (("lane_multiproc", 0), ("ring", 0), ("lane_multiproc", la.LA_SCHED_SINGLE_LAUNCH)):
+            for r in range(P):
+                views[r].copy_(to_dev(x[r]))
+            sched = la.la_schedule_build(t, algo, n, NAME[x.dtype], flags)
+            la.allreduce_tensors(sched, views)
+            torch.cuda.synchronize()
+            got = np.stack([to_host(v) for v in views])
+            ref = oracle.allreduce(algo, *topo, x)
+            assert np.array_equal(bits(got), bits(ref)), (kind, n, algo, flags)
+            for r in range(P):
+                h = to_host(big[r])
+                assert not h[:shift].any() and not h[shift + n:].any(), (kind, n, algo, flags, r)
+
+
 # ------------------------------------------------------------------------------ special values
 
 def test_fp32_special_values_and_denormals(oracle):
