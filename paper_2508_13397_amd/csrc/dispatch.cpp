@@ -39,6 +39,23 @@ uint32_t tiles_for(uint64_t max_units, const Tuning& tune)
     return (uint32_t)(tiles ? tiles : 1);
 }
 
+// Everything that can refuse a launch, without launching: callers that enqueue other work for the
+// launch first (a table upload) ask this before they enqueue anything.
+la_status_t check_launch(const StepTable& t, la_dtype_t dtype, const Tuning& tune)
+{
+    if (t.num_segments == 0) return LA_OK;
+    if (t.k < 1 || t.m < 1) return fail(LA_ERR_INVALID_ARG, "internal: step with k=%u m=%u", t.k, t.m);
+    if (!known_op((int)t.op)) return fail(LA_ERR_UNSUPPORTED, "unknown operation %u", t.op);
+    const uint64_t blocks = (uint64_t)t.edge_blocks + (uint64_t)t.num_segments * t.tiles_per_seg;
+    if (blocks > 0x7fffffffull) return fail(LA_ERR_INVALID_ARG, "step needs %llu workgroups", (unsigned long long)blocks);
+    if (family_of(tune) < 0)
+        return fail(LA_ERR_INVALID_ARG, "unsupported launch shape: %d lanes x %d vectors", tune.block, tune.unroll);
+    if (tune.cache_policy < 0 || tune.cache_policy > 7)
+        return fail(LA_ERR_INVALID_ARG, "unsupported cache policy %d", tune.cache_policy);
+    if (!known_dtype((int)dtype)) return fail(LA_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+    return LA_OK;
+}
+
 // The caller guarantees: tables are device-resident and hold num_segments * k (resp. m)
 // pointers; every pointer range [ptr, ptr + len*esize) is valid device memory;
 // tiles_per_seg covers the longest segment in tiles of tune.block * tune.unroll vectors (counted
@@ -47,15 +64,10 @@ uint32_t tiles_for(uint64_t max_units, const Tuning& tune)
 la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream)
 {
     if (t.num_segments == 0) return LA_OK;
-    if (t.k < 1 || t.m < 1) return fail(LA_ERR_INVALID_ARG, "internal: step with k=%u m=%u", t.k, t.m);
-    if (!known_op((int)t.op)) return fail(LA_ERR_UNSUPPORTED, "unknown operation %u", t.op);
+    const la_status_t st = check_launch(t, dtype, tune);
+    if (st != LA_OK) return st;
     const uint64_t blocks = (uint64_t)t.edge_blocks + (uint64_t)t.num_segments * t.tiles_per_seg;
-    if (blocks > 0x7fffffffull) return fail(LA_ERR_INVALID_ARG, "step needs %llu workgroups", (unsigned long long)blocks);
-    const int family = family_of(tune);
-    if (family < 0)
-        return fail(LA_ERR_INVALID_ARG, "unsupported launch shape: %d lanes x %d vectors", tune.block, tune.unroll);
-    if ((int)dtype >= 0 && (int)dtype < 5) return kFamilies[(int)dtype][family](t, tune, (uint32_t)blocks, hip_stream);
-    return fail(LA_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+    return kFamilies[(int)dtype][family_of(tune)](t, tune, (uint32_t)blocks, hip_stream);
 }
 
 } // namespace la

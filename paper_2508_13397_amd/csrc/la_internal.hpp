@@ -63,6 +63,44 @@ struct SegInfo {
     uint64_t alias_mask; // bit t: source t (t < 64) is also a destination of the segment
 };
 
+// Host and device code share the arithmetic that describes a segment.
+#if defined(__HIPCC__) || defined(__HIP__)
+#define LA_HOST_DEVICE __host__ __device__
+#else
+#define LA_HOST_DEVICE
+#endif
+
+inline LA_HOST_DEVICE uint64_t align_up(uint64_t x, uint64_t a)
+{
+    return (x + a - 1) / a * a;
+}
+
+// Complete the record of a segment of `len` elements whose first operand starts at byte address
+// `first`, given whether all its operands agree modulo 16 bytes (`congruent`) and the largest of
+// 16 and 128 bytes modulo which they all agree (`align`); returns the segment's length in 16-byte
+// units as the launch sees it.  The vector body starts at the first 16-byte boundary -- or, when
+// all operands also agree modulo a cache line (the usual case: an odd element offset into
+// 256-byte aligned buffers), at the first 128-byte boundary, so that every wave's 1 KiB access
+// covers whole lines (otherwise each touches nine lines instead of eight and stores partial
+// lines: an odd n cost 14 to 26 % of the whole all-reduce).  The elements before it are done one
+// per lane.
+inline LA_HOST_DEVICE uint64_t finish_segment(SegInfo& si, uint64_t len, uint64_t first, uint32_t esize, bool congruent,
+                                              uint32_t align)
+{
+    const uint64_t vec = 16 / esize;
+    si.len = len;
+    if (!congruent) {
+        si.head = 0;
+        si.vec_ok = 0;
+        return (len + vec - 1) / vec;
+    }
+    uint64_t head = ((align - (first & (align - 1))) & (align - 1)) / esize;
+    if (head > len) head = len;
+    si.head = (uint32_t)head;
+    si.vec_ok = 1;
+    return (len - head) / vec;
+}
+
 // How the kernel cuts the 16-byte vectors of a segment into tiles of at most block * unroll.
 enum : uint32_t {
     TILING_PLAIN = 0,   // full tiles from the segment's start, the last one ragged
@@ -110,9 +148,24 @@ Tuning current_tuning();
 Tuning resolve_tuning(const Tuning& requested, uint32_t k, uint32_t m, uint64_t longest_units,
                       uint64_t bytes_per_operand, bool all_inputs, size_t esize, uint64_t working_set);
 
+// runtime.cpp: a segment's record from its resolved operand addresses (ptrs = k sources followed by
+// the destinations; returns its length in 16-byte units), and the grid of a launch: edge
+// workgroups, workgroups per segment, tiling.  dp = destination addresses, m per segment.
+uint64_t describe_segment(SegInfo& si, uint64_t len, const uint64_t* ptrs, size_t count, size_t esize, size_t k);
+uint32_t plan_edges(const SegInfo* seg, size_t S, size_t esize, const Tuning& shape);
+uint32_t plan_tiles(const SegInfo* seg, const uint64_t* dp, size_t S, size_t m, size_t esize, const Tuning& shape,
+                    uint64_t longest, uint32_t* tiling);
+
 // kernels.hip
 la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune, void* hip_stream);
+la_status_t check_launch(const StepTable& t, la_dtype_t dtype, const Tuning& tune); // what launch_step would refuse
 uint32_t tiles_for(uint64_t max_units, const Tuning& tune); // units = 16-byte vectors per operand
+
+// runtime.cpp: the argument checks common to la_reduce_segments and its allocation-free variant
+// (everything but the overlap of segments); *nothing is set when the call has no work to do.
+la_status_t check_reduce_segments_args(const char* who, const void* dst, const void* const* srcs, int k,
+                                       const size_t* seg_offsets, size_t num_segments, size_t seg_len, la_dtype_t dtype,
+                                       la_op_t op, bool* nothing);
 
 // error reporting
 la_status_t fail(la_status_t st, const char* fmt, ...);

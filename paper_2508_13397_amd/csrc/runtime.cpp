@@ -214,45 +214,22 @@ void release_binding(la_binding* b)
     delete b;
 }
 
-namespace {
-
-inline uint64_t align_up(uint64_t x, uint64_t a)
-{
-    return (x + a - 1) / a * a;
-}
-
 // Fill SegInfo for one segment from its resolved operand addresses; returns its length in
 // 16-byte units as the launch sees it.
 uint64_t describe_segment(SegInfo& si, uint64_t len, const uint64_t* ptrs, size_t count, size_t esize, size_t k)
 {
     // ptrs = k sources followed by the destinations
-    const uint64_t vec = 16 / esize;
     si.alias_mask = 0;
     for (size_t t = 0; t < k && t < 64; ++t)
         for (size_t d = k; d < count; ++d)
             if (ptrs[d] == ptrs[t]) si.alias_mask |= uint64_t(1) << t;
     bool congruent = true;
-    for (size_t i = 1; i < count; ++i)
+    uint32_t align = 128;
+    for (size_t i = 1; i < count; ++i) {
         if (((ptrs[i] ^ ptrs[0]) & 15u) != 0) congruent = false;
-    si.len = len;
-    if (!congruent) {
-        si.head = 0;
-        si.vec_ok = 0;
-        return (len + vec - 1) / vec;
-    }
-    // The vector body starts at the first 16-byte boundary -- or, when all operands also agree
-    // modulo a cache line (the usual case: an odd element offset into 256-byte aligned buffers),
-    // at the first 128-byte boundary, so that every wave's 1 KiB access covers whole lines
-    // (otherwise each touches nine lines instead of eight and stores partial lines: an odd n
-    // cost 14 to 26 % of the whole all-reduce).  The elements before it are done one per lane.
-    uint64_t align = 128;
-    for (size_t i = 1; i < count; ++i)
         if (((ptrs[i] ^ ptrs[0]) & 127u) != 0) align = 16;
-    uint64_t head = ((align - (ptrs[0] & (align - 1))) & (align - 1)) / esize;
-    if (head > len) head = len;
-    si.head = (uint32_t)head;
-    si.vec_ok = 1;
-    return (len - head) / vec;
+    }
+    return finish_segment(si, len, ptrs[0], (uint32_t)esize, congruent, align);
 }
 
 // Workgroups per segment of a launch and how the kernel cuts a segment into tiles.
@@ -310,6 +287,8 @@ uint32_t plan_tiles(const SegInfo* seg, const uint64_t* dp, size_t S, size_t m, 
     *tiling = TILING_ALIGNED;
     return (uint32_t)most;
 }
+
+namespace {
 
 struct HostTables {
     std::vector<unsigned char> blob;
@@ -564,8 +543,13 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void*
         if (b->graph_exec && b->graph_op != op) drop_graph(b);
         if (!b->graph_exec && capture_graph(sched, b, op) != LA_OK) b->graph_failed = true;
         if (b->graph_exec) {
-            LA_HIP(hipGraphLaunch(b->graph_exec, stream));
-            launched = true;
+            if (hipGraphLaunch(b->graph_exec, stream) == hipSuccess) {
+                launched = true;
+            } else {
+                (void)hipGetLastError(); // the graph is given up; the steps are launched one by one
+                drop_graph(b);
+                b->graph_failed = true;
+            }
         }
     }
     if (!launched) {
@@ -582,6 +566,35 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void*
 }
 
 } // namespace
+} // namespace la
+
+namespace la {
+la_status_t check_reduce_segments_args(const char* who, const void* dst, const void* const* srcs, int k,
+                                       const size_t* seg_offsets, size_t num_segments, size_t seg_len, la_dtype_t dtype,
+                                       la_op_t op, bool* nothing)
+{
+    *nothing = false;
+    if (!known_op((int)op)) return fail(LA_ERR_UNSUPPORTED, "%s: unknown operation %d", who, (int)op);
+    if (!known_dtype((int)dtype)) return fail(LA_ERR_UNSUPPORTED, "%s: unknown dtype %d", who, (int)dtype);
+    if (k < 0) return fail(LA_ERR_INVALID_ARG, "%s: k is negative", who);
+    if (!dst) return fail(LA_ERR_INVALID_ARG, "%s: dst is NULL", who);
+    if (k > 0 && !srcs) return fail(LA_ERR_INVALID_ARG, "%s: srcs is NULL", who);
+    if (num_segments > 0 && !seg_offsets) return fail(LA_ERR_INVALID_ARG, "%s: seg_offsets is NULL", who);
+    const size_t e = dtype_size(dtype);
+    if (reinterpret_cast<uint64_t>(dst) % e) return fail(LA_ERR_INVALID_ARG, "%s: dst is not aligned to the element size", who);
+    for (int t = 0; t < k; ++t) {
+        if (!srcs[t]) return fail(LA_ERR_INVALID_ARG, "%s: srcs[%d] is NULL", who, t);
+        if (reinterpret_cast<uint64_t>(srcs[t]) % e)
+            return fail(LA_ERR_INVALID_ARG, "%s: srcs[%d] is not aligned to the element size", who, t);
+        if (srcs[t] == dst) return fail(LA_ERR_INVALID_ARG, "%s: srcs[%d] aliases dst", who, t);
+    }
+    if (k == 0 || num_segments == 0 || seg_len == 0) {
+        *nothing = true; // nothing to add
+        return LA_OK;
+    }
+    if (num_segments > 0xffffffffull) return fail(LA_ERR_INVALID_ARG, "%s: too many segments", who);
+    return LA_OK;
+}
 } // namespace la
 
 // ---- pinned upload chunks for one-shot tables ----------------------------------------------------
@@ -695,10 +708,14 @@ la_status_t la_schedule_launch_plan(const la_schedule_t* sched, int step, const 
     addr[sched->nbuf] = reinterpret_cast<uint64_t>(staging);
     if (sched->staging_elems > 0 && (addr[sched->nbuf] == 0 || addr[sched->nbuf] % 16))
         return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: the schedule is staged: pass a 16-byte aligned staging address");
-    const std::vector<Step> one(1, sched->steps[step]);
     HostTables ht;
     std::vector<Tuning> shapes;
-    resolve_tables(one, addr, e, current_tuning(), (uint64_t)sched->nbuf * sched->n * e, ht, shapes);
+    try {
+        const std::vector<Step> one(1, sched->steps[step]);
+        resolve_tables(one, addr, e, current_tuning(), (uint64_t)sched->nbuf * sched->n * e, ht, shapes);
+    } catch (const std::bad_alloc&) {
+        return fail(LA_ERR_OUT_OF_MEMORY, "la_schedule_launch_plan: out of host memory");
+    }
     const StepTable& v = ht.view[0];
     out->block = shapes[0].block;
     out->unroll = shapes[0].unroll;
@@ -714,31 +731,21 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
                                size_t num_segments, size_t seg_len, la_dtype_t dtype, la_op_t op,
                                void* hip_stream)
 {
-    if (!known_op((int)op)) return fail(LA_ERR_UNSUPPORTED, "la_reduce_segments: unknown operation %d", (int)op);
-    if (!known_dtype((int)dtype))
-        return fail(LA_ERR_UNSUPPORTED, "la_reduce_segments: unknown dtype %d", (int)dtype);
-    if (k < 0) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: k is negative");
-    if (!dst) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: dst is NULL");
-    if (k > 0 && !srcs) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: srcs is NULL");
-    if (num_segments > 0 && !seg_offsets) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: seg_offsets is NULL");
-    const size_t e = dtype_size(dtype);
-    const uint64_t d = reinterpret_cast<uint64_t>(dst);
-    if (d % e) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: dst is not aligned to the element size");
-    for (int t = 0; t < k; ++t) {
-        if (!srcs[t]) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: srcs[%d] is NULL", t);
-        if (reinterpret_cast<uint64_t>(srcs[t]) % e)
-            return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: srcs[%d] is not aligned to the element size", t);
-        if (srcs[t] == dst) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: srcs[%d] aliases dst", t);
-    }
-    if (k == 0 || num_segments == 0 || seg_len == 0) return LA_OK; // nothing to add
-    if (num_segments > 0xffffffffull) return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: too many segments");
-    {
+    bool nothing = false;
+    la_status_t vst = check_reduce_segments_args("la_reduce_segments", dst, srcs, k, seg_offsets, num_segments, seg_len,
+                                                 dtype, op, &nothing);
+    if (vst != LA_OK || nothing) return vst;
+    try {
         std::vector<size_t> sorted(seg_offsets, seg_offsets + num_segments);
         std::sort(sorted.begin(), sorted.end());
         for (size_t s = 1; s < num_segments; ++s)
             if (sorted[s] < sorted[s - 1] + seg_len)
                 return fail(LA_ERR_INVALID_ARG, "la_reduce_segments: segments overlap");
+    } catch (const std::bad_alloc&) {
+        return fail(LA_ERR_OUT_OF_MEMORY, "la_reduce_segments: out of host memory");
     }
+    const size_t e = dtype_size(dtype);
+    const uint64_t d = reinterpret_cast<uint64_t>(dst);
 
     // Tables for one step with k+1 sources (dst first) and one destination.
     const size_t K = (size_t)k + 1;
@@ -755,16 +762,38 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
     uint64_t* sp = reinterpret_cast<uint64_t*>(blob + seg_bytes);
     uint64_t* dp = reinterpret_cast<uint64_t*>(blob + seg_bytes + src_bytes);
     uint64_t longest = 0;
-    std::vector<uint64_t> all;
+    uint64_t all_small[66];
+    std::vector<uint64_t> all_big;
+    uint64_t* all = all_small;
+    try {
+        if (K + 1 > 66) {
+            all_big.resize(K + 1);
+            all = all_big.data();
+        }
+    } catch (const std::bad_alloc&) {
+        return fail(LA_ERR_OUT_OF_MEMORY, "la_reduce_segments: out of host memory");
+    }
     for (size_t s = 0; s < num_segments; ++s) {
         const uint64_t byte_off = (uint64_t)seg_offsets[s] * e;
         sp[s * K] = d + byte_off;
         for (int t = 0; t < k; ++t) sp[s * K + 1 + t] = reinterpret_cast<uint64_t>(srcs[t]) + byte_off;
         dp[s] = d + byte_off;
-        all.assign(sp + s * K, sp + (s + 1) * K);
-        all.push_back(dp[s]);
-        longest = std::max(longest, describe_segment(seg[s], seg_len, all.data(), all.size(), e, K));
+        std::copy(sp + s * K, sp + (s + 1) * K, all);
+        all[K] = dp[s];
+        longest = std::max(longest, describe_segment(seg[s], seg_len, all, K + 1, e, K));
     }
+    // the launch is planned, and everything that can refuse it is checked, before anything is enqueued
+    StepTable t;
+    t.k = (uint32_t)K;
+    t.m = 1;
+    t.op = (uint32_t)op;
+    t.num_segments = (uint32_t)num_segments;
+    const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest, (uint64_t)num_segments * seg_len * e, false, e,
+                                       (uint64_t)(K + 1) * num_segments * seg_len * e);
+    t.tiles_per_seg = plan_tiles(seg, dp, num_segments, 1, e, tune, longest, &t.tiling);
+    t.edge_blocks = plan_edges(seg, num_segments, e, tune);
+    la_status_t st = check_launch(t, dtype, tune);
+    if (st != LA_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     void* dev = nullptr;
     if (hipMallocAsync(&dev, total_bytes, stream) != hipSuccess)
@@ -777,20 +806,11 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
         return fail(LA_ERR_DEVICE, "la_reduce_segments: table upload failed: %s", hipGetErrorString(he));
     }
     chunk->in_flight = true;
-    StepTable t;
     const uint64_t b = reinterpret_cast<uint64_t>(dev);
     t.seg = reinterpret_cast<const SegInfo*>(b);
     t.src_ptr = reinterpret_cast<const uint64_t*>(b + seg_bytes);
     t.dst_ptr = reinterpret_cast<const uint64_t*>(b + seg_bytes + src_bytes);
-    t.k = (uint32_t)K;
-    t.m = 1;
-    t.op = (uint32_t)op;
-    t.num_segments = (uint32_t)num_segments;
-    const Tuning tune = resolve_tuning(current_tuning(), t.k, t.m, longest, (uint64_t)num_segments * seg_len * e, false, e,
-                                       (uint64_t)(K + 1) * num_segments * seg_len * e);
-    t.tiles_per_seg = plan_tiles(seg, dp, num_segments, 1, e, tune, longest, &t.tiling);
-    t.edge_blocks = plan_edges(seg, num_segments, e, tune);
-    la_status_t st = launch_step(t, dtype, tune, hip_stream);
+    st = launch_step(t, dtype, tune, hip_stream);
     (void)hipFreeAsync(dev, stream); // stream-ordered: freed after the kernel has run
     return st;
 }
