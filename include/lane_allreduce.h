@@ -290,6 +290,24 @@ la_status_t la_reduce_segments(void* dst, const void* const* srcs, int k, const 
                                size_t num_segments, size_t seg_len, la_dtype_t dtype, la_op_t op,
                                void* hip_stream);
 
+/*
+ * la_reduce_segments for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result, bit for bit; the
+ * call makes no allocation of any kind on the device or in pinned host memory and no copy: the
+ * per-call tables that la_reduce_segments keeps in a stream-ordered allocation live in a static
+ * device array of 1 MiB (held by every GPU the library runs on until the process ends) and are
+ * written there by a small kernel launched on hip_stream ahead of the reduce kernel.
+ * Limits: k <= 64, num_segments <= 8192, and num_segments * (32 + 8 * (k + 1)) bytes (each of the
+ * three tables rounded up to 256) <= 1 MiB; beyond them LA_ERR_INVALID_ARG, nothing enqueued.
+ * All calls on one GPU share the one array: calls on the same stream are ordered and safe, calls
+ * that may overlap on the GPU (different streams, or host threads on different streams) race and
+ * must be ordered by the caller.  The array's device address is looked up on the first call on a
+ * device; make that call outside a graph capture.
+ */
+la_status_t la_reduce_segments_static(void* dst, const void* const* srcs, int k, const size_t* seg_offsets,
+                                      size_t num_segments, size_t seg_len, la_dtype_t dtype, la_op_t op,
+                                      void* hip_stream);
+
 /* ---- diagnostics and tuning ----------------------------------------------------------- */
 
 const char* la_status_string(la_status_t status);

@@ -44,6 +44,7 @@ EXPORTS = (
     "la_schedule_num_buffers", "la_schedule_owned_ranges", "la_schedule_step_group",
     "la_schedule_staging_elems", "la_schedule_step_info", "la_schedule_step_table",
     "la_allreduce_emulated", "la_allreduce_emulated_out_of_place", "la_schedule_run_step", "la_reduce_segments",
+    "la_reduce_segments_static",
     "la_schedule_launch_plan",
     "la_status_string", "la_last_error", "la_tuning_set", "la_tuning_get",
 )
@@ -97,6 +98,7 @@ def lib() -> ctypes.CDLL:
     L.la_schedule_run_step.argtypes = [vp, i32, pp(vp), vp]
     L.la_schedule_launch_plan.argtypes = [vp, i32, pp(vp), pp(vp), vp, pp(LaunchPlan)]
     L.la_reduce_segments.argtypes = [vp, pp(vp), i32, pp(sz), sz, sz, i32, i32, vp]
+    L.la_reduce_segments_static.argtypes = L.la_reduce_segments.argtypes
     L.la_status_string.argtypes = [i32]
     L.la_status_string.restype = ctypes.c_char_p
     L.la_last_error.restype = ctypes.c_char_p
@@ -288,3 +290,13 @@ def la_reduce_segments(dst: int, srcs: Sequence[int], seg_offsets: Sequence[int]
     _check(lib().la_reduce_segments(ctypes.c_void_p(dst), _ptr_array(srcs), len(srcs), offs, len(seg_offsets),
                                     int(seg_len), dtype, int(op), ctypes.c_void_p(stream)),
            "la_reduce_segments")
+
+
+def la_reduce_segments_static(dst: int, srcs: Sequence[int], seg_offsets: Sequence[int], seg_len: int, dtype,
+                              op: int = LA_SUM, stream: int = 0) -> None:
+    """la_reduce_segments without any allocation (tables in the library's static device array)."""
+    dtype = DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
+    offs = (ctypes.c_size_t * max(len(seg_offsets), 1))(*[int(o) for o in seg_offsets])
+    _check(lib().la_reduce_segments_static(ctypes.c_void_p(dst), _ptr_array(srcs), len(srcs), offs, len(seg_offsets),
+                                           int(seg_len), dtype, int(op), ctypes.c_void_p(stream)),
+           "la_reduce_segments_static")

@@ -24,7 +24,7 @@ FLAGS = [
 # family; the largest units come first so that the pool stays busy to the end
 UNITS = [("kernels.hip", f"kernels_dtype{d}_shape{f}.o", [f"-DLA_KERNEL_DTYPE={d}", f"-DLA_KERNEL_SHAPE={f}"])
          for f in (2, 0, 1) for d in (2, 3, 4, 1, 0)] + [
-    ("dispatch.cpp", "dispatch.o", []), ("runtime.cpp", "runtime.o", []), ("schedule.cpp", "schedule.o", [])]
+    ("static_scratch.hip", "static_scratch.o", []), ("dispatch.cpp", "dispatch.o", []), ("runtime.cpp", "runtime.o", []), ("schedule.cpp", "schedule.o", [])]
 
 
 def stale() -> bool:
