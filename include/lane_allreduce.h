@@ -274,6 +274,19 @@ typedef struct la_launch_plan {
 la_status_t la_schedule_launch_plan(const la_schedule_t* sched, int step, const void* const* bufs,
                                     const void* const* sendbufs, const void* staging, la_launch_plan_t* out);
 
+/* Host only, like la_schedule_launch_plan: the segments of one step as they are launched.  A table
+ * segment whose source ranges start where those of the segment before it end, and whose destination
+ * ranges do too (as a set: the order of a destination list does not matter, every destination
+ * receives the same value), is launched as part of that segment: the N pieces of a part in the
+ * inter-node step, every segment of the one-launch form.  The sums and their order are unchanged,
+ * and la_schedule_step_info / la_schedule_step_table keep reporting the segments as generated.
+ * Writes the number of launch segments to *count and, for the first min(capacity, *count) of them,
+ * seg_len[g] (elements), src_addr[g * fan_in + t] and dst_addr[g * fan_out + d] (byte addresses;
+ * any of the three arrays may be NULL) [host]. */
+la_status_t la_schedule_launch_segments(const la_schedule_t* sched, int step, const void* const* bufs,
+                                        const void* const* sendbufs, const void* staging, size_t capacity,
+                                        size_t* count, uint64_t* seg_len, uint64_t* src_addr, uint64_t* dst_addr);
+
 /*
  * k incoming segments summed into the owned segment (the local reduction that follows each
  * received message, "GPU-Aware All-Reduce Operations" subsection), for num_segments segments
@@ -325,6 +338,8 @@ const char* la_last_error(void);
  *                 A three-digit value abc sets policy a for pure reduce steps, b for reduce
  *                 steps with several destinations and c for copy / broadcast steps.
  *   "block"       lanes per workgroup: 256, 1024; 0 = automatic
+ *   "merge"       1 (default): table-adjacent segments that continue each other are launched as one
+ *                 (see la_schedule_launch_segments); 0: every table segment is a launch segment
  *   "graph"       1: la_allreduce_emulated replays the schedule as one HIP graph of kernel nodes,
  *                 0: it launches step by step, -1 (default): graph for schedules of 16+ launches
  * la_tuning_set returns LA_ERR_INVALID_ARG for an unknown key or value; la_tuning_get returns

@@ -45,7 +45,7 @@ EXPORTS = (
     "la_schedule_staging_elems", "la_schedule_step_info", "la_schedule_step_table",
     "la_allreduce_emulated", "la_allreduce_emulated_out_of_place", "la_schedule_run_step", "la_reduce_segments",
     "la_reduce_segments_static",
-    "la_schedule_launch_plan",
+    "la_schedule_launch_plan", "la_schedule_launch_segments",
     "la_status_string", "la_last_error", "la_tuning_set", "la_tuning_get",
 )
 
@@ -97,6 +97,7 @@ def lib() -> ctypes.CDLL:
     L.la_allreduce_emulated_out_of_place.argtypes = [vp, pp(vp), pp(vp), sz, i32, i32, vp]
     L.la_schedule_run_step.argtypes = [vp, i32, pp(vp), vp]
     L.la_schedule_launch_plan.argtypes = [vp, i32, pp(vp), pp(vp), vp, pp(LaunchPlan)]
+    L.la_schedule_launch_segments.argtypes = [vp, i32, pp(vp), pp(vp), vp, sz, pp(sz), vp, vp, vp]
     L.la_reduce_segments.argtypes = [vp, pp(vp), i32, pp(sz), sz, sz, i32, i32, vp]
     L.la_reduce_segments_static.argtypes = L.la_reduce_segments.argtypes
     L.la_status_string.argtypes = [i32]
@@ -281,6 +282,23 @@ def la_schedule_launch_plan(sched: Schedule, step: int, bufs: Sequence[int], sen
                                          _ptr_array(sendbufs) if sendbufs is not None else None,
                                          ctypes.c_void_p(staging), ctypes.byref(plan)), "la_schedule_launch_plan")
     return {name: int(getattr(plan, name)) for name, _ in LaunchPlan._fields_}
+
+
+def la_schedule_launch_segments(sched: Schedule, step: int, bufs: Sequence[int],
+                                sendbufs: Optional[Sequence[int]] = None, staging: int = 0) -> dict:
+    """Host only: the segments of `step` as launched for buffers at these addresses (after merging)."""
+    info = sched.step_info(step)
+    k, m, cap = info["fan_in"], info["fan_out"], info["num_segments"]
+    count = ctypes.c_size_t()
+    seg_len = np.zeros(max(cap, 1), dtype=np.uint64)
+    src = np.zeros((max(cap, 1), k), dtype=np.uint64)
+    dst = np.zeros((max(cap, 1), m), dtype=np.uint64)
+    _check(lib().la_schedule_launch_segments(sched.handle, int(step), _ptr_array(bufs),
+                                             _ptr_array(sendbufs) if sendbufs is not None else None,
+                                             ctypes.c_void_p(staging), cap, ctypes.byref(count), seg_len.ctypes.data,
+                                             src.ctypes.data, dst.ctypes.data), "la_schedule_launch_segments")
+    c = int(count.value)
+    return dict(count=c, seg_len=seg_len[:c], src_addr=src[:c], dst_addr=dst[:c])
 
 
 def la_reduce_segments(dst: int, srcs: Sequence[int], seg_offsets: Sequence[int], seg_len: int, dtype,

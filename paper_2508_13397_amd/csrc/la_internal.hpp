@@ -134,9 +134,10 @@ struct Tuning {
     int unroll = 0;       // 16-byte vectors per lane and operand: 1, 2, 4, 8
     int cache_policy = -1; // 0..7, see Policy<> in kernels.hip
     int block = 0;        // lanes per workgroup: 256, 1024
+    int merge = 1;        // launch table-adjacent segments that continue each other as one
     bool operator==(const Tuning& o) const
     {
-        return unroll == o.unroll && block == o.block && cache_policy == o.cache_policy;
+        return unroll == o.unroll && block == o.block && cache_policy == o.cache_policy && merge == o.merge;
     }
 };
 Tuning current_tuning();

@@ -24,6 +24,7 @@ namespace la {
 static std::atomic<int> g_unroll{0};
 static std::atomic<int> g_cache_policy{-1};
 static std::atomic<int> g_block{0};
+static std::atomic<int> g_merge{1};
 static std::atomic<int> g_graph{-1}; // -1: graphs for schedules of GRAPH_MIN_STEPS launches or more
 // Measured: a graph launch costs the host about 15 us whatever it holds, a stream launch 2.5 to 3 us;
 // on the GPU a kernel node and a stream launch take the same time.  Below 16 launches the stream wins.
@@ -35,6 +36,7 @@ Tuning current_tuning()
     t.unroll = g_unroll.load();
     t.cache_policy = g_cache_policy.load();
     t.block = g_block.load();
+    t.merge = g_merge.load();
     return t;
 }
 
@@ -60,6 +62,7 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
                       bool all_inputs, size_t esize, uint64_t working_set)
 {
     Tuning t;
+    bool store_bound = false; // many more stores than loads per workgroup: the workgroup count matters little
     int cls; // step class: 0 pure reduce, 1 reduce + multi-destination store, 2 copy / broadcast
     // measured on 16 ranks: the cache-resident shapes win up to about 1.25 times the cache (a result of
     // 320 MiB: 0.575 against 0.590 ms), and lose from 1.5 times on (0.738 against 0.709 ms)
@@ -85,9 +88,15 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
             t.block = 1024;
             t.unroll = 8;
         } else if (k >= 3) {
-            // operands that stream from DRAM want long runs; cache-resident ones small tiles
+            // Operands that stream from DRAM want long runs; cache-resident ones small tiles.  What
+            // decides is what the step READS: k operands of the result's size.  C2 S1 (k = 4, result
+            // 256 MiB, inputs 1 GiB) streams its inputs whatever the loop before it left in the cache:
+            // from a cold cache 128 KiB tiles give 6.10 TB/s against 5.65 with 16 KiB tiles; in a loop
+            // over the same buffers, where a quarter of the inputs is still cache-resident, they cost
+            // 5 % of the step (201 against 191 us).
+            const bool reads_fit = (uint64_t)k * bytes_per_operand <= LAST_LEVEL_CACHE_BYTES + LAST_LEVEL_CACHE_BYTES / 4;
             t.block = 1024;
-            t.unroll = fits ? 1 : 8;
+            t.unroll = reads_fit ? 1 : 8;
         } else {
             t.block = fits ? 256 : 1024; // short launches start and drain faster with small workgroups
             t.unroll = 4;
@@ -132,10 +141,15 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
             t.block = 1024;
             t.unroll = esize < 4 ? 4 : 8;
         } else if (m >= 8 && m > k) {
-            // the all-gathers folded into the reduce: store-dominated, like a broadcast
+            // The all-gathers folded into the reduce: store-dominated, like a broadcast.  A workgroup
+            // streams its tile to m destinations, so few large workgroups do better than one per
+            // compute unit: C3 (k = 8, m = 128, 1 MiB segments) 128 workgroups of 128 KiB 342 us, 256 of
+            // 64 KiB 364; C5 (k = 32, m = 1024, 128 KiB segments) 64 workgroups of 64 KiB 706 us, 256 of
+            // 16 KiB 825, 32 of 128 KiB 1162 (with a fan-in of 32 the loads of a 128 KiB tile take too long).
             t.cache_policy = fits ? 4 : 6;
             t.block = 1024;
-            t.unroll = 8;
+            t.unroll = k >= 16 ? 4 : 8;
+            store_bound = true;
         } else if (k < 8) {
             t.block = 1024;
             t.unroll = 1;
@@ -161,9 +175,9 @@ Tuning resolve_tuning(const Tuning& req, uint32_t k, uint32_t m, uint64_t longes
     // ... nor so long that the step has fewer workgroups than the GPU has compute units
     const uint64_t vectors = bytes_per_operand / 16;
     constexpr uint64_t COMPUTE_UNITS = 256;
-    if (req.unroll <= 0)
+    if (req.unroll <= 0 && !store_bound)
         while (t.unroll > 1 && vectors / ((uint64_t)t.block * t.unroll) < COMPUTE_UNITS) t.unroll /= 2;
-    if (req.block <= 0)
+    if (req.block <= 0 && !store_bound)
         if (t.block > 256 && vectors / ((uint64_t)t.block * t.unroll) < COMPUTE_UNITS) t.block = 256;
     if (t.unroll == 8 && t.block != 1024) t.unroll = 4; // 128 KiB tiles exist for 1024 lanes only
     return t;
@@ -325,28 +339,59 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
     // gains 5 to 19 %, at 96 MiB nothing, beyond that it is +-2 % either way.
     Tuning request = tune;
     if (working_set <= SMALL_SCHEDULE_BYTES && request.block <= 0) request.block = 256;
-    std::vector<uint64_t> all;
+    std::vector<uint64_t> all, cur_dst, cand_dst;
     for (size_t i = 0; i < steps.size(); ++i) {
         const Step& p = steps[i];
-        const size_t S = p.num_segments();
+        const size_t S = p.num_segments(), k = (size_t)p.k, m = (size_t)p.m;
         SegInfo* seg = reinterpret_cast<SegInfo*>(out.blob.data() + seg_at[i]);
         uint64_t* sp = reinterpret_cast<uint64_t*>(out.blob.data() + src_at[i]);
         uint64_t* dp = reinterpret_cast<uint64_t*>(out.blob.data() + dst_at[i]);
-        uint64_t longest = 0, step_elems = 0;
+        // Launch segments: a table segment continues the one before it when every source range starts
+        // where that one's ended and the destination ranges do too, as a set (a piece is stored to the
+        // same buffers whoever reduces it; only the order of the list differs, and every destination
+        // receives the same value).  Such runs are launched as one segment: the pieces of a part in the
+        // inter-node step (C5: 1024 segments of 4 KiB become 32 of 128 KiB), every segment of the
+        // one-launch form.  Same sums in the same order; the logical tables stay as generated.
+        size_t launched = 0; // segments written so far
+        uint64_t step_elems = 0;
+        bool cur_dst_valid = false;
         for (size_t g = 0; g < S; ++g) {
             step_elems += p.len[g];
-            all.clear();
-            for (int t = 0; t < p.k; ++t) {
-                const Operand& o = p.src[g * p.k + t];
-                sp[g * p.k + t] = base[o.buf] + o.off * esize;
-                all.push_back(sp[g * p.k + t]);
+            uint64_t* s_new = sp + launched * k;
+            uint64_t* d_new = dp + launched * m;
+            for (size_t t = 0; t < k; ++t) s_new[t] = base[p.src[g * k + t].buf] + p.src[g * k + t].off * esize;
+            for (size_t d = 0; d < m; ++d) d_new[d] = base[p.dst[g * m + d].buf] + p.dst[g * m + d].off * esize;
+            if (tune.merge && launched > 0) {
+                const uint64_t shift = seg[launched - 1].len * esize;
+                const uint64_t* s_old = s_new - k;
+                const uint64_t* d_old = d_new - m;
+                bool same = true;
+                for (size_t t = 0; t < k && same; ++t) same = s_new[t] == s_old[t] + shift;
+                if (same && m == 1) same = d_new[0] == d_old[0] + shift;
+                if (same && m > 1) {
+                    if (!cur_dst_valid) {
+                        cur_dst.assign(d_old, d_old + m);
+                        std::sort(cur_dst.begin(), cur_dst.end());
+                        cur_dst_valid = true;
+                    }
+                    cand_dst.assign(d_new, d_new + m);
+                    std::sort(cand_dst.begin(), cand_dst.end());
+                    for (size_t d = 0; d < m && same; ++d) same = cand_dst[d] == cur_dst[d] + shift;
+                }
+                if (same) {
+                    seg[launched - 1].len += p.len[g];
+                    continue;
+                }
             }
-            for (int d = 0; d < p.m; ++d) {
-                const Operand& o = p.dst[g * p.m + d];
-                dp[g * p.m + d] = base[o.buf] + o.off * esize;
-                all.push_back(dp[g * p.m + d]);
-            }
-            longest = std::max(longest, describe_segment(seg[g], p.len[g], all.data(), all.size(), esize, (size_t)p.k));
+            seg[launched].len = p.len[g];
+            cur_dst_valid = false;
+            ++launched;
+        }
+        uint64_t longest = 0;
+        for (size_t g = 0; g < launched; ++g) {
+            all.assign(sp + g * k, sp + (g + 1) * k);
+            all.insert(all.end(), dp + g * m, dp + (g + 1) * m);
+            longest = std::max(longest, describe_segment(seg[g], seg[g].len, all.data(), all.size(), esize, k));
         }
         StepTable& v = out.view[i];
         v.seg = reinterpret_cast<const SegInfo*>(seg_at[i]);
@@ -355,11 +400,11 @@ void resolve_tables(const std::vector<Step>& steps, const std::vector<uint64_t>&
         v.k = (uint32_t)p.k;
         v.m = (uint32_t)p.m;
         v.group = (uint32_t)p.group;
-        v.num_segments = (uint32_t)S;
+        v.num_segments = (uint32_t)launched;
         shapes[i] = resolve_tuning(request, v.k, v.m, longest, step_elems * esize,
                                    p.stage == LA_STAGE_S1_S2_S3 && p.k > 1 && p.m > 1, esize, working_set);
-        v.tiles_per_seg = plan_tiles(seg, dp, S, (size_t)p.m, esize, shapes[i], longest, &v.tiling);
-        v.edge_blocks = plan_edges(seg, S, esize, shapes[i]);
+        v.tiles_per_seg = plan_tiles(seg, dp, launched, m, esize, shapes[i], longest, &v.tiling);
+        v.edge_blocks = plan_edges(seg, launched, esize, shapes[i]);
     }
 }
 
@@ -693,29 +738,38 @@ la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* con
     return run_steps(sched, bufs, nullptr, step, step + 1, (uint32_t)LA_SUM, hip_stream);
 }
 
-la_status_t la_schedule_launch_plan(const la_schedule_t* sched, int step, const void* const* bufs,
-                                    const void* const* sendbufs, const void* staging, la_launch_plan_t* out)
+// the launch tables of one step for buffers at the given addresses (host only)
+static la_status_t plan_one_step(const char* who, const la_schedule_t* sched, int step, const void* const* bufs,
+                                 const void* const* sendbufs, const void* staging, HostTables& ht,
+                                 std::vector<Tuning>& shapes)
 {
-    if (!sched) return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: schedule is NULL");
-    if (!bufs) return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: bufs is NULL");
-    if (!out) return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: out is NULL");
-    if (step < 0 || step >= (int)sched->steps.size())
-        return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: step %d out of range", step);
-    std::vector<uint64_t> addr;
-    la_status_t st = check_buffers(*sched, const_cast<void* const*>(bufs), sendbufs, addr);
-    if (st != LA_OK) return st;
-    const size_t e = dtype_size(sched->dtype);
-    addr[sched->nbuf] = reinterpret_cast<uint64_t>(staging);
-    if (sched->staging_elems > 0 && (addr[sched->nbuf] == 0 || addr[sched->nbuf] % 16))
-        return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: the schedule is staged: pass a 16-byte aligned staging address");
-    HostTables ht;
-    std::vector<Tuning> shapes;
+    if (!sched) return fail(LA_ERR_INVALID_ARG, "%s: schedule is NULL", who);
+    if (!bufs) return fail(LA_ERR_INVALID_ARG, "%s: bufs is NULL", who);
+    if (step < 0 || step >= (int)sched->steps.size()) return fail(LA_ERR_INVALID_ARG, "%s: step %d out of range", who, step);
     try {
+        std::vector<uint64_t> addr;
+        la_status_t st = check_buffers(*sched, const_cast<void* const*>(bufs), sendbufs, addr);
+        if (st != LA_OK) return st;
+        const size_t e = dtype_size(sched->dtype);
+        addr[sched->nbuf] = reinterpret_cast<uint64_t>(staging);
+        if (sched->staging_elems > 0 && (addr[sched->nbuf] == 0 || addr[sched->nbuf] % 16))
+            return fail(LA_ERR_INVALID_ARG, "%s: the schedule is staged: pass a 16-byte aligned staging address", who);
         const std::vector<Step> one(1, sched->steps[step]);
         resolve_tables(one, addr, e, current_tuning(), (uint64_t)sched->nbuf * sched->n * e, ht, shapes);
     } catch (const std::bad_alloc&) {
-        return fail(LA_ERR_OUT_OF_MEMORY, "la_schedule_launch_plan: out of host memory");
+        return fail(LA_ERR_OUT_OF_MEMORY, "%s: out of host memory", who);
     }
+    return LA_OK;
+}
+
+la_status_t la_schedule_launch_plan(const la_schedule_t* sched, int step, const void* const* bufs,
+                                    const void* const* sendbufs, const void* staging, la_launch_plan_t* out)
+{
+    if (!out) return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_plan: out is NULL");
+    HostTables ht;
+    std::vector<Tuning> shapes;
+    const la_status_t st = plan_one_step("la_schedule_launch_plan", sched, step, bufs, sendbufs, staging, ht, shapes);
+    if (st != LA_OK) return st;
     const StepTable& v = ht.view[0];
     out->block = shapes[0].block;
     out->unroll = shapes[0].unroll;
@@ -724,6 +778,30 @@ la_status_t la_schedule_launch_plan(const la_schedule_t* sched, int step, const 
     out->tiles_per_segment = v.tiles_per_seg;
     out->edge_workgroups = v.edge_blocks;
     out->workgroups = (uint64_t)v.edge_blocks + (uint64_t)v.num_segments * v.tiles_per_seg;
+    return LA_OK;
+}
+
+la_status_t la_schedule_launch_segments(const la_schedule_t* sched, int step, const void* const* bufs,
+                                        const void* const* sendbufs, const void* staging, size_t capacity,
+                                        size_t* count, uint64_t* seg_len, uint64_t* src_addr, uint64_t* dst_addr)
+{
+    if (!count) return fail(LA_ERR_INVALID_ARG, "la_schedule_launch_segments: count is NULL");
+    HostTables ht;
+    std::vector<Tuning> shapes;
+    const la_status_t st = plan_one_step("la_schedule_launch_segments", sched, step, bufs, sendbufs, staging, ht, shapes);
+    if (st != LA_OK) return st;
+    const StepTable& v = ht.view[0];
+    const unsigned char* blob = ht.blob.data(); // the views hold offsets into the blob until they are relocated
+    const SegInfo* seg = reinterpret_cast<const SegInfo*>(blob + reinterpret_cast<uint64_t>(v.seg));
+    const uint64_t* sp = reinterpret_cast<const uint64_t*>(blob + reinterpret_cast<uint64_t>(v.src_ptr));
+    const uint64_t* dp = reinterpret_cast<const uint64_t*>(blob + reinterpret_cast<uint64_t>(v.dst_ptr));
+    *count = v.num_segments;
+    const size_t take = std::min<size_t>(capacity, v.num_segments);
+    for (size_t g = 0; g < take; ++g) {
+        if (seg_len) seg_len[g] = seg[g].len;
+        if (src_addr) std::copy(sp + g * v.k, sp + (g + 1) * v.k, src_addr + g * v.k);
+        if (dst_addr) std::copy(dp + g * v.m, dp + (g + 1) * v.m, dst_addr + g * v.m);
+    }
     return LA_OK;
 }
 
@@ -838,6 +916,11 @@ la_status_t la_tuning_set(const char* key, int value)
         g_graph.store(value);
         return LA_OK;
     }
+    if (k == "merge") {
+        if (value != 0 && value != 1) return fail(LA_ERR_INVALID_ARG, "la_tuning_set: merge must be 0 or 1");
+        g_merge.store(value);
+        return LA_OK;
+    }
     if (k == "block") {
         if (value != 0 && value != 256 && value != 1024)
             return fail(LA_ERR_INVALID_ARG, "la_tuning_set: block must be 0 (auto), 256 or 1024");
@@ -855,6 +938,7 @@ int la_tuning_get(const char* key)
     if (k == "cache_policy") return g_cache_policy.load();
     if (k == "block") return g_block.load();
     if (k == "graph") return g_graph.load();
+    if (k == "merge") return g_merge.load();
     return -2;
 }
 

@@ -983,6 +983,33 @@ def test_reduce_segments_many_segments_and_misaligned_sources(oracle):
     assert np.array_equal(bits(to_host(dst)), bits(ref))
 
 
+@pytest.mark.parametrize("flags", [0, la.LA_SCHED_FUSED_GATHER, la.LA_SCHED_SINGLE_LAUNCH, la.LA_SCHED_P2P_GATHER])
+def test_merged_and_unmerged_launch_segments_give_the_same_bits(oracle, flags):
+    """Table-adjacent segments that continue each other are launched as one (the pieces of a part in
+    the inter-node step, everything in the one-launch form); with the knob off every table segment
+    is launched by itself.  Both must equal the oracle bit for bit, on lengths that leave ragged
+    pieces and on views at an odd offset."""
+    topo = (3, 2, 2)
+    for kind, n, shift in (("f32order", 100003, 0), ("bf16", 77777, 3), ("i32wrap", 4099, 1), ("f32order", 1 << 18, 0)):
+        x = make(12, n, kind, seed=9)
+        ref = oracle.allreduce("lane_multiproc", *topo, x)
+        for merge in (1, 0):
+            try:
+                la.la_tuning_set("merge", merge)
+                t = la.la_topology_create(*topo)
+                sched = la.la_schedule_build(t, "lane_multiproc", n, NAME[x.dtype], flags)
+                full = [to_dev(np.concatenate([x[r][:shift], x[r], x[r][:8]])) for r in range(12)]
+                views = [f[shift: shift + n] for f in full]
+                print("merge", merge, kind, n, shift, flags, flush=True)
+                la.la_allreduce_emulated(sched, [v.data_ptr() for v in views], n, NAME[x.dtype], la.LA_SUM,
+                                         torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+                got = np.stack([to_host(v) for v in views])
+            finally:
+                la.la_tuning_set("merge", 1)
+            assert np.array_equal(bits(got), bits(ref)), (kind, n, shift, flags, merge)
+
+
 # ------------------------------------------------------------------------------ random combinations
 
 def test_random_flag_combinations_on_the_gpu(oracle):

@@ -22,15 +22,15 @@ def fake_buffers(count, n, esize, shift_elems=0, skew=None):
     return [BASE + r * stride + (shift_elems if skew is None else skew[r]) * esize for r in range(count)]
 
 
-def segment_geometry(tab, bufs, esize):
-    """Per segment: (whole vectors, head + tail elements, address of the first whole vector in
-    destination 0 or None when the operands disagree modulo 16 bytes)."""
+def segment_geometry(launch, esize):
+    """Per launch segment: (whole vectors, head + tail elements, address of the first whole vector
+    in destination 0 or None when the operands disagree modulo 16 bytes)."""
     vec = 16 // esize
     out = []
-    for g in range(tab["num_segments"]):
-        addrs = [bufs[b] + int(o) * esize for b, o in zip(tab["src_buf"][g], tab["src_off"][g])]
-        dsts = [bufs[b] + int(o) * esize for b, o in zip(tab["dst_buf"][g], tab["dst_off"][g])]
-        ln = int(tab["seg_len"][g])
+    for g in range(launch["count"]):
+        addrs = [int(a) for a in launch["src_addr"][g]]
+        dsts = [int(a) for a in launch["dst_addr"][g]]
+        ln = int(launch["seg_len"][g])
         every = addrs + dsts
         if any((a ^ every[0]) & 15 for a in every):
             out.append((ln // vec, ln % vec, None))
@@ -42,15 +42,43 @@ def segment_geometry(tab, bufs, esize):
     return out
 
 
-def check_plan(sched, bufs, esize):
+def check_merge(sched, step, bufs, esize, launch):
+    """The launch segments are runs of consecutive table segments: every source list continues the
+    previous one's, the destination sets do too, and a run ends exactly where that stops."""
+    tab = sched.step_table(step)
+    k, m = tab["fan_in"], tab["fan_out"]
+    runs, cur = [], None
+    for g in range(tab["num_segments"]):
+        src = [bufs[b] + int(o) * esize for b, o in zip(tab["src_buf"][g], tab["src_off"][g])]
+        dst = [bufs[b] + int(o) * esize for b, o in zip(tab["dst_buf"][g], tab["dst_off"][g])]
+        ln = int(tab["seg_len"][g])
+        if cur is not None:
+            shift = cur["len"] * esize
+            if src == [a + shift for a in cur["src"]] and sorted(dst) == sorted(a + shift for a in cur["dst"]):
+                cur["len"] += ln
+                continue
+        cur = dict(src=src, dst=dst, len=ln)
+        runs.append(cur)
+    assert launch["count"] == len(runs), (step, launch["count"], len(runs))
+    for g, r in enumerate(runs):
+        assert int(launch["seg_len"][g]) == r["len"]
+        assert [int(a) for a in launch["src_addr"][g]] == r["src"]
+        assert [int(a) for a in launch["dst_addr"][g]] == r["dst"]  # the first segment's order is kept
+    assert sum(int(x) for x in launch["seg_len"]) == sum(int(x) for x in tab["seg_len"])
+    assert (k, m) == (launch["src_addr"].shape[1], launch["dst_addr"].shape[1])
+
+
+def check_plan(sched, bufs, esize, sendbufs=None):
     for step in range(sched.num_steps):
-        plan = la.la_schedule_launch_plan(sched, step, bufs)
-        tab = sched.step_table(step)
-        S = tab["num_segments"]
+        plan = la.la_schedule_launch_plan(sched, step, bufs, sendbufs=sendbufs)
+        launch = la.la_schedule_launch_segments(sched, step, bufs, sendbufs=sendbufs)
+        if sendbufs is None and sched.staging_elems == 0:
+            check_merge(sched, step, bufs, esize, launch)
+        S = launch["count"]
         tile = plan["block"] * plan["unroll"]
         assert plan["block"] in (256, 1024) and plan["unroll"] in (1, 2, 4, 8) and 0 <= plan["cache_policy"] <= 7
         assert plan["unroll"] < 8 or plan["block"] == 1024
-        geo = segment_geometry(tab, bufs, esize)
+        geo = segment_geometry(launch, esize)
         longest = max(max(nvec, 1 if edge and first is None else 0) for nvec, edge, first in geo)
         need, leads = 1, []
         for nvec, edge, first in geo:
@@ -76,10 +104,10 @@ def check_plan(sched, bufs, esize):
 
 @pytest.mark.parametrize("cfg,expect", [
     (((2, 4, 1), "lane", 1 << 16, "float32"), [(256, 1, 6), (256, 1, 7), (256, 1, 4)]),  # small: one workgroup size for all steps
-    (((4, 4, 1), "lane", 1 << 24, "float32"), [(1024, 1, 6), (1024, 1, 7), (256, 1, 4)]),
+    (((4, 4, 1), "lane", 1 << 24, "float32"), [(1024, 8, 6), (1024, 1, 7), (256, 1, 4)]),  # S1 streams 1 GiB of inputs
     (((8, 4, 4), "lane_multiproc", 1 << 22, "float32"), [(1024, 4, 6), (256, 4, 7), (1024, 8, 4)]),
     (((2, 4, 2), "lane_multiproc", 1 << 27, "bfloat16"), [(1024, 8, 3), (1024, 1, 7), (1024, 8, 7)]),
-    (((32, 4, 8), "lane_multiproc", 1 << 20, "float32"), [(1024, 4, 6), (256, 1, 7), (1024, 8, 4)]),
+    (((32, 4, 8), "lane_multiproc", 1 << 20, "float32"), [(1024, 4, 6), (256, 4, 7), (1024, 8, 4)]),  # S2: 32 merged segments of 128 KiB
 ])
 def test_launch_shapes_of_the_benchmark_configurations(cfg, expect):
     topo, algo, n, dtype = cfg
@@ -172,3 +200,33 @@ def test_plan_of_an_out_of_place_schedule_needs_both_buffer_sets():
     in_place = la.la_schedule_build(la.la_topology_create(2, 2, 2), "lane_multiproc", n, "bfloat16")
     with pytest.raises(la.LaError):
         la.la_schedule_launch_plan(in_place, 0, recv, sendbufs=send)
+
+
+def test_pieces_of_a_part_are_launched_as_one_segment():
+    """The inter-node step of config 5 has 1024 table segments (32 parts x 32 pieces of 4 KiB, fan-in
+    and fan-out 32); the pieces of a part read the same 32 buffers back to back and store to the same 32
+    buffers, so the launch has 32 segments of 128 KiB.  With fused all-gathers likewise (fan-out 1024),
+    and the one-launch form is a single segment: every table segment has the same 1024 sources and
+    destinations.  The logical tables are unchanged, and the knob restores one launch segment per table segment."""
+    topo, n = (32, 4, 8), 1 << 20
+    for flags, step, table_segments, launch_segments in ((0, 1, 1024, 32), (la.LA_SCHED_FUSED_GATHER, 1, 1024, 32),
+                                                         (la.LA_SCHED_SINGLE_LAUNCH, 0, 1024, 1), (0, 0, 1024, 1024),
+                                                         (0, 2, 1024, 1024)):
+        sched = la.la_schedule_build(la.la_topology_create(*topo), "lane_multiproc", n, "float32", flags)
+        bufs = fake_buffers(sched.num_buffers, n, 4)
+        assert sched.step_info(step)["num_segments"] == table_segments
+        launch = la.la_schedule_launch_segments(sched, step, bufs)
+        assert launch["count"] == launch_segments, (flags, step, launch["count"])
+        check_merge(sched, step, bufs, 4, launch)
+        try:
+            la.la_tuning_set("merge", 0)
+            assert la.la_schedule_launch_segments(sched, step, bufs)["count"] == table_segments
+        finally:
+            la.la_tuning_set("merge", 1)
+    # buffers that do not follow each other's layout (every rank at its own odd offset) merge all the same:
+    # the condition is on the addresses of consecutive table segments, which move together
+    sched = la.la_schedule_build(la.la_topology_create(3, 2, 2), "lane_multiproc", 100003, "int32")
+    bufs = fake_buffers(sched.num_buffers, 100003, 4, skew=[r % 5 for r in range(12)])
+    for step in range(sched.num_steps):
+        check_merge(sched, step, bufs, 4, la.la_schedule_launch_segments(sched, step, bufs))
+    assert la.la_schedule_launch_segments(sched, 1, bufs)["count"] == 4  # 4 parts x 3 pieces
