@@ -125,6 +125,42 @@ def device_buffers_drawn_on_the_gpu(torch, cfg, P):
     return bufs
 
 
+def launch_units(la, sched):
+    """The launches of one all-reduce as the library makes them: one per step, except that a run of
+    steps which the library fuses without being asked (the ring forms) is ONE launch.  Each unit:
+    dict(first, count, stage_name, fan_in, fan_out, bytes (as executed), table_bytes (as the step
+    tables count them: a fused launch takes a chunk that the same lane has just stored from its
+    registers instead of loading it again))."""
+    info = sched.steps()
+    runs = {}
+    if la.la_tuning_get("fuse") != 0:
+        for r in range(la.la_schedule_fusion_runs(sched)):
+            f = la.la_schedule_fusion_table(sched, r)
+            if f["automatic"] or la.la_tuning_get("fuse") == 1:
+                runs[f["first_step"]] = f
+    units, i = [], 0
+    while i < len(info):
+        if i in runs:
+            f = runs[i]
+            part = info[i:i + f["num_steps"]]
+            names = []
+            for s in part:
+                if s["stage_name"] not in names:
+                    names.append(s["stage_name"])
+            units.append(dict(first=i, count=f["num_steps"], stage_name="+".join(names) + f" (one fused launch of {f['num_steps']} steps)",
+                              fan_in=max(s["fan_in"] for s in part), fan_out=max(s["fan_out"] for s in part),
+                              bytes=f["bytes_read"] + f["bytes_written"],
+                              table_bytes=sum(s["bytes_read"] + s["bytes_written"] for s in part), fused=True))
+            i += f["num_steps"]
+        else:
+            s = info[i]
+            b = s["bytes_read"] + s["bytes_written"]
+            units.append(dict(first=i, count=1, stage_name=s["stage_name"], fan_in=s["fan_in"], fan_out=s["fan_out"], bytes=b,
+                              table_bytes=b, fused=False))
+            i += 1
+    return units
+
+
 def time_schedule(la, torch, sched, bufs, steps, warmup, flush=None, instrumented=INSTRUMENTED, one_call=True):
     """W warm-up all-reduces; K timed ones through la_allreduce_emulated, the entry point an
     application calls (wall clock around the region, synchronised on both sides); then a second pass
@@ -133,12 +169,17 @@ def time_schedule(la, torch, sched, bufs, steps, warmup, flush=None, instrumente
     the stream several microseconds, so the whole-job figure is never taken from the instrumented
     pass.)  With a flush buffer, that buffer (1 GiB) is rewritten before every all-reduce of the
     instrumented pass, and the whole-job time is the median over as many all-reduces issued through the one-call entry
-    point, each after a flush, between two events."""
+    point, each after a flush, between two events.  Returns (ms per all-reduce, ms per launch unit, runs, units)."""
     stream = torch.cuda.current_stream()
     ptrs = la.ptr_array([b.data_ptr() for b in bufs])
-    ns = sched.num_steps
+    units = launch_units(la, sched)
+    fused_before = la.la_tuning_get("fused_launches")
     for _ in range(warmup):
         la.la_allreduce_emulated(sched, ptrs, sched.n, sched.dtype, la.LA_SUM, stream.cuda_stream)
+    if warmup and any(u["fused"] for u in units) and la.la_tuning_get("fused_launches") == fused_before:
+        # the buffers did not allow the fused launch (addresses that disagree modulo 16 bytes): every step is a launch
+        la.la_tuning_set("fuse", 0)
+        units = launch_units(la, sched)
     wall_ms = None
     if one_call:
         torch.cuda.synchronize()
@@ -148,17 +189,18 @@ def time_schedule(la, torch, sched, bufs, steps, warmup, flush=None, instrumente
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) / steps * 1e3
     runs = max(instrumented, 1)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(ns + 1)] for _ in range(runs)]
+    nu = len(units)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(nu + 1)] for _ in range(runs)]
     torch.cuda.synchronize()
     for k in range(runs):
         if flush is not None:
             flush.add_(1.0)
         ev[k][0].record(stream)
-        for s in range(ns):
-            la.la_schedule_run_step(sched, s, ptrs, stream.cuda_stream)
-            ev[k][s + 1].record(stream)
+        for i, u in enumerate(units):
+            la.la_schedule_run_steps(sched, u["first"], u["count"], ptrs, la.LA_SUM, stream.cuda_stream)
+            ev[k][i + 1].record(stream)
     torch.cuda.synchronize()
-    per_step_ms = [statistics.median(ev[k][s].elapsed_time(ev[k][s + 1]) for k in range(runs)) for s in range(ns)]
+    per_unit_ms = [statistics.median(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(runs)) for i in range(nu)]
     if flush is not None:
         # whole all-reduces from a flushed cache, through the one-call entry point: two events around each
         pair = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(runs)]
@@ -169,17 +211,17 @@ def time_schedule(la, torch, sched, bufs, steps, warmup, flush=None, instrumente
             b.record(stream)
         torch.cuda.synchronize()
         wall_ms = statistics.median(a.elapsed_time(b) for a, b in pair)
-    return wall_ms, per_step_ms, runs
+    return wall_ms, per_unit_ms, runs, units
 
 
-def families(info, step_bytes, per_step_ms):
+def families(units, per_unit_ms):
     """Launches of one shape (stage, fan-in, fan-out) are one kernel family."""
     fam = {}
-    for i, s in enumerate(info):
-        key = (s["stage_name"], s["fan_in"], s["fan_out"])
+    for u, ms in zip(units, per_unit_ms):
+        key = (u["stage_name"], u["fan_in"], u["fan_out"])
         f = fam.setdefault(key, {"ms": 0.0, "bytes": 0, "launches": 0})
-        f["ms"] += per_step_ms[i]
-        f["bytes"] += step_bytes[i]
+        f["ms"] += ms
+        f["bytes"] += u["bytes"]
         f["launches"] += 1
     return fam
 
@@ -224,13 +266,17 @@ def measure_config(la, torch, cfg, algo, flags, bufs, steps, warmup, flush):
     topo = la.la_topology_create(N, G, Q)
     sched = la.la_schedule_build(topo, algo, cfg["n"], cfg["dtype"], flags)
     info = sched.steps()
-    step_bytes = [s["bytes_read"] + s["bytes_written"] for s in info]
-    total = sum(step_bytes)
-    wall_ms, per_ms, runs = time_schedule(la, torch, sched, bufs, steps, warmup)
-    cold_wall_ms, cold_ms, _ = time_schedule(la, torch, sched, bufs, 0, 1, flush=flush, one_call=False)
-    fam, fam_cold = families(info, step_bytes, per_ms), families(info, step_bytes, cold_ms)
+    fuse_knob = la.la_tuning_get("fuse")
+    try:
+        wall_ms, per_ms, runs, units = time_schedule(la, torch, sched, bufs, steps, warmup)
+        cold_wall_ms, cold_ms, _, _ = time_schedule(la, torch, sched, bufs, 0, 1, flush=flush, one_call=False)
+    finally:
+        la.la_tuning_set("fuse", fuse_knob)
+    total = sum(u["bytes"] for u in units)              # as executed
+    table_total = sum(u["table_bytes"] for u in units)  # as the step tables count them
+    fam, fam_cold = families(units, per_ms), families(units, cold_ms)
     dom = max(fam, key=lambda k: fam[k]["ms"])
-    return dict(sched=sched, info=info, step_bytes=step_bytes, total=total, wall_ms=wall_ms, per_ms=per_ms,
+    return dict(sched=sched, info=info, units=units, total=total, table_total=table_total, wall_ms=wall_ms, per_ms=per_ms,
                 cold_ms=cold_ms, cold_wall_ms=cold_wall_ms, fam=fam, fam_cold=fam_cold, dom=dom, runs=runs)
 
 
@@ -239,7 +285,8 @@ def side_record(rid, cfg, algo, m, e):
     fam, cold, dom = m["fam"], m["fam_cold"], m["dom"]
     cold_total = m["cold_wall_ms"]
     return {"id": rid, "workload": cfg["name"], "algo": algo, "dtype": DTYPE_TAG[cfg["dtype"]],
-            "launches_per_allreduce": len(m["info"]), "algorithmic_bytes_per_allreduce": m["total"],
+            "steps_per_allreduce": len(m["info"]), "launches_per_allreduce": len(m["units"]),
+            "algorithmic_bytes_per_allreduce": m["total"], "step_table_bytes_per_allreduce": m["table_total"],
             "ms_per_allreduce": round(m["wall_ms"], 5), "GBps": round(gbps(m["total"], m["wall_ms"]), 1),
             "frac_of_peak": round(gbps(m["total"], m["wall_ms"]) / HBM_PEAK_GBS, 4),
             "ms_per_allreduce_cold": round(cold_total, 5), "GBps_cold": round(gbps(m["total"], cold_total), 1),
@@ -420,7 +467,8 @@ def main():
         "dtype": DTYPE_TAG[cfg["dtype"]],
         "data": "synthetic",
         "config": {"workload": cfg["name"], "config_id": args.config, "algo": algo, "schedule_flags": args.flags,
-                   "virtual_ranks": N * G * Q, "buffers": P, "elements_per_rank": n, "launches_per_allreduce": len(info),
+                   "virtual_ranks": N * G * Q, "buffers": P, "elements_per_rank": n, "steps_per_allreduce": len(info),
+                   "launches_per_allreduce": len(m["units"]),
                    "unroll": la.la_tuning_get("unroll"), "cache_policy": la.la_tuning_get("cache_policy"),
                    "skew_bytes": args.skew, "flush_cache_between_allreduces": bool(args.flush_cache),
                    "instrumented_allreduces": m["runs"]},
@@ -428,6 +476,7 @@ def main():
         "pct_of_hbm_peak_cold": round(gbps(total_bytes, m["cold_wall_ms"]) / HBM_PEAK_GBS * 100, 2),
         "ms_per_step_cold": round(m["cold_wall_ms"], 5),
         "algorithmic_bytes_per_allreduce": total_bytes,
+        "step_table_bytes_per_allreduce": m["table_total"],
         "allreduce_bytes_per_s_per_rank": round(n * e / (ms * 1e-3), 1),
         "bus_bandwidth_bytes_per_s": round(n * e / (ms * 1e-3) * 2 * (P - 1) / P, 1),
         "schedule_report": [{"step": i, "stage": s["stage_name"], "segments": s["num_segments"],
@@ -451,7 +500,7 @@ def main():
         for name, bit in (("fused_gather_variant", la.LA_SCHED_FUSED_GATHER), ("single_launch_variant", la.LA_SCHED_SINGLE_LAUNCH)):
             v = la.la_schedule_build(topo, algo, n, cfg["dtype"], args.flags | bit)
             vbytes = sum(s["bytes_read"] + s["bytes_written"] for s in v.steps())
-            vms, _, _ = time_schedule(la, torch, v, bufs, max(3, args.steps // 2), 1, instrumented=1)
+            vms, _, _, _ = time_schedule(la, torch, v, bufs, max(3, args.steps // 2), 1, instrumented=1)
             out[name] = {"ms_per_allreduce": round(vms, 5), "launches": v.num_steps, "algorithmic_bytes": vbytes,
                          "GBps": round(gbps(vbytes, vms), 1), "allreduce_bytes_per_s_per_rank": round(n * e / (vms * 1e-3), 1)}
             del v

@@ -235,8 +235,9 @@ la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_
  * A schedule remembers the last 8 buffer sets it was run with (1 if it owns a staging area) and
  * keeps their resolved tables on the device; a call with a set it does not remember uploads
  * tables with a synchronous copy, after waiting for the work of the set it forgets in exchange.
- * Schedules of 16 or more launches (the ring forms) are recorded once per buffer set into a HIP
- * graph of kernel nodes and replayed.  Calls on one schedule are serialised by the library;
+ * Runs of steps with at most two sources and destinations per segment (the ring forms) go out as
+ * one launch each (see la_schedule_fusion_runs); a schedule of 16 or more launches without such a
+ * run is recorded once per buffer set into a HIP graph of kernel nodes and replayed.  Calls on one schedule are serialised by the library;
  * different schedules can be used from different host threads at the same time.
  * int32 wraps; fp32 adds are IEEE, in the fixed operand order of the tables; bf16 operands are
  * widened to fp32, summed in fp32 and rounded to nearest-even once per reduce step.
@@ -251,9 +252,14 @@ la_status_t la_allreduce_emulated_out_of_place(const la_schedule_t* sched, const
                                                void* const* recvbufs, size_t n, la_dtype_t dtype, la_op_t op,
                                                void* hip_stream);
 
-/* Enqueue a single step of the schedule (same conventions): for per-step timing and for tests
- * that look at intermediate states. */
+/* Enqueue a single step of the schedule (same conventions, LA_SUM): for per-step timing and for
+ * tests that look at intermediate states. */
 la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* const* bufs, void* hip_stream);
+/* Enqueue steps [first_step, first_step + num_steps) with the given operation, launched as
+ * la_allreduce_emulated launches them (a run of steps that lies inside the range goes out as one
+ * fused launch if the "fuse" knob selects it).  Not for out-of-place schedules. */
+la_status_t la_schedule_run_steps(const la_schedule_t* sched, int first_step, int num_steps, void* const* bufs,
+                                  la_op_t op, void* hip_stream);
 
 /* Host only, for tests and for reading the launch heuristics: how one step would be launched for
  * buffers at the given addresses.  The addresses are never dereferenced and no device call is
@@ -273,6 +279,43 @@ typedef struct la_launch_plan {
 } la_launch_plan_t;
 la_status_t la_schedule_launch_plan(const la_schedule_t* sched, int step, const void* const* bufs,
                                     const void* const* sendbufs, const void* staging, la_launch_plan_t* out);
+
+/*
+ * Column analysis of a schedule (host only).  Algorithms 1 and 2 exchange chunks that sit at the same
+ * element offset in every rank's buffer, so element i of a buffer only ever meets element i of other
+ * buffers.  Cutting the element axis wherever a segment of a step starts or ends gives column ranges
+ * ("chains") that never exchange data; a chain's operations are the (step, segment) pairs that cover
+ * it, in step order (Algorithm 1 over P ranks: P chains, one per chunk, of 2(P - 1) operations).  A
+ * "run" is a maximal sequence of two or more consecutive steps whose segments have at most two
+ * sources and two destinations each (the two loops of Algorithm 1, the ring form of the inter-node
+ * stage, recursive halving and doubling, point-to-point copies).  la_allreduce_emulated executes a
+ * run as ONE launch in which a wave takes its piece of a chain through all the run's steps (same
+ * sums in the same order, every store of every step made, no synchronisation between workgroups),
+ * instead of one launch per step; which runs, see the "fuse" knob of la_tuning_set.  Steps outside
+ * runs (the fan-in and fan-out steps of Algorithm 2) keep their own launches.
+ *   la_schedule_fusion_runs   number of runs (0: none; -1: NULL schedule or out of memory)
+ *   la_schedule_fusion_info   first step and number of steps of a run, its chains and operations, and
+ *                             whether it is fused without being asked (four steps or more, and the
+ *                             longest chain has fewer than 8 operations per step); bytes_read and
+ *                             bytes_written are what the fused launch moves with the current "forward"
+ *                             setting: every destination is stored, a source is loaded unless it is
+ *                             taken from registers (the steps' own figures, la_schedule_step_info,
+ *                             count every source); any out pointer may be NULL
+ *   la_schedule_fusion_table  [host arrays sized from la_schedule_fusion_info; any may be NULL]
+ *     chain_lo[C], chain_len[C]    the chain's elements; chain_first_op[C + 1] prefix sums into the ops
+ *     op_step[ops], op_segment[ops]   the operation: that segment of that step, restricted to the chain
+ *     op_prefetch_source[ops]      a source no earlier operation of the chain has written (it may be
+ *                                  loaded ahead of time), or -1
+ *     op_forward_source[ops]       a source that is exactly what the previous operation of the chain
+ *                                  stored (taken from registers, see the "forward" knob), or -1
+ */
+int la_schedule_fusion_runs(const la_schedule_t* sched);
+la_status_t la_schedule_fusion_info(const la_schedule_t* sched, int run, int* first_step, int* num_steps,
+                                    uint64_t* num_chains, uint64_t* num_ops, int* automatic, size_t* bytes_read,
+                                    size_t* bytes_written);
+la_status_t la_schedule_fusion_table(const la_schedule_t* sched, int run, uint64_t* chain_lo, uint64_t* chain_len,
+                                     uint64_t* chain_first_op, uint32_t* op_step, uint32_t* op_segment,
+                                     int32_t* op_prefetch_source, int32_t* op_forward_source);
 
 /* Host only, like la_schedule_launch_plan: the segments of one step as they are launched.  A table
  * segment whose source ranges start where those of the segment before it end, and whose destination
@@ -340,6 +383,16 @@ const char* la_last_error(void);
  *   "block"       lanes per workgroup: 256, 1024; 0 = automatic
  *   "merge"       1 (default): table-adjacent segments that continue each other are launched as one
  *                 (see la_schedule_launch_segments); 0: every table segment is a launch segment
+ *   "fuse"        which runs of steps (see la_schedule_fusion_runs) la_allreduce_emulated executes as
+ *                 one launch each: -1 (default): those of four steps or more whose longest chain has
+ *                 fewer than 8 operations per step (the ring forms; recursive halving on up to 32
+ *                 ranks); 1: every run; 0: none.
+ *                 A run is fused only if all buffers share their address modulo 16 bytes.
+ *   "forward"     fused launches only.  1 (default): a source that is exactly what the previous
+ *                 operation of its chain stored (the chunk a rank has just received from its
+ *                 predecessor) is taken from the registers of the lane that stored it; the store to the
+ *                 rank buffer is made all the same.  0: every source is loaded from memory
+ *                 (la_tuning_get("fused_launches") counts the fused launches made so far; read-only)
  *   "graph"       1: la_allreduce_emulated replays the schedule as one HIP graph of kernel nodes,
  *                 0: it launches step by step, -1 (default): graph for schedules of 16+ launches
  * la_tuning_set returns LA_ERR_INVALID_ARG for an unknown key or value; la_tuning_get returns

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     LA_STAGE_RECURSIVE_DOUBLING, LA_STAGE_RING_AG,
     LA_STAGE_RING_RS, LA_STAGE_S1, LA_STAGE_S2, LA_STAGE_S2_RING_AG, LA_STAGE_S2_RING_RS, LA_STAGE_S2A, LA_STAGE_S2B, LA_STAGE_S3, LA_STEP_COPY,
     LA_STEP_REDUCE, LA_SUM, LIB_PATH, LaError, Schedule, Topology, la_allreduce_emulated, la_allreduce_emulated_out_of_place, la_last_error,
-    la_reduce_segments, la_reduce_segments_static, la_schedule_build, la_schedule_launch_plan, la_schedule_launch_segments, la_schedule_run_step, la_status_string, la_topology_create,
+    la_reduce_segments, la_reduce_segments_static, la_schedule_build, la_schedule_fusion_runs, la_schedule_fusion_table, la_schedule_launch_plan, la_schedule_launch_segments, la_schedule_run_step, la_schedule_run_steps, la_status_string, la_topology_create,
     la_tuning_get, la_tuning_set, lib, ptr_array,
 )
 

@@ -43,9 +43,10 @@ EXPORTS = (
     "la_schedule_build", "la_schedule_build_ex", "la_schedule_destroy", "la_schedule_num_steps",
     "la_schedule_num_buffers", "la_schedule_owned_ranges", "la_schedule_step_group",
     "la_schedule_staging_elems", "la_schedule_step_info", "la_schedule_step_table",
-    "la_allreduce_emulated", "la_allreduce_emulated_out_of_place", "la_schedule_run_step", "la_reduce_segments",
+    "la_allreduce_emulated", "la_allreduce_emulated_out_of_place", "la_schedule_run_step", "la_schedule_run_steps", "la_reduce_segments",
     "la_reduce_segments_static",
-    "la_schedule_launch_plan", "la_schedule_launch_segments",
+    "la_schedule_launch_plan", "la_schedule_launch_segments", "la_schedule_fusion_runs", "la_schedule_fusion_info",
+    "la_schedule_fusion_table",
     "la_status_string", "la_last_error", "la_tuning_set", "la_tuning_get",
 )
 
@@ -98,6 +99,11 @@ def lib() -> ctypes.CDLL:
     L.la_schedule_run_step.argtypes = [vp, i32, pp(vp), vp]
     L.la_schedule_launch_plan.argtypes = [vp, i32, pp(vp), pp(vp), vp, pp(LaunchPlan)]
     L.la_schedule_launch_segments.argtypes = [vp, i32, pp(vp), pp(vp), vp, sz, pp(sz), vp, vp, vp]
+    L.la_schedule_fusion_runs.argtypes = [vp]
+    L.la_schedule_fusion_info.argtypes = [vp, i32, pp(i32), pp(i32), pp(ctypes.c_uint64), pp(ctypes.c_uint64), pp(i32),
+                                          pp(sz), pp(sz)]
+    L.la_schedule_run_steps.argtypes = [vp, i32, i32, pp(vp), i32, vp]
+    L.la_schedule_fusion_table.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     L.la_reduce_segments.argtypes = [vp, pp(vp), i32, pp(sz), sz, sz, i32, i32, vp]
     L.la_reduce_segments_static.argtypes = L.la_reduce_segments.argtypes
     L.la_status_string.argtypes = [i32]
@@ -274,6 +280,12 @@ def la_schedule_run_step(sched: Schedule, step: int, bufs: Sequence[int], stream
            "la_schedule_run_step")
 
 
+def la_schedule_run_steps(sched: Schedule, first_step: int, num_steps: int, bufs: Sequence[int], op: int = LA_SUM,
+                          stream: int = 0) -> None:
+    _check(lib().la_schedule_run_steps(sched.handle, int(first_step), int(num_steps), _ptr_array(bufs), int(op),
+                                       ctypes.c_void_p(stream)), "la_schedule_run_steps")
+
+
 def la_schedule_launch_plan(sched: Schedule, step: int, bufs: Sequence[int], sendbufs: Optional[Sequence[int]] = None,
                             staging: int = 0) -> dict:
     """Host only: how `step` would be launched for buffers at these addresses (never dereferenced)."""
@@ -299,6 +311,33 @@ def la_schedule_launch_segments(sched: Schedule, step: int, bufs: Sequence[int],
                                              src.ctypes.data, dst.ctypes.data), "la_schedule_launch_segments")
     c = int(count.value)
     return dict(count=c, seg_len=seg_len[:c], src_addr=src[:c], dst_addr=dst[:c])
+
+
+def la_schedule_fusion_runs(sched: Schedule) -> int:
+    """Host only: how many runs of steps the schedule has that can execute as one launch each."""
+    r = int(lib().la_schedule_fusion_runs(sched.handle))
+    if r < 0:
+        raise LaError(LA_ERR_OUT_OF_MEMORY, "la_schedule_fusion_runs", la_last_error())
+    return r
+
+
+def la_schedule_fusion_table(sched: Schedule, run: int) -> dict:
+    """Host only: the chains of one run and their operations."""
+    first, steps, auto = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    C, O = ctypes.c_uint64(), ctypes.c_uint64()
+    rd, wr = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().la_schedule_fusion_info(sched.handle, int(run), ctypes.byref(first), ctypes.byref(steps), ctypes.byref(C),
+                                         ctypes.byref(O), ctypes.byref(auto), ctypes.byref(rd), ctypes.byref(wr)),
+           "la_schedule_fusion_info")
+    c, o = int(C.value), int(O.value)
+    lo, ln, first_op = np.zeros(c, np.uint64), np.zeros(c, np.uint64), np.zeros(c + 1, np.uint64)
+    step, seg, pf, fw = np.zeros(o, np.uint32), np.zeros(o, np.uint32), np.zeros(o, np.int32), np.zeros(o, np.int32)
+    _check(lib().la_schedule_fusion_table(sched.handle, int(run), lo.ctypes.data, ln.ctypes.data, first_op.ctypes.data,
+                                          step.ctypes.data, seg.ctypes.data, pf.ctypes.data, fw.ctypes.data),
+           "la_schedule_fusion_table")
+    return dict(first_step=first.value, num_steps=steps.value, automatic=bool(auto.value), bytes_read=rd.value,
+                bytes_written=wr.value, chain_lo=lo, chain_len=ln,
+                chain_first_op=first_op, op_step=step, op_segment=seg, op_prefetch_source=pf, op_forward_source=fw)
 
 
 def la_reduce_segments(dst: int, srcs: Sequence[int], seg_offsets: Sequence[int], seg_len: int, dtype,

@@ -24,6 +24,8 @@ FLAGS = [
 # family; the largest units come first so that the pool stays busy to the end
 UNITS = [("kernels.hip", f"kernels_dtype{d}_shape{f}.o", [f"-DLA_KERNEL_DTYPE={d}", f"-DLA_KERNEL_SHAPE={f}"])
          for f in (2, 0, 1) for d in (2, 3, 4, 1, 0)] + [
+    ("fused.hip", f"fused_dtype{d}.o", [f"-DLA_KERNEL_DTYPE={d}"]) for d in (2, 3, 4, 1, 0)] + [
+    ("fusion.cpp", "fusion.o", []),
     ("static_scratch.hip", "static_scratch.o", []), ("dispatch.cpp", "dispatch.o", []), ("runtime.cpp", "runtime.o", []), ("schedule.cpp", "schedule.o", [])]
 
 

@@ -16,6 +16,12 @@ LA_DECLARE_FAMILIES(3)
 LA_DECLARE_FAMILIES(4)
 #undef LA_DECLARE_FAMILIES
 
+la_status_t launch_fused_0(const FusedTable&, int unroll, void* stream);
+la_status_t launch_fused_1(const FusedTable&, int unroll, void* stream);
+la_status_t launch_fused_2(const FusedTable&, int unroll, void* stream);
+la_status_t launch_fused_3(const FusedTable&, int unroll, void* stream);
+la_status_t launch_fused_4(const FusedTable&, int unroll, void* stream);
+
 namespace {
 using FamilyFn = la_status_t (*)(const StepTable&, const Tuning&, uint32_t, void*);
 #define LA_FAMILY_ROW(d) {launch_family_##d##_0, launch_family_##d##_1, launch_family_##d##_2}
@@ -68,6 +74,22 @@ la_status_t launch_step(const StepTable& t, la_dtype_t dtype, const Tuning& tune
     if (st != LA_OK) return st;
     const uint64_t blocks = (uint64_t)t.edge_blocks + (uint64_t)t.num_segments * t.tiles_per_seg;
     return kFamilies[(int)dtype][family_of(tune)](t, tune, (uint32_t)blocks, hip_stream);
+}
+
+// One launch for the whole schedule (fused.hip, one translation unit per element type).
+la_status_t launch_fused(const FusedTable& t, la_dtype_t dtype, int unroll, void* hip_stream)
+{
+    if (t.workgroups == 0) return LA_OK;
+    if (!known_op((int)t.op_code)) return fail(LA_ERR_UNSUPPORTED, "unknown operation %u", t.op_code);
+    if (t.workgroups > 0x7fffffffu) return fail(LA_ERR_INVALID_ARG, "fused launch needs %u workgroups", t.workgroups);
+    switch (dtype) {
+    case LA_I32: return launch_fused_0(t, unroll, hip_stream);
+    case LA_F32: return launch_fused_1(t, unroll, hip_stream);
+    case LA_BF16: return launch_fused_2(t, unroll, hip_stream);
+    case LA_F16: return launch_fused_3(t, unroll, hip_stream);
+    case LA_F64: return launch_fused_4(t, unroll, hip_stream);
+    }
+    return fail(LA_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
 }
 
 } // namespace la

@@ -128,6 +128,82 @@ struct StepTable {
     uint32_t edge_blocks = 0; // leading workgroups that do the elements outside the whole vectors (0: there are none)
 };
 
+// ---- column-fused execution of runs of steps in one launch ---------------------------------------
+// Every step of the schedules here is element-wise at one element offset: all operands of a
+// segment start at the same offset of their buffers.  Element i of any buffer therefore only ever
+// meets element i of other buffers, and the element axis can be cut, at every offset where some
+// segment of some step starts or ends, into column ranges that never exchange data.  A "chain" is
+// one column range with the ordered list of (step, segment) pairs that cover it; chains are
+// independent of each other, so one wave can run all steps of its piece of a chain, in step order,
+// without waiting for any other wave: the launches of a run of steps (2(P - 1) for Algorithm 1)
+// collapse into one, and every store of every step is still performed.  A run is a maximal sequence
+// of consecutive steps whose segments have at most two sources and two destinations (the ring forms,
+// recursive halving and doubling, point-to-point copies); the fan-in and fan-out steps of Algorithm 2
+// keep their own launches, whose large tiles suit them better.
+struct FusionRun {
+    int first_step = 0, num_steps = 0;
+    uint64_t max_chain_ops = 0;                // operations of the longest chain
+    // Fused without being asked?  A wave executes its chain's operations one after the other, about
+    // half a microsecond each when an operand has to come back from the L2, while a launch costs
+    // about 4 us whatever it carries: worth it when the longest chain has fewer than 8 operations per
+    // step saved (Algorithm 1: one per step; recursive halving over 16 ranks: 30 in 8 steps; recursive
+    // doubling over 16 ranks, 32 in 4 steps, measured 17 % slower fused at small sizes).
+    bool automatic() const { return num_steps >= 4 && max_chain_ops < 8 * (uint64_t)num_steps; }
+    std::vector<uint64_t> chain_lo, chain_len; // [C] column range in elements
+    std::vector<uint64_t> chain_first;         // [C + 1] first op of each chain (prefix sums)
+    std::vector<uint32_t> op_step, op_seg;     // [ops] chain-major, in step order (absolute step index)
+    // a source of the op that no earlier op of the chain has written (an original input of the run),
+    // which the kernel may load ahead of time; -1: none
+    std::vector<int32_t> op_prefetch;
+    std::vector<uint32_t> op_dep_mask;         // bit t: source t was written by an earlier op of the chain
+    // a source that is exactly what the previous op of the chain stored (the message a rank has just
+    // received and now passes on, or adds to): the lane that stored it still holds it; -1: none
+    std::vector<int32_t> op_forward;
+};
+struct FusionPlan {
+    bool analysed = false;
+    std::vector<FusionRun> runs;
+};
+constexpr int FUSED_MAX_FAN = 2;      // sources, and destinations, of a segment that can run fused
+
+struct ChainInfo { // device record of one chain
+    uint64_t first_op;
+    uint64_t nvec;     // whole 16-byte vectors of the column range
+    uint32_t num_ops;
+    uint32_t head;     // elements before the first whole vector
+    uint32_t tail;     // elements after the last one
+    uint32_t pad;
+};
+
+// Device record of one operation of a chain: one 64-byte line that holds everything the operation
+// needs, so that a wave fetches it with one load.
+struct FusedOp {
+    uint32_t dep_mask;  // bit t: source t was written by an earlier op of the chain
+    uint32_t live;      // 1: an operation; 0: padding behind a chain's last operation (chains are padded to
+                        // a multiple of eight records, so that the kernel's loop needs no test per operation)
+    uint16_t k, m;
+    int16_t prefetch;   // a source that is an original input of the run (loadable ahead), or -1
+    int16_t forward;    // a source that is what the previous op of the chain stored (still in registers), or -1
+    // byte address of the chain's first element in each operand: k sources, then m destinations
+    uint64_t addr[2 * FUSED_MAX_FAN];
+    uint64_t pad1[2];
+};
+static_assert(sizeof(FusedOp) == 64, "one cache line per operation");
+
+constexpr uint32_t FUSED_LANES = 64; // one wave per workgroup: no barrier anywhere in the kernel
+constexpr uint32_t FUSED_CHAIN_PAD = 8;            // records per chain: a multiple of this
+constexpr uint32_t FUSED_EDGE_TILE = 0xffffffffu;  // wg_tile of the workgroup that does a chain's elements
+                                                   // outside its whole 16-byte vectors
+
+struct FusedTable { // passed to the kernel by value
+    const ChainInfo* chain;
+    const FusedOp* op;
+    const uint32_t* wg_chain; // [workgroups] chain of each workgroup
+    const uint32_t* wg_tile;  // [workgroups] which tile of FUSED_LANES * unroll vectors of the chain
+    uint32_t workgroups;
+    uint32_t op_code = 0;     // la_op_t
+};
+
 // Launch shape of one step.  In the process-wide setting 0 (unroll, block) and -1 (cache_policy)
 // mean "choose per step from its fan-in, fan-out and segment length".
 struct Tuning {
@@ -135,9 +211,11 @@ struct Tuning {
     int cache_policy = -1; // 0..7, see Policy<> in kernels.hip
     int block = 0;        // lanes per workgroup: 256, 1024
     int merge = 1;        // launch table-adjacent segments that continue each other as one
+    int forward = 1;      // fused launch: take what the previous op of a chain stored from registers
     bool operator==(const Tuning& o) const
     {
-        return unroll == o.unroll && block == o.block && cache_policy == o.cache_policy && merge == o.merge;
+        return unroll == o.unroll && block == o.block && cache_policy == o.cache_policy && merge == o.merge &&
+               forward == o.forward;
     }
 };
 Tuning current_tuning();
@@ -195,12 +273,17 @@ struct la_schedule {
     std::vector<std::vector<la::Part>> owned; // per buffer: ranges it holds fully reduced between the halves
     // device-side state, created by the first run
     mutable std::mutex mu;
+    mutable la::FusionPlan fusion; // built on first use (under mu)
     // the buffer sets the schedule has been run on lately, most recent first (a few, so that a
     // caller that alternates between buffer sets does not re-upload tables on every call)
     mutable std::vector<la_binding*> bound;
 };
 
 namespace la {
+// fusion.cpp: fills s.fusion (once) with the runs of steps that can execute column-fused
+void analyse_fusion(const la_schedule& s);
+// fused.hip
+la_status_t launch_fused(const FusedTable& t, la_dtype_t dtype, int unroll, void* hip_stream);
 la_status_t generate_steps(la_schedule& s);
 la_status_t validate_hazards(const la_schedule& s);
 void release_binding(la_binding* b);

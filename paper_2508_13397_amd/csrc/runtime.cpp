@@ -25,7 +25,12 @@ static std::atomic<int> g_unroll{0};
 static std::atomic<int> g_cache_policy{-1};
 static std::atomic<int> g_block{0};
 static std::atomic<int> g_merge{1};
-static std::atomic<int> g_graph{-1}; // -1: graphs for schedules of GRAPH_MIN_STEPS launches or more
+static std::atomic<int> g_forward{1};
+static std::atomic<int> g_graph{-1};
+static std::atomic<int> g_fused_launches{0}; // column-fused launches made so far (read-only knob, for tests)
+// -1: fuse the runs that FusionRun::automatic() selects (the ring forms, recursive halving on few ranks);
+// 1: every run of two steps or more; 0: never
+static std::atomic<int> g_fuse{-1}; // -1: graphs for schedules of GRAPH_MIN_STEPS launches or more
 // Measured: a graph launch costs the host about 15 us whatever it holds, a stream launch 2.5 to 3 us;
 // on the GPU a kernel node and a stream launch take the same time.  Below 16 launches the stream wins.
 constexpr int GRAPH_MIN_STEPS = 16;
@@ -37,6 +42,7 @@ Tuning current_tuning()
     t.cache_policy = g_cache_policy.load();
     t.block = g_block.load();
     t.merge = g_merge.load();
+    t.forward = g_forward.load();
     return t;
 }
 
@@ -203,6 +209,14 @@ struct la_binding {
     hipGraphExec_t graph_exec = nullptr;
     uint32_t graph_op = 0;       // the operation recorded in the graph's kernel arguments
     bool graph_failed = false;
+    // the runs of steps that execute as one column-fused launch each (fused.hip), built on first use
+    struct FusedRun {
+        void* tables = nullptr;
+        FusedTable table;
+        int unroll = 0;
+        bool ready = false, impossible = false;
+    };
+    std::vector<FusedRun> fused; // one per run of the schedule's fusion plan
 };
 
 namespace la {
@@ -223,6 +237,8 @@ void release_binding(la_binding* b)
     drop_graph(b);
     if (b->capture_stream) (void)hipStreamDestroy(b->capture_stream);
     if (b->tables) (void)hipFree(b->tables);
+    for (la_binding::FusedRun& r : b->fused)
+        if (r.tables) (void)hipFree(r.tables);
     if (b->staging) (void)hipFree(b->staging);
     if (b->last_use) (void)hipEventDestroy(b->last_use);
     delete b;
@@ -527,6 +543,9 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     b->step = std::move(ht.view);
     b->bufs = key;
     drop_graph(b); // recorded launches point at the old tables
+    for (la_binding::FusedRun& r : b->fused)
+        if (r.tables) (void)hipFree(r.tables);
+    b->fused.clear();
     b->requested = tune;
     b->shape = std::move(shapes);
     b->used = false;
@@ -568,6 +587,107 @@ la_status_t capture_graph(const la_schedule_t* sched, la_binding* b, uint32_t op
     return LA_OK;
 }
 
+// Device tables of one column-fused run for the binding's addresses.  Sets `impossible` when the
+// addresses do not allow it (then its steps are launched one by one).
+la_status_t build_fused(const la_schedule& s, la_binding* b, size_t run, const std::vector<uint64_t>& addr)
+{
+    const FusionRun& f = s.fusion.runs[run];
+    la_binding::FusedRun& out = b->fused[run];
+    out.impossible = true;
+    const size_t e = dtype_size(s.dtype);
+    for (size_t i = 0; i < addr.size(); ++i)
+        if (i != (size_t)s.nbuf && ((addr[i] ^ addr[0]) & 15u) != 0) return LA_OK; // no common 16-byte phase
+    const size_t C = f.chain_lo.size();
+    const uint64_t vec = 16 / e;
+    std::vector<ChainInfo> chain(C);
+    uint64_t O = 0; // records, every chain padded to a multiple of FUSED_CHAIN_PAD
+    for (size_t c = 0; c < C; ++c) {
+        const uint64_t first = (addr[0] + f.chain_lo[c] * e) & 15u;
+        uint64_t head = ((16 - first) & 15u) / e;
+        if (head > f.chain_len[c]) head = f.chain_len[c];
+        chain[c].first_op = O;
+        chain[c].num_ops = (uint32_t)align_up(f.chain_first[c + 1] - f.chain_first[c], FUSED_CHAIN_PAD);
+        chain[c].head = (uint32_t)head;
+        chain[c].nvec = (f.chain_len[c] - head) / vec;
+        chain[c].tail = (uint32_t)((f.chain_len[c] - head) % vec);
+        chain[c].pad = 0;
+        O += chain[c].num_ops;
+    }
+    // One vector per lane (a wave takes 1 KiB of its chain through all operations), unless the
+    // "unroll" knob asks for 2 or 4: more, smaller chains in flight did better at every size measured
+    // (16 ranks x 64 MiB: 467 / 489 / 517 us with 1 / 2 / 4 vectors; 1024 ranks x 4 MiB: 2927 / 2957 / 3331).
+    // One more workgroup per chain that has elements outside its whole vectors.
+    auto workgroups_for = [&](uint64_t unroll) {
+        uint64_t w = 0;
+        for (size_t c = 0; c < C; ++c) w += (chain[c].nvec + FUSED_LANES * unroll - 1) / (FUSED_LANES * unroll);
+        return w;
+    };
+    uint64_t unroll = 1;
+    if (b->requested.unroll == 2 || b->requested.unroll == 4) unroll = (uint64_t)b->requested.unroll;
+    uint64_t W = workgroups_for(unroll);
+    for (size_t c = 0; c < C; ++c) W += chain[c].head + chain[c].tail > 0 ? 1 : 0;
+    if (W > 0x7fffffffull || C > 0xffffffffull) return LA_OK;
+    const uint64_t chain_at = 0;
+    const uint64_t op_at = align_up(chain_at + C * sizeof(ChainInfo), 256);
+    const uint64_t wgc_at = align_up(op_at + O * sizeof(FusedOp), 256);
+    const uint64_t wgt_at = align_up(wgc_at + W * sizeof(uint32_t), 256);
+    const uint64_t total = align_up(wgt_at + W * sizeof(uint32_t), 256);
+    std::vector<unsigned char> blob(total, 0); // padding records are all zeros
+    std::copy(chain.begin(), chain.end(), reinterpret_cast<ChainInfo*>(blob.data() + chain_at));
+    FusedOp* op = reinterpret_cast<FusedOp*>(blob.data() + op_at);
+    for (size_t c = 0; c < C; ++c) {
+        FusedOp* to_op = op + chain[c].first_op;
+        for (uint64_t o = f.chain_first[c]; o < f.chain_first[c + 1]; ++o, ++to_op) {
+            const Step& p = s.steps[f.op_step[o]];
+            const size_t g = f.op_seg[o];
+            to_op->dep_mask = f.op_dep_mask[o];
+            to_op->live = 1;
+            to_op->k = (uint16_t)p.k;
+            to_op->m = (uint16_t)p.m;
+            to_op->prefetch = (int16_t)f.op_prefetch[o];
+            to_op->forward = b->requested.forward ? (int16_t)f.op_forward[o] : (int16_t)-1;
+            // a source that comes from registers is not also requested ahead of time
+            if (to_op->forward >= 0 && to_op->forward == to_op->prefetch) to_op->prefetch = -1;
+            // the chain's first element in every operand (all operands of a segment share its offset)
+            uint64_t* to = to_op->addr;
+            for (int t = 0; t < p.k; ++t) *to++ = addr[p.src[g * p.k + t].buf] + f.chain_lo[c] * e;
+            for (int d = 0; d < p.m; ++d) *to++ = addr[p.dst[g * p.m + d].buf] + f.chain_lo[c] * e;
+        }
+    }
+    uint32_t* wgc = reinterpret_cast<uint32_t*>(blob.data() + wgc_at);
+    uint32_t* wgt = reinterpret_cast<uint32_t*>(blob.data() + wgt_at);
+    uint64_t w = 0;
+    for (size_t c = 0; c < C; ++c) {
+        const uint64_t tiles = (chain[c].nvec + FUSED_LANES * unroll - 1) / (FUSED_LANES * unroll);
+        for (uint64_t t = 0; t < tiles; ++t, ++w) {
+            wgc[w] = (uint32_t)c;
+            wgt[w] = (uint32_t)t;
+        }
+    }
+    for (size_t c = 0; c < C; ++c)
+        if (chain[c].head + chain[c].tail > 0) {
+            wgc[w] = (uint32_t)c;
+            wgt[w++] = FUSED_EDGE_TILE;
+        }
+    std::lock_guard<std::mutex> device_lock(g_device_mu);
+    if (hipMalloc(&out.tables, total) != hipSuccess) {
+        out.tables = nullptr;
+        (void)hipGetLastError();
+        return LA_OK; // no room for the fused tables: launch step by step
+    }
+    LA_HIP(hipMemcpy(out.tables, blob.data(), total, hipMemcpyHostToDevice));
+    const uint64_t base = reinterpret_cast<uint64_t>(out.tables);
+    out.table.chain = reinterpret_cast<const ChainInfo*>(base + chain_at);
+    out.table.op = reinterpret_cast<const FusedOp*>(base + op_at);
+    out.table.wg_chain = reinterpret_cast<const uint32_t*>(base + wgc_at);
+    out.table.wg_tile = reinterpret_cast<const uint32_t*>(base + wgt_at);
+    out.table.workgroups = (uint32_t)W;
+    out.unroll = (int)unroll;
+    out.ready = true;
+    out.impossible = false;
+    return LA_OK;
+}
+
 la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void* const* sendbufs, int first,
                       int last, uint32_t op, void* hip_stream)
 {
@@ -583,8 +703,37 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void*
     const int mode = g_graph.load();
     const bool whole = first == 0 && last == (int)sched->steps.size();
     const bool want_graph = whole && last > 0 && (mode == 1 || (mode < 0 && last >= GRAPH_MIN_STEPS));
+    // which runs of steps go out as one column-fused launch each
+    const int fuse = g_fuse.load();
+    std::vector<int> run_at; // per step: the fused run that starts there, or -1
+    bool any_fused = false;
+    if (fuse != 0 && last - first >= 2) {
+        try {
+            analyse_fusion(*sched);
+            const std::vector<FusionRun>& runs = sched->fusion.runs;
+            if (b->fused.size() != runs.size()) b->fused.resize(runs.size());
+            run_at.assign(sched->steps.size(), -1);
+            for (size_t r = 0; r < runs.size(); ++r) {
+                const FusionRun& f = runs[r];
+                if (f.first_step < first || f.first_step + f.num_steps > last) continue;
+                if (fuse < 0 && !f.automatic()) continue;
+                if (!b->fused[r].ready && !b->fused[r].impossible) {
+                    st = build_fused(*sched, b, r, addr);
+                    if (st != LA_OK) return st;
+                }
+                if (b->fused[r].ready) {
+                    run_at[f.first_step] = (int)r;
+                    any_fused = true;
+                }
+            }
+        } catch (const std::bad_alloc&) {
+            sched->fusion = FusionPlan();
+            run_at.clear();
+            any_fused = false;
+        }
+    }
     bool launched = false;
-    if (want_graph && !b->graph_failed) {
+    if (!any_fused && want_graph && !b->graph_failed) {
         if (b->graph_exec && b->graph_op != op) drop_graph(b);
         if (!b->graph_exec && capture_graph(sched, b, op) != LA_OK) b->graph_failed = true;
         if (b->graph_exec) {
@@ -598,11 +747,22 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void*
         }
     }
     if (!launched) {
-        for (int i = first; i < last; ++i) {
+        for (int i = first; i < last;) {
+            if (any_fused && run_at[i] >= 0) {
+                const la_binding::FusedRun& r = b->fused[run_at[i]];
+                FusedTable t = r.table;
+                t.op_code = op;
+                st = launch_fused(t, sched->dtype, r.unroll, hip_stream);
+                if (st != LA_OK) return st;
+                g_fused_launches.fetch_add(1);
+                i += sched->fusion.runs[run_at[i]].num_steps;
+                continue;
+            }
             StepTable t = b->step[i];
             t.op = op;
             st = launch_step(t, sched->dtype, b->shape[i], hip_stream);
             if (st != LA_OK) return st;
+            ++i;
         }
     }
     LA_HIP(hipEventRecord(b->last_use, stream));
@@ -727,6 +887,20 @@ la_status_t la_allreduce_emulated_out_of_place(const la_schedule_t* sched, const
         return fail(LA_ERR_INVALID_ARG, "la_allreduce_emulated_out_of_place: n/dtype differ from the schedule's (%llu, %d)",
                     (unsigned long long)sched->n, (int)sched->dtype);
     return run_steps(sched, recvbufs, sendbufs, 0, (int)sched->steps.size(), (uint32_t)op, hip_stream);
+}
+
+la_status_t la_schedule_run_steps(const la_schedule_t* sched, int first_step, int num_steps, void* const* bufs,
+                                  la_op_t op, void* hip_stream)
+{
+    if (!sched) return fail(LA_ERR_INVALID_ARG, "la_schedule_run_steps: schedule is NULL");
+    if (!bufs) return fail(LA_ERR_INVALID_ARG, "la_schedule_run_steps: bufs is NULL");
+    if (!known_op((int)op)) return fail(LA_ERR_UNSUPPORTED, "la_schedule_run_steps: unknown operation %d", (int)op);
+    if (first_step < 0 || num_steps < 0 || first_step > (int)sched->steps.size() ||
+        num_steps > (int)sched->steps.size() - first_step)
+        return fail(LA_ERR_INVALID_ARG, "la_schedule_run_steps: steps [%d, %d + %d) out of range", first_step, first_step,
+                    num_steps);
+    if (num_steps == 0) return LA_OK;
+    return run_steps(sched, bufs, nullptr, first_step, first_step + num_steps, (uint32_t)op, hip_stream);
 }
 
 la_status_t la_schedule_run_step(const la_schedule_t* sched, int step, void* const* bufs, void* hip_stream)
@@ -921,6 +1095,16 @@ la_status_t la_tuning_set(const char* key, int value)
         g_merge.store(value);
         return LA_OK;
     }
+    if (k == "forward") {
+        if (value != 0 && value != 1) return fail(LA_ERR_INVALID_ARG, "la_tuning_set: forward must be 0 or 1");
+        g_forward.store(value);
+        return LA_OK;
+    }
+    if (k == "fuse") {
+        if (value < -1 || value > 1) return fail(LA_ERR_INVALID_ARG, "la_tuning_set: fuse must be -1 (auto), 0 or 1");
+        g_fuse.store(value);
+        return LA_OK;
+    }
     if (k == "block") {
         if (value != 0 && value != 256 && value != 1024)
             return fail(LA_ERR_INVALID_ARG, "la_tuning_set: block must be 0 (auto), 256 or 1024");
@@ -939,6 +1123,9 @@ int la_tuning_get(const char* key)
     if (k == "block") return g_block.load();
     if (k == "graph") return g_graph.load();
     if (k == "merge") return g_merge.load();
+    if (k == "fuse") return g_fuse.load();
+    if (k == "forward") return g_forward.load();
+    if (k == "fused_launches") return g_fused_launches.load();
     return -2;
 }
 

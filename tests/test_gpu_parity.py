@@ -499,6 +499,7 @@ def test_graph_replays_match_step_by_step_launches(oracle, algo, flags, topo):
     ref = x
     scratch = torch.zeros(1 << 20, device="cuda")
     try:
+        la.la_tuning_set("fuse", 0)  # the ring steps would otherwise go out as one fused launch, not as a graph
         for replay in range(4):
             la.la_tuning_set("graph", -1 if auto else 1)
             la.allreduce_tensors(sched, bufs)              # graph replay
@@ -520,6 +521,7 @@ def test_graph_replays_match_step_by_step_launches(oracle, algo, flags, topo):
         assert np.array_equal(bits(np.stack([to_host(b) for b in other])), bits(oracle.allreduce(oracle_name(algo, flags), N, G, Q, x)))
     finally:
         la.la_tuning_set("graph", -1)
+        la.la_tuning_set("fuse", -1)
 
 
 # ------------------------------------------------------------------------------ operations and wide types
@@ -1008,6 +1010,206 @@ def test_merged_and_unmerged_launch_segments_give_the_same_bits(oracle, flags):
             finally:
                 la.la_tuning_set("merge", 1)
             assert np.array_equal(bits(got), bits(ref)), (kind, n, shift, flags, merge)
+
+
+# ------------------------------------------------------------------------------ one launch for all steps
+
+class fused_launch:
+    """with fused_launch(mode): ... sets the "fuse" knob (1: every run of two or more steps with at most two
+    sources and destinations per segment goes out as one launch; -1: the automatic choice; 0: none);
+    .count = fused launches made inside"""
+
+    def __init__(self, mode=1):
+        self.mode = mode
+
+    def __enter__(self):
+        la.la_tuning_set("fuse", self.mode)
+        self.start = la.la_tuning_get("fused_launches")
+        return self
+
+    def __exit__(self, *exc):
+        self.count = la.la_tuning_get("fused_launches") - self.start
+        la.la_tuning_set("fuse", -1)
+        return False
+
+
+@pytest.mark.parametrize("algo,flags", [("ring", 0), ("lane", 0), ("lane_multiproc", 0), ("lane", la.LA_SCHED_INNER_RING),
+                                        ("lane_multiproc", la.LA_SCHED_INNER_RING), ("lane_multiproc", la.LA_SCHED_P2P_GATHER),
+                                        ("lane_multiproc", la.LA_SCHED_FUSED_GATHER), ("rabenseifner", 0),
+                                        ("recursive_doubling", 0)])
+def test_fused_launch_small_topologies_ragged_sizes_all_dtypes(oracle, algo, flags):
+    """The whole schedule in one launch, every chain start to end by one wave: bit-equal to the
+    oracle (and so to the step-by-step launches) on lengths with ragged chains, heads and tails."""
+    topos = [(2, 2, 2), (4, 2, 1), (1, 4, 2)] if algo in ("rabenseifner", "recursive_doubling") else \
+            [(2, 2, 2), (3, 2, 1), (1, 3, 2), (2, 1, 3), (5, 1, 1), (4, 2, 2)]
+    for topo in topos:
+        P = topo[0] * topo[1] * topo[2]
+        for n, kind in ((1, "i32wrap"), (7, "f32order"), (1000, "bf16"), (4097, "f32order"), (65536, "i32wrap"),
+                        (100003, "bf16"), (262144 + 5, "f32order")):
+            x = make(P, n, kind, seed=n)
+            ref = oracle.allreduce(oracle_name(algo, flags), *topo, x)
+            print("fused", algo, flags, topo, n, kind, flush=True)
+            with fused_launch() as f:
+                got = gpu_allreduce(topo, algo, x, flags)
+            runs = la.la_schedule_fusion_runs(la.la_schedule_build(la.la_topology_create(*topo), algo, n, NAME[x.dtype], flags))
+            assert f.count == runs, (algo, topo, n, f.count, runs)
+            assert np.array_equal(bits(got), bits(ref)), (algo, flags, topo, n, kind)
+
+
+@pytest.mark.parametrize("op", ["sum", "prod", "max", "min"])
+def test_fused_launch_operations_and_wide_types(oracle, op):
+    topo, n = (3, 2, 2), 30011
+    for kind in ("i32wrap", "f32order", "bf16", "f16", "f64"):
+        x = wide_inputs(12, n, kind, 3) if kind in ("f16", "f64") else make(12, n, kind, seed=5)
+        for algo, flags in (("ring", 0), ("lane_multiproc", la.LA_SCHED_INNER_RING)):
+            ref = oracle.allreduce(oracle_name(algo, flags), *topo, x, op=op)
+            print("fused", op, kind, algo, flush=True)
+            with fused_launch() as f:
+                got = gpu_allreduce(topo, algo, x, flags, op=op)
+            assert f.count == 1
+            assert np.array_equal(bits(got), bits(ref)), (op, kind, algo)
+
+
+def test_fused_launch_views_at_odd_offsets_and_fallback(oracle):
+    """Views that share an odd element offset have heads and tails in every chain; views whose offsets
+    differ modulo 16 bytes cannot run fused and must fall back to the step-by-step launches."""
+    topo, n = (2, 2, 2), 50001
+    for kind in ("f32order", "bf16", "i32wrap"):
+        x = make(8, n, kind, seed=11)
+        ref = oracle.allreduce("ring", *topo, x)
+        for shifts, fused in (([3] * 8, 1), ([1] * 8, 1), ([0, 1, 2, 3, 4, 5, 6, 7], 0)):
+            full = [to_dev(np.concatenate([x[r][:shifts[r]], x[r], x[r][:8]])) for r in range(8)]
+            views = [full[r][shifts[r]: shifts[r] + n] for r in range(8)]
+            sched = la.la_schedule_build(la.la_topology_create(*topo), "ring", n, NAME[x.dtype])
+            print("fused views", kind, shifts, flush=True)
+            with fused_launch() as f:
+                la.la_allreduce_emulated(sched, [v.data_ptr() for v in views], n, NAME[x.dtype], la.LA_SUM,
+                                         torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+            assert f.count == fused, (kind, shifts, f.count)
+            got = np.stack([to_host(v) for v in views])
+            assert np.array_equal(bits(got), bits(ref)), (kind, shifts)
+            # the elements around the views are untouched
+            for r in range(8):
+                h = to_host(full[r])
+                assert np.array_equal(h[:shifts[r]], x[r][:shifts[r]]) and np.array_equal(h[shifts[r] + n:], x[r][:8])
+
+
+def test_fused_launch_out_of_place_shared_buffers_and_repeats(oracle):
+    topo, n = (2, 2, 2), 70001
+    x = make(8, n, "f32order", seed=2)
+    ref = oracle.allreduce("ring", *topo, x)
+    sched = la.la_schedule_build(la.la_topology_create(*topo), "ring", n, "float32", la.LA_SCHED_OUT_OF_PLACE)
+    send = [to_dev(x[r]) for r in range(8)]
+    recv = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(8)]
+    with fused_launch() as f:
+        for _ in range(3):  # the second and third call reuse the binding's fused tables
+            la.la_allreduce_emulated_out_of_place(sched, [t.data_ptr() for t in send], [t.data_ptr() for t in recv], n,
+                                                  "float32", la.LA_SUM, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+    assert f.count == 3
+    assert np.array_equal(bits(np.stack([to_host(t) for t in recv])), bits(ref))
+    assert np.array_equal(np.stack([to_host(t) for t in send]), x)
+    # shared buffers, standard approach: Q rings in one launch per iteration; fused: one launch in all
+    xs = make(4, n, "bf16", seed=4)
+    refs = oracle.allreduce("ring", *topo, xs, shared=True)
+    sh = la.la_schedule_build(la.la_topology_create(*topo), "ring", n, "bfloat16", la.LA_SCHED_SHARED_BUFFERS)
+    bufs = [to_dev(xs[b]) for b in range(4)]
+    with fused_launch() as f:
+        la.allreduce_tensors(sh, bufs)
+        torch.cuda.synchronize()
+    assert f.count == 1
+    assert np.array_equal(bits(np.stack([to_host(b) for b in bufs])), bits(refs))
+    # a staged ring: the pack and reduce steps work through the staging area and keep their launches,
+    # the gather loop (rank buffer to rank buffer) is one fused launch
+    st = la.la_schedule_build(la.la_topology_create(*topo), "ring", n, "float32", la.LA_SCHED_STAGED)
+    bufs = [to_dev(x[r]) for r in range(8)]
+    with fused_launch() as f:
+        la.allreduce_tensors(st, bufs)
+        torch.cuda.synchronize()
+    assert f.count == 1
+    assert np.array_equal(bits(np.stack([to_host(b) for b in bufs])), bits(ref))
+    # with the knob off nothing is fused, and the result is the same
+    bufs = [to_dev(x[r]) for r in range(8)]
+    plain = la.la_schedule_build(la.la_topology_create(*topo), "ring", n, "float32")
+    with fused_launch(0) as f:
+        la.allreduce_tensors(plain, bufs)
+        torch.cuda.synchronize()
+    assert f.count == 0
+    assert np.array_equal(bits(np.stack([to_host(b) for b in bufs])), bits(ref))
+    # the automatic choice fuses the ring (14 steps, one operation per step and chain) ...
+    bufs = [to_dev(x[r]) for r in range(8)]
+    with fused_launch(-1) as f:
+        la.allreduce_tensors(plain, bufs)
+        torch.cuda.synchronize()
+    assert f.count == 1
+    assert np.array_equal(bits(np.stack([to_host(b) for b in bufs])), bits(ref))
+    # ... with and without taking the incoming chunk from registers
+    try:
+        la.la_tuning_set("forward", 0)
+        bufs = [to_dev(x[r]) for r in range(8)]
+        with fused_launch(-1) as f:
+            la.allreduce_tensors(plain, bufs)
+            torch.cuda.synchronize()
+        assert f.count == 1
+        assert np.array_equal(bits(np.stack([to_host(b) for b in bufs])), bits(ref))
+    finally:
+        la.la_tuning_set("forward", 1)
+    # ... but not recursive doubling (4 steps, 8 operations per step on its one chain)
+    rd = la.la_schedule_build(la.la_topology_create(*topo), "recursive_doubling", n, "float32")
+    bufs = [to_dev(x[r]) for r in range(8)]
+    with fused_launch(-1) as f:
+        la.allreduce_tensors(rd, bufs)
+        torch.cuda.synchronize()
+    assert f.count == 0
+    assert np.array_equal(bits(np.stack([to_host(b) for b in bufs])), bits(oracle.allreduce("recursive_doubling", *topo, x)))
+
+
+@pytest.mark.parametrize("algo,flags", [("ring", 0), ("lane_multiproc", 0), ("lane", la.LA_SCHED_INNER_RING), ("rabenseifner", 0)])
+def test_fused_launch_of_the_stand_alone_halves(oracle, algo, flags):
+    """Reduce-scatter half then all-gather half, each as one fused launch: together the all-reduce.
+    (The all-gather half of a lane schedule broadcasts original inputs: one source, many destinations.)"""
+    topo, n = ((2, 2, 2) if algo == "rabenseifner" else (3, 2, 2)), 40003
+    P = topo[0] * topo[1] * topo[2]
+    for kind in ("f32order", "bf16"):
+        x = make(P, n, kind, seed=6)
+        ref = oracle.allreduce(oracle_name(algo, flags), *topo, x)
+        t = la.la_topology_create(*topo)
+        rs = la.la_schedule_build(t, algo, n, NAME[x.dtype], flags | la.LA_SCHED_ONLY_REDUCE_SCATTER)
+        ag = la.la_schedule_build(t, algo, n, NAME[x.dtype], flags | la.LA_SCHED_ONLY_ALLGATHER)
+        bufs = [to_dev(x[r]) for r in range(P)]
+        print("fused halves", algo, flags, kind, rs.num_steps, ag.num_steps, flush=True)
+        with fused_launch() as f:
+            la.allreduce_tensors(rs, bufs)
+            la.allreduce_tensors(ag, bufs)
+            torch.cuda.synchronize()
+        assert f.count == la.la_schedule_fusion_runs(rs) + la.la_schedule_fusion_runs(ag)
+        assert np.array_equal(bits(np.stack([to_host(b) for b in bufs])), bits(ref)), (algo, flags, kind)
+
+
+@pytest.mark.parametrize("algo,flags,topo,n", [("ring", 0, (32, 4, 8), 1 << 20),
+                                               ("lane_multiproc", la.LA_SCHED_INNER_RING, (32, 4, 8), 1 << 20),
+                                               ("ring", 0, (4, 4, 1), 1 << 24),
+                                               ("lane_multiproc", la.LA_SCHED_INNER_RING, (8, 4, 4), 1 << 22)])
+def test_fused_launch_full_size(oracle, algo, flags, topo, n):
+    """Algorithm 1 over 1024 ranks (2046 steps), the ring as inter-node stage of configs 5 and 3, and the
+    ring of config 2, each as ONE launch, against the oracle at full size."""
+    P = topo[0] * topo[1] * topo[2]
+    x = synth.make_inputs(P, n, "uniform_pm1")
+    bufs = [to_dev(x[r]) for r in range(P)]
+    sched = la.la_schedule_build(la.la_topology_create(*topo), algo, n, "float32", flags)
+    print("fused full size", algo, flags, topo, n, "steps", sched.num_steps, flush=True)
+    with fused_launch() as f:
+        la.allreduce_tensors(sched, bufs)
+        torch.cuda.synchronize()
+    assert f.count == 1
+    got0 = to_host(bufs[0])
+    for r in range(1, P):  # all ranks identical, compared on the device
+        assert torch.equal(bufs[r], bufs[0]), r
+    del bufs
+    torch.cuda.empty_cache()
+    ref = oracle.allreduce(oracle_name(algo, flags), *topo, x, in_place=True)
+    assert np.array_equal(bits(got0), bits(ref[0]))
 
 
 # ------------------------------------------------------------------------------ random combinations
