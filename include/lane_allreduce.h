@@ -80,10 +80,10 @@ enum {
      * Without it the reduce reads the peers' segments in place (fused pack + reduce). */
     LA_SCHED_STAGED = 2u,
     /* Lane schedules only: the inter-node all-reduce of every part is Algorithm 1 run on the lane
-     * communicator (the variant of the Results section "where the ring algorithm is used in the
-     * inter-node stage of the multi-lane all-reduce"): 2(N-1) launches, each one ring iteration
-     * of all lane communicators, instead of the direct N-way exchange.  Ignored by the algorithms
-     * that have no inter-node stage (ring, recursive doubling, Rabenseifner). */
+     * communicator (the inter-node ring variant that the Results section measures): 2(N-1) steps,
+     * each one ring iteration of all lane communicators, instead of the direct N-way exchange.
+     * Ignored by the algorithms that have no inter-node stage (ring, recursive doubling,
+     * Rabenseifner). */
     LA_SCHED_INNER_RING = 4u,
     /* The shared-buffer model of "Multiple Processes Per GPU": one buffer per GPU (bufs holds
      * nodes * gpus_per_node pointers, index node * gpus_per_node + gpu); the procs_per_gpu

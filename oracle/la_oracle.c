@@ -75,8 +75,8 @@ enum {
     ORACLE_RING = 0,
     ORACLE_LANE = 1,
     ORACLE_LANE_MULTIPROC = 2,
-    /* Algorithm 2 with Algorithm 1 as the all-reduce on the lane communicator (the variant the
-     * Results section measures "where the ring algorithm is used in the inter-node stage") */
+    /* Algorithm 2 with Algorithm 1 as the all-reduce on the lane communicator (the inter-node ring
+     * variant that the Results section measures) */
     ORACLE_LANE_RING = 3,
     ORACLE_LANE_MULTIPROC_RING = 4,
     /* the small- and medium-size algorithms of the Background section, flat over the P ranks
@@ -364,12 +364,9 @@ int oracle_definition_sum(int dtype, int P, uint64_t n, const void* const* in, v
 
 /* ---- element-wise k-operand sum, operands in the order given -------------- */
 
-static int g_op = OP_SUM; /* the operation of the run in progress (set by the entry points) */
-
-static void sum_operands(int dtype, void* dst, const void* const* ops, int k, uint64_t cnt)
+static void sum_operands(int dtype, int op, void* dst, const void* const* ops, int k, uint64_t cnt)
 {
     int64_t m = (int64_t)cnt;
-    const int op = g_op;
     if (dtype == ORACLE_I32) {
 #pragma omp parallel for num_threads(g_threads) schedule(static)
         for (int64_t i = 0; i < m; ++i) {
@@ -424,14 +421,13 @@ int oracle_reduce_segments_op(int dtype, int op, void* dst, const void* const* s
                               const uint64_t* seg_offsets, uint64_t num_segments, uint64_t seg_len)
 {
     if (k < 0 || k > 4096 || op < OP_SUM || op > OP_MIN) return 1;
-    g_op = op;
     size_t e = elem_size(dtype);
     const void* ops[4097];
     for (uint64_t s = 0; s < num_segments; ++s) {
         uint64_t o = seg_offsets[s];
         ops[0] = (const char*)dst + o * e;
         for (int t = 0; t < k; ++t) ops[t + 1] = (const char*)srcs[t] + o * e;
-        sum_operands(dtype, (char*)dst + o * e, ops, k + 1, seg_len);
+        sum_operands(dtype, op, (char*)dst + o * e, ops, k + 1, seg_len);
     }
     return 0;
 }
@@ -452,6 +448,7 @@ typedef struct {
 typedef struct {
     int P;
     int dtype;
+    int op;         /* the reduction operation of the run */
     size_t esz;
     uint64_t n;
     void** buf;     /* the buffers (caller's memory, updated in place) */
@@ -557,7 +554,7 @@ static int run_ring(world_t* w, int max_rounds)
             if (!l) return 4;
             char* own = mem(w, r) + l->off * w->esz;
             const void* ops[2] = {own, l->data}; /* own = own + incoming */
-            sum_operands(w->dtype, own, ops, 2, l->cnt);
+            sum_operands(w->dtype, w->op, own, ops, 2, l->cnt);
         }
         end_round(w);
     }
@@ -603,7 +600,7 @@ static int run_recursive_doubling(world_t* w, int max_rounds)
             if (!l) return 4;
             char* own = mem(w, r);
             const void* two[2] = {own, l->data}; /* own = own + incoming */
-            sum_operands(w->dtype, own, two, 2, l->cnt);
+            sum_operands(w->dtype, w->op, own, two, 2, l->cnt);
         }
         end_round(w);
     }
@@ -645,7 +642,7 @@ static int run_rabenseifner(world_t* w, int max_rounds)
             if (!l || l->off != lo[r * (L + 1) + s + 1]) return 4;
             char* own = mem(w, r) + l->off * w->esz;
             const void* two[2] = {own, l->data};
-            sum_operands(w->dtype, own, two, 2, l->cnt);
+            sum_operands(w->dtype, w->op, own, two, 2, l->cnt);
         }
         end_round(w);
     }
@@ -738,7 +735,7 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
                         ops[l] = le->data;
                     }
                 }
-                sum_operands(w->dtype, mine, ops, R, cnt);
+                sum_operands(w->dtype, w->op, mine, ops, R, cnt);
             }
         end_round(w);
     }
@@ -768,7 +765,7 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
                         if (loop == 0) {
                             char* mine = mem(w, me) + le->off * w->esz;
                             const void* two[2] = {mine, le->data}; /* own = own + incoming */
-                            sum_operands(w->dtype, mine, two, 2, le->cnt);
+                            sum_operands(w->dtype, w->op, mine, two, 2, le->cnt);
                         } else {
                             overwrite(w, me, le);
                         }
@@ -812,7 +809,7 @@ static int run_lane(world_t* w, const lane_cfg_t* c, int max_rounds)
                         ops[from] = le->data;
                     }
                 }
-                sum_operands(w->dtype, mine, ops, N, pc);
+                sum_operands(w->dtype, w->op, mine, ops, N, pc);
             }
         }
         end_round(w);
@@ -891,7 +888,7 @@ static int run_shared_standard(world_t* w, int N, int G, int Q, int max_rounds)
                     if (loop == 0) {
                         char* mine = mem(w, me) + le->off * w->esz;
                         const void* two[2] = {mine, le->data};
-                        sum_operands(w->dtype, mine, two, 2, le->cnt);
+                        sum_operands(w->dtype, w->op, mine, two, 2, le->cnt);
                     } else {
                         overwrite(w, me, le);
                     }
@@ -938,7 +935,7 @@ static int run_shared_lane(world_t* w, int N, int G, int Q, int max_rounds)
                             ops[from] = le->data;
                         }
                     }
-                    sum_operands(w->dtype, mine, ops, G, cc);
+                    sum_operands(w->dtype, w->op, mine, ops, G, cc);
                 }
             }
         end_round(w);
@@ -982,7 +979,7 @@ static int run_shared_lane(world_t* w, int N, int G, int Q, int max_rounds)
                                 ops[from] = le->data;
                             }
                         }
-                        sum_operands(w->dtype, mine, ops, N, pc);
+                        sum_operands(w->dtype, w->op, mine, ops, N, pc);
                     }
                 }
             }
@@ -1023,7 +1020,7 @@ static int run_shared_lane(world_t* w, int N, int G, int Q, int max_rounds)
  *   number of messages sent (which may exceed trace_cap).
  * Returns 0 on success.
  */
-static int run_world(int shared, int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
+static int run_world(int shared, int op, int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
                      int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len);
 
 /* Same as oracle_allreduce / oracle_allreduce_shared with an operation other than the sum. */
@@ -1031,17 +1028,13 @@ int oracle_allreduce_op(int shared, int op, int algo, int N, int G, int Q, uint6
                         int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
 {
     if (op < OP_SUM || op > OP_MIN) return 2;
-    g_op = op;
-    int rc = run_world(shared, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
-    g_op = OP_SUM;
-    return rc;
+    return run_world(shared, op, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
 }
 
 int oracle_allreduce(int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
                      int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
 {
-    g_op = OP_SUM;
-    return run_world(0, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
+    return run_world(0, OP_SUM, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
 }
 
 /* The shared-buffer model: bufs holds N*G buffers (index node*G + gpu) of n elements; P = N*G*Q
@@ -1051,11 +1044,10 @@ int oracle_allreduce(int algo, int N, int G, int Q, uint64_t n, int dtype, void*
 int oracle_allreduce_shared(int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
                             int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
 {
-    g_op = OP_SUM;
-    return run_world(1, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
+    return run_world(1, OP_SUM, algo, N, G, Q, n, dtype, bufs, max_rounds, trace, trace_cap, trace_len);
 }
 
-static int run_world(int shared, int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
+static int run_world(int shared, int op, int algo, int N, int G, int Q, uint64_t n, int dtype, void** bufs,
                      int max_rounds, oracle_msg_t* trace, uint64_t trace_cap, uint64_t* trace_len)
 {
     if (N < 1 || G < 1 || Q < 1 || !bufs) return 1;
@@ -1064,6 +1056,7 @@ static int run_world(int shared, int algo, int N, int G, int Q, uint64_t n, int 
     memset(&w, 0, sizeof w);
     w.P = N * G * Q;
     w.dtype = dtype;
+    w.op = op;
     w.esz = elem_size(dtype);
     w.n = n;
     w.buf = bufs;

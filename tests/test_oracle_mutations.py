@@ -24,7 +24,7 @@ MUTATIONS = [
      "post(w, r, imod(r - 1, P), D[sp], cnt[sp]);\n        }\n        for (int r = 0; r < P; ++r) {\n            const letter_t* l = letter_from(w, r, (r + 1) % P);\n            if (!l) return 4;\n            char* own"),
     ("s1_owner_first", "                for (int l = 0; l < R; ++l) {\n                    if (l == own) {\n                        ops[l] = mine;",
      "                ops[0] = mine;\n                for (int l = 0; l < R; ++l) {\n                    if (l == own) {\n                        if (l) ops[l] = ops[0]; if (l) ops[0] = mine;"),
-    ("s1_drops_last_operand", "sum_operands(w->dtype, mine, ops, R, cnt);", "sum_operands(w->dtype, mine, ops, R > 1 ? R - 1 : R, cnt);"),
+    ("s1_drops_last_operand", "sum_operands(w->dtype, w->op, mine, ops, R, cnt);", "sum_operands(w->dtype, w->op, mine, ops, R > 1 ? R - 1 : R, cnt);"),
     ("s2a_piece_index_swapped", "part(cnt, (uint64_t)N, (uint64_t)to, &po, &pc);\n                    if (to != from) post",
      "part(cnt, (uint64_t)N, (uint64_t)from, &po, &pc);\n                    if (to != from) post"),
     ("s2a_descending_order", "ops[from] = le->data;", "ops[N - 1 - from] = le->data;"),
@@ -42,8 +42,8 @@ MUTATIONS = [
     ("shared_standard_gpu_major_slices", "part(sc, (uint64_t)M, (uint64_t)sp, &co, &cc);\n                    post(w, u * Q + q, ((u + 1) % M) * Q + q, so + co, cc);",
      "part(w->n, (uint64_t)M, (uint64_t)sp, &co, &cc); part(cc, (uint64_t)Q, (uint64_t)q, &so, &sc);\n                    post(w, u * Q + q, ((u + 1) % M) * Q + q, so + co, sc);"),
     ("shared_standard_crosses_local_ranks", "post(w, u * Q + q, ((u + 1) % M) * Q + q, so + co, cc);", "post(w, u * Q + q, ((u + 1) % M) * Q + (q + 1) % Q, so + co, cc);"),
-    ("shared_lane_s1_descending", "                            ops[from] = le->data;\n                        }\n                    }\n                    sum_operands(w->dtype, mine, ops, G, cc);",
-     "                            ops[from] = le->data;\n                        }\n                    }\n                    if (G > 1) { const void* t0 = ops[0]; ops[0] = ops[G - 1]; ops[G - 1] = t0; }\n                    sum_operands(w->dtype, mine, ops, G, cc);"),
+    ("shared_lane_s1_descending", "                            ops[from] = le->data;\n                        }\n                    }\n                    sum_operands(w->dtype, w->op, mine, ops, G, cc);",
+     "                            ops[from] = le->data;\n                        }\n                    }\n                    if (G > 1) { const void* t0 = ops[0]; ops[0] = ops[G - 1]; ops[G - 1] = t0; }\n                    sum_operands(w->dtype, w->op, mine, ops, G, cc);"),
     ("shared_lane_gather_skips_last_gpu", "for (int to = 0; to < G; ++to)\n                        if (to != g) post(w, proc_rank(G, Q, node, g, q), proc_rank(G, Q, node, to, q), so + co, cc);",
      "for (int to = 0; to < G - 1; ++to)\n                        if (to != g) post(w, proc_rank(G, Q, node, g, q), proc_rank(G, Q, node, to, q), so + co, cc);"),
     ("shared_lane_piece_of_wrong_member", "part(cc, (uint64_t)N, (uint64_t)(half == 0 ? to : from), &po, &pc);", "part(cc, (uint64_t)N, (uint64_t)(half == 0 ? from : to), &po, &pc);"),
@@ -81,7 +81,7 @@ MUTATIONS = [
     ("definition_skips_rank0", "for (int p = 0; p < P; ++p) s += ((const int32_t*)in[p])[i];", "for (int p = 1; p < P; ++p) s += ((const int32_t*)in[p])[i];"),
     ("definition_float_in_single", "double s = as_double(dtype, in[0], i);\n            for (int p = 1; p < P; ++p) s = op_f64(op, s, as_double(dtype, in[p], i));",
      "float s = (float)as_double(dtype, in[0], i);\n            for (int p = 1; p < P; ++p) s = (float)op_f64(op, s, as_double(dtype, in[p], i));"),
-    ("reduce_segments_ignores_dst", "sum_operands(dtype, (char*)dst + o * e, ops, k + 1, seg_len);", "sum_operands(dtype, (char*)dst + o * e, ops + (k > 0), k > 0 ? k : 1, seg_len);"),
+    ("reduce_segments_ignores_dst", "sum_operands(dtype, op, (char*)dst + o * e, ops, k + 1, seg_len);", "sum_operands(dtype, op, (char*)dst + o * e, ops + (k > 0), k > 0 ? k : 1, seg_len);"),
     ("overwrite_wrong_offset", "memcpy(mem(w, at) + l->off * w->esz, l->data, l->cnt * w->esz);", "memcpy(mem(w, at) + (l->off ? l->off - 1 : 0) * w->esz, l->data, l->cnt * w->esz);"),
     ("shared_buffer_of_wrong_gpu", "return (char*)w->buf[rank / w->share];", "return (char*)w->buf[w->share > 1 ? rank % (w->P / w->share) : rank];"),
 ]
