@@ -200,7 +200,6 @@ struct la_binding {
     void* tables = nullptr;     // one device allocation holding every step's tables
     size_t tables_bytes = 0;
     void* staging = nullptr;    // library-owned staging area (LA_SCHED_STAGED)
-    hipEvent_t last_use = nullptr;
     bool used = false;
     std::vector<StepTable> step; // device views
     // the whole schedule as one executable graph of kernel nodes (launch-bound schedules)
@@ -230,17 +229,29 @@ static void drop_graph(la_binding* b)
     b->graph_failed = false;
 }
 
+// Work that a binding's tables serve may still be in flight on whatever streams the caller used.
+// Nothing is recorded per call to track it (an event record per all-reduce costs the stream about
+// as much as a short kernel); the rare operations that free or rewrite a used binding's tables
+// wait for the whole device instead.
+static void wait_for_device(int device)
+{
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) return;
+    if (cur != device && hipSetDevice(device) != hipSuccess) return;
+    (void)hipDeviceSynchronize();
+    if (cur != device) (void)hipSetDevice(cur);
+}
+
 void release_binding(la_binding* b)
 {
     if (!b) return;
-    if (b->used && b->last_use) (void)hipEventSynchronize(b->last_use);
+    if (b->used) wait_for_device(b->device);
     drop_graph(b);
     if (b->capture_stream) (void)hipStreamDestroy(b->capture_stream);
     if (b->tables) (void)hipFree(b->tables);
     for (la_binding::FusedRun& r : b->fused)
         if (r.tables) (void)hipFree(r.tables);
     if (b->staging) (void)hipFree(b->staging);
-    if (b->last_use) (void)hipEventDestroy(b->last_use);
     delete b;
 }
 
@@ -494,7 +505,7 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
         // recycle the least recently used one (its allocations are reused when it is on this device)
         b = s.bound.back();
         s.bound.pop_back();
-        if (b->used) (void)hipEventSynchronize(b->last_use); // earlier work still reads its tables
+        if (b->used) wait_for_device(b->device); // earlier work still reads its tables
         if (b->device != dev) {
             release_binding(b);
             b = nullptr;
@@ -504,10 +515,6 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
         b = new (std::nothrow) la_binding;
         if (!b) return fail(LA_ERR_OUT_OF_MEMORY, "out of host memory");
         b->device = dev;
-        if (hipEventCreateWithFlags(&b->last_use, hipEventDisableTiming) != hipSuccess) {
-            delete b;
-            return fail(LA_ERR_DEVICE, "hipEventCreate failed");
-        }
     }
     s.bound.insert(s.bound.begin(), b);
     b->bufs.clear(); // not a match for anything until it is complete
@@ -688,17 +695,49 @@ la_status_t build_fused(const la_schedule& s, la_binding* b, size_t run, const s
     return LA_OK;
 }
 
+// A binding that was made for exactly these pointers (in this order) on this device with this
+// tuning: the set was validated when it was bound.  No allocation, no sort: a repeat call costs one
+// comparison of P addresses.
+la_binding* find_binding(const la_schedule& s, void* const* bufs, const void* const* sendbufs, int dev,
+                         const Tuning& tune)
+{
+    const size_t P = (size_t)s.nbuf;
+    const bool oop = (s.flags & LA_SCHED_OUT_OF_PLACE) != 0;
+    if (oop != (sendbufs != nullptr)) return nullptr;
+    for (size_t i = 0; i < s.bound.size(); ++i) {
+        la_binding* c = s.bound[i];
+        if (c->device != dev || !(c->requested == tune) || c->bufs.size() != (oop ? 2 * P + 1 : P + 1)) continue;
+        bool same = true;
+        for (size_t r = 0; r < P && same; ++r) same = c->bufs[r] == reinterpret_cast<uint64_t>(bufs[r]);
+        for (size_t r = 0; oop && r < P && same; ++r) same = c->bufs[P + 1 + r] == reinterpret_cast<uint64_t>(sendbufs[r]);
+        if (!same) continue;
+        if (i) std::rotate(s.bound.begin(), s.bound.begin() + i, s.bound.begin() + i + 1); // to the front
+        return c;
+    }
+    return nullptr;
+}
+
 la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void* const* sendbufs, int first,
                       int last, uint32_t op, void* hip_stream)
 {
-    std::vector<uint64_t> addr;
-    la_status_t st = check_buffers(*sched, bufs, sendbufs, addr);
-    if (st != LA_OK) return st;
+    la_status_t st = LA_OK;
     std::lock_guard<std::mutex> lock(sched->mu);
     const Tuning tune = current_tuning();
-    st = bind(*sched, addr, tune);
-    if (st != LA_OK) return st;
-    la_binding* b = sched->bound.front();
+    int dev = -1;
+    LA_HIP(hipGetDevice(&dev));
+    la_binding* b = find_binding(*sched, bufs, sendbufs, dev, tune);
+    if (!b) {
+        try {
+            std::vector<uint64_t> fresh;
+            st = check_buffers(*sched, bufs, sendbufs, fresh);
+            if (st != LA_OK) return st;
+            st = bind(*sched, fresh, tune);
+            if (st != LA_OK) return st;
+        } catch (const std::bad_alloc&) {
+            return fail(LA_ERR_OUT_OF_MEMORY, "out of host memory");
+        }
+        b = sched->bound.front();
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int mode = g_graph.load();
     const bool whole = first == 0 && last == (int)sched->steps.size();
@@ -718,6 +757,7 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void*
                 if (f.first_step < first || f.first_step + f.num_steps > last) continue;
                 if (fuse < 0 && !f.automatic()) continue;
                 if (!b->fused[r].ready && !b->fused[r].impossible) {
+                    std::vector<uint64_t> addr = b->bufs; // the caller's addresses; the staging slot is not used by a run
                     st = build_fused(*sched, b, r, addr);
                     if (st != LA_OK) return st;
                 }
@@ -765,7 +805,6 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void*
             ++i;
         }
     }
-    LA_HIP(hipEventRecord(b->last_use, stream));
     b->used = true;
     return LA_OK;
 }

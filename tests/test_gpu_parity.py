@@ -381,6 +381,36 @@ def test_ring_steps_match_oracle_rounds(oracle):
         assert np.array_equal(bits(got), bits(ref)), step
 
 
+@pytest.mark.parametrize("op", ["prod", "max", "min"])
+@pytest.mark.parametrize("algo,flags", [("lane_multiproc", la.LA_SCHED_P2P_GATHER), ("ring", 0),
+                                        ("lane", la.LA_SCHED_INNER_RING)])
+def test_steps_with_other_operations_match_oracle_rounds(oracle, algo, flags, op):
+    """la_schedule_run_steps takes the operation: every step by itself, and the steps in pairs, against
+    the oracle stopped after as many rounds (product, maximum, minimum; fp32 and bf16)."""
+    topo, n = (3, 2, 2), 9001
+    for kind in ("f32order", "bf16"):
+        x = make(12, n, kind, seed=8)
+        if op == "prod" and kind == "f32order":
+            x = (np.sign(x) * (1.0 + (np.abs(x) % 1.0) * 0.25)).astype(np.float32)  # keep 12-fold products finite
+        sched = la.la_schedule_build(la.la_topology_create(*topo), algo, n, NAME[x.dtype], flags)
+        for stride in (1, 2):
+            bufs = [to_dev(x[r]) for r in range(12)]
+            ptrs = [b.data_ptr() for b in bufs]
+            for first in range(0, sched.num_steps, stride):
+                count = min(stride, sched.num_steps - first)
+                print("run_steps", algo, flags, op, kind, first, count, flush=True)
+                la.la_schedule_run_steps(sched, first, count, ptrs, la.OPS[op], torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+                got = np.stack([to_host(b) for b in bufs])
+                ref = oracle.allreduce(oracle_name(algo, flags), *topo, x, max_rounds=first + count, op=op)
+                assert np.array_equal(bits(got), bits(ref)), (first, count)
+    with pytest.raises(la.LaError):
+        la.la_schedule_run_steps(sched, sched.num_steps, 1, ptrs)
+    with pytest.raises(la.LaError):
+        la.la_schedule_run_steps(sched, 0, 1, ptrs, 17)
+    la.la_schedule_run_steps(sched, sched.num_steps, 0, ptrs)  # an empty range is no work
+
+
 # ------------------------------------------------------------------------------ streams, rebinding, repetition
 
 def test_side_stream_rebinding_and_repeated_calls(oracle):
