@@ -411,6 +411,45 @@ def test_steps_with_other_operations_match_oracle_rounds(oracle, algo, flags, op
     la.la_schedule_run_steps(sched, sched.num_steps, 0, ptrs)  # an empty range is no work
 
 
+def test_copies_move_signalling_nans_unchanged(oracle):
+    """A copy or broadcast step moves bits: a signalling NaN of a 16-bit type must arrive as it was
+    sent (widening and narrowing it would set its quiet bit), as the gather rounds of the oracle move
+    what they carry unchanged.  Reached where original inputs are copied: the out-of-place form on one
+    rank (a single copy step), and the all-gather half, which distributes ranges no reduce has touched."""
+    n = 4099
+    for dtype, snan in ((np.uint16, [0x7F81, 0xFF81, 0x7FA0]), (np.float16, [0x7D01, 0xFD01, 0x7C01])):
+        x = make(1, n, "bf16", seed=1) if dtype == np.uint16 else wide_inputs(1, n, "f16", 1)
+        raw = x.view(np.uint16)
+        raw[0, 5:5 + len(snan)] = snan
+        raw[0, n - 1] = snan[0]
+        name = NAME[x.dtype]
+        sched = la.la_schedule_build(la.la_topology_create(1, 1, 1), "lane", n, name, la.LA_SCHED_OUT_OF_PLACE)
+        send = to_dev(x[0]) if dtype == np.uint16 else torch.from_numpy(x[0]).cuda()
+        recv = torch.zeros_like(send)
+        la.la_allreduce_emulated_out_of_place(sched, [send.data_ptr()], [recv.data_ptr()], n, name)
+        torch.cuda.synchronize()
+        got = to_host(recv).view(np.uint16)
+        assert sched.num_steps == 1 and sched.step_info(0)["kind"] == la.LA_STEP_COPY
+        assert np.array_equal(got, raw[0]), name
+        # the all-gather half of a ring and of a lane schedule on 2 x 2 x 1 ranks: every rank's owned range holds
+        # signalling NaNs; afterwards every rank holds them all, bit for bit
+        for algo in ("ring", "lane"):
+            P = 4
+            ag = la.la_schedule_build(la.la_topology_create(2, 2, 1), algo, n, name, la.LA_SCHED_ONLY_ALLGATHER)
+            y = np.zeros((P, n), dtype=np.uint16)
+            want = np.zeros(n, dtype=np.uint16)
+            for r in range(P):
+                for off, ln in ag.owned_ranges(r):
+                    y[r, off:off + ln] = np.resize(np.array(snan, dtype=np.uint16) + r, ln)
+                    want[off:off + ln] = y[r, off:off + ln]
+            bufs = [torch.from_numpy(y[r].view(np.int16)).cuda().view(torch.bfloat16 if dtype == np.uint16 else torch.float16)
+                    for r in range(P)]
+            la.allreduce_tensors(ag, bufs)
+            torch.cuda.synchronize()
+            for r in range(P):
+                assert np.array_equal(bufs[r].view(torch.int16).cpu().numpy().view(np.uint16), want), (name, algo, r)
+
+
 # ------------------------------------------------------------------------------ streams, rebinding, repetition
 
 def test_side_stream_rebinding_and_repeated_calls(oracle):
