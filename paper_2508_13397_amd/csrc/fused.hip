@@ -73,7 +73,7 @@ __device__ __forceinline__ void chain_op(const ChainContext<U>& c, uint32_t rec,
                                          u32x4 (&last)[U])
 {
     using P = Policy<1>; // original inputs non-temporal; sources an earlier operation wrote, and all stores, plain
-    if (record_dword(rec, 1) != 0) { // not padding behind the chain's last operation
+    if ((record_dword(rec, 1) & 1u) != 0) { // not padding behind the chain's last operation
         const uint32_t km = record_dword(rec, 2), pf = record_dword(rec, 3);
         const uint32_t k = km & 0xffffu, m = km >> 16;
         const int32_t ps = (int16_t)(pf & 0xffffu), fw = (int16_t)(pf >> 16);
@@ -134,7 +134,7 @@ __device__ __forceinline__ void chain_op(const ChainContext<U>& c, uint32_t rec,
     }
     // the slot is free: request the original input of the operation PREFETCH_DEPTH ahead, if it has one
     const int32_t pn = (int16_t)(record_dword(ahead, 3) & 0xffffu);
-    if (pn >= 0 && record_dword(ahead, 1) != 0) {
+    if (pn >= 0 && (record_dword(ahead, 1) & 1u) != 0) {
         const uint64_t next = pn == 1 ? record_address(ahead, 1) : record_address(ahead, 0);
         const __amdgpu_buffer_rsrc_t r = tile_rsrc(next, c.tile_off, c.tile_bytes);
 #pragma unroll
@@ -150,7 +150,7 @@ __device__ void edge_chain(const LA_CONSTANT FusedOp* ops, uint32_t num_ops, uin
 {
     using elem_t = typename T::elem;
     for (uint32_t j = 0; j < num_ops; ++j) {
-        if (ops[j].live == 0) continue;
+        if ((ops[j].live & 1u) == 0) continue;
         const uint32_t k = ops[j].k, m = ops[j].m;
         const elem_t e0 = reinterpret_cast<const elem_t*>(ops[j].addr[0])[elem];
         elem_t r = e0;
@@ -160,11 +160,54 @@ __device__ void edge_chain(const LA_CONSTANT FusedOp* ops, uint32_t num_ops, uin
     }
 }
 
+// Eight consecutive operations of one of the two shapes that make up a ring, as straight-line code.
+//   FUSED_BLOCK_ADD   every operation adds what the lane stored in the previous operation (source 1)
+//                     to an original input that was requested ahead of time (source 0) and stores to
+//                     one destination: a rank receives a partial sum and adds its own copy;
+//   FUSED_BLOCK_COPY  every operation stores what the lane stored in the previous operation to one
+//                     destination: a rank receives a finished chunk.
+// The host marks a block (in its first record) only if, in addition, the four operations behind it
+// want a prefetch (ADD) or none of them does (COPY), so that no access in the block is conditional.
+// Without branches the compiler can count which of the loads in flight an operation has to wait
+// for; the general path below, with its branches, waits for all of them in every operation, which
+// made every operation as long as a trip to memory (1.4 us on Algorithm 1 over 1024 ranks).
+template <typename T, int U, int KIND>
+__device__ __forceinline__ void ring_block(const ChainContext<U>& c, uint32_t j, uint32_t (&r)[RECORD_DEPTH],
+                                           u32x4 (&slot)[PREFETCH_DEPTH][U], u32x4 (&last)[U])
+{
+    using P = Policy<1>;
+#pragma unroll
+    for (int i = 0; i < RECORD_DEPTH; ++i) {
+        const uint32_t rec = r[i];
+        if constexpr (KIND == FUSED_BLOCK_ADD) {
+            const uint64_t d0 = record_address(rec, 2);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                typename T::Acc a = T::widen(slot[i % PREFETCH_DEPTH][u]);
+                T::add(a, last[u], c.op);
+                last[u] = T::narrow(a);
+            }
+            const __amdgpu_buffer_rsrc_t rd = tile_rsrc(d0, c.tile_off, c.tile_bytes);
+#pragma unroll
+            for (int u = 0; u < U; ++u) store16<P::ST>(rd, c.off[u], last[u]);
+            const __amdgpu_buffer_rsrc_t rn =
+                tile_rsrc(record_address(r[(i + PREFETCH_DEPTH) % RECORD_DEPTH], 0), c.tile_off, c.tile_bytes);
+#pragma unroll
+            for (int u = 0; u < U; ++u) slot[i % PREFETCH_DEPTH][u] = load16<P::LD>(rn, c.off[u]);
+        } else {
+            const __amdgpu_buffer_rsrc_t rd = tile_rsrc(record_address(rec, 1), c.tile_off, c.tile_bytes);
+#pragma unroll
+            for (int u = 0; u < U; ++u) store16<P::ST>(rd, c.off[u], last[u]);
+        }
+        r[i] = load_record<U>(c, j + RECORD_DEPTH + (uint32_t)i);
+    }
+}
+
 template <typename T, int U, int MODE>
-__global__ __launch_bounds__(FUSED_LANES) void fused_chain_kernel(FusedTable tab)
+__global__ __launch_bounds__(FUSED_LANES) __attribute__((amdgpu_waves_per_eu(8, 8))) void fused_chain_kernel(FusedTable tab)
 {
     using elem = typename T::elem;
-    static_assert(PREFETCH_DEPTH == 4 && RECORD_DEPTH == 8, "the loop below names four data slots and eight record slots");
+    static_assert(PREFETCH_DEPTH == 4 && RECORD_DEPTH == 8 && RECORD_DEPTH == (int)FUSED_CHAIN_PAD, "slots and padding");
     const uint32_t tid = threadIdx.x;
     const uint32_t chain = ((const LA_CONSTANT uint32_t*)tab.wg_chain)[blockIdx.x];
     const uint32_t tile = ((const LA_CONSTANT uint32_t*)tab.wg_tile)[blockIdx.x];
@@ -192,34 +235,29 @@ __global__ __launch_bounds__(FUSED_LANES) void fused_chain_kernel(FusedTable tab
     for (int u = 0; u < U; ++u) c.off[u] = (tid + (uint32_t)u * FUSED_LANES) * 16u;
     c.record_lane = (tid & 15u) * 4u;
 
-    uint32_t r0 = load_record<U>(c, 0), r1 = load_record<U>(c, 1), r2 = load_record<U>(c, 2), r3 = load_record<U>(c, 3);
-    uint32_t r4 = load_record<U>(c, 4), r5 = load_record<U>(c, 5), r6 = load_record<U>(c, 6), r7 = load_record<U>(c, 7);
-    u32x4 a0[U], a1[U], a2[U], a3[U], last[U], none[U];
+    uint32_t r[RECORD_DEPTH];
+#pragma unroll
+    for (int i = 0; i < RECORD_DEPTH; ++i) r[i] = load_record<U>(c, (uint32_t)i);
+    u32x4 slot[PREFETCH_DEPTH][U], last[U], none[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) last[u] = none[u] = u32x4{0, 0, 0, 0};
     // the first PREFETCH_DEPTH operations' original inputs: requested through the same code as later
     // ones, by four operations that do nothing (a record of zeros is padding) but prefetch
-    chain_op<T, U>(c, 0u, r0, a0, none);
-    chain_op<T, U>(c, 0u, r1, a1, none);
-    chain_op<T, U>(c, 0u, r2, a2, none);
-    chain_op<T, U>(c, 0u, r3, a3, none);
+#pragma unroll
+    for (int i = 0; i < PREFETCH_DEPTH; ++i) chain_op<T, U>(c, 0u, r[i], slot[i], none);
     for (uint32_t j = 0; j < c.num_ops; j += RECORD_DEPTH) {
-        chain_op<T, U>(c, r0, r4, a0, last);
-        r0 = load_record<U>(c, j + 8);
-        chain_op<T, U>(c, r1, r5, a1, last);
-        r1 = load_record<U>(c, j + 9);
-        chain_op<T, U>(c, r2, r6, a2, last);
-        r2 = load_record<U>(c, j + 10);
-        chain_op<T, U>(c, r3, r7, a3, last);
-        r3 = load_record<U>(c, j + 11);
-        chain_op<T, U>(c, r4, r0, a0, last);
-        r4 = load_record<U>(c, j + 12);
-        chain_op<T, U>(c, r5, r1, a1, last);
-        r5 = load_record<U>(c, j + 13);
-        chain_op<T, U>(c, r6, r2, a2, last);
-        r6 = load_record<U>(c, j + 14);
-        chain_op<T, U>(c, r7, r3, a3, last);
-        r7 = load_record<U>(c, j + 15);
+        const uint32_t kind = record_dword(r[0], 1) >> 8; // of the eight operations that start here
+        if (MODE == MODE_SUM && kind == FUSED_BLOCK_ADD) {
+            ring_block<T, U, FUSED_BLOCK_ADD>(c, j, r, slot, last);
+        } else if (kind == FUSED_BLOCK_COPY) {
+            ring_block<T, U, FUSED_BLOCK_COPY>(c, j, r, slot, last);
+        } else {
+#pragma unroll
+            for (int i = 0; i < RECORD_DEPTH; ++i) {
+                chain_op<T, U>(c, r[i], r[(i + PREFETCH_DEPTH) % RECORD_DEPTH], slot[i % PREFETCH_DEPTH], last);
+                r[i] = load_record<U>(c, j + RECORD_DEPTH + (uint32_t)i);
+            }
+        }
     }
 }
 
@@ -245,17 +283,14 @@ la_status_t launch_unroll(const FusedTable& t, hipStream_t s)
 #define LA_FUSED_NAME(d) LA_CONCAT2(launch_fused_, d)
 // The caller guarantees: the tables are device-resident and consistent (every workgroup's chain and
 // tile exist, every op has one or two sources and destinations whose addresses are valid for the
-// chain's whole column range), all operand addresses agree modulo 16 bytes, unroll is 1, 2 or 4 and
-// wg_tile counts tiles of 64 * unroll vectors.
+// chain's whole column range), all operand addresses agree modulo 16 bytes, unroll is 1 and wg_tile
+// counts tiles of 64 vectors.
 la_status_t LA_FUSED_NAME(LA_KERNEL_DTYPE)(const FusedTable& t, int unroll, void* stream)
 {
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    switch (unroll) {
-    case 1: return launch_unroll<ElemTraits, 1>(t, s);
-    case 2: return launch_unroll<ElemTraits, 2>(t, s);
-    case 4: return launch_unroll<ElemTraits, 4>(t, s);
-    }
-    return fail(LA_ERR_INVALID_ARG, "internal: fused launch with %d vectors per lane", unroll);
+    // one vector per lane: more, smaller pieces of chains in flight did better at every size measured
+    // (16 ranks x 64 MiB: 467 / 489 / 517 us with 1 / 2 / 4 vectors; 1024 ranks x 4 MiB: 2927 / 2957 / 3331)
+    if (unroll != 1) return fail(LA_ERR_INVALID_ARG, "internal: fused launch with %d vectors per lane", unroll);
+    return launch_unroll<ElemTraits, 1>(t, static_cast<hipStream_t>(stream));
 }
 
 } // namespace la

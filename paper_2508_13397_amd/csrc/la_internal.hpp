@@ -179,8 +179,9 @@ struct ChainInfo { // device record of one chain
 // needs, so that a wave fetches it with one load.
 struct FusedOp {
     uint32_t dep_mask;  // bit t: source t was written by an earlier op of the chain
-    uint32_t live;      // 1: an operation; 0: padding behind a chain's last operation (chains are padded to
-                        // a multiple of eight records, so that the kernel's loop needs no test per operation)
+    uint32_t live;      // bit 0: 1 = an operation, 0 = padding behind a chain's last operation (chains are
+                        // padded to a multiple of eight records, so that the kernel's loop needs no test
+                        // per operation); bits 8 and up, in the first record of every eight: FUSED_BLOCK_*
     uint16_t k, m;
     int16_t prefetch;   // a source that is an original input of the run (loadable ahead), or -1
     int16_t forward;    // a source that is what the previous op of the chain stored (still in registers), or -1
@@ -192,6 +193,8 @@ static_assert(sizeof(FusedOp) == 64, "one cache line per operation");
 
 constexpr uint32_t FUSED_LANES = 64; // one wave per workgroup: no barrier anywhere in the kernel
 constexpr uint32_t FUSED_CHAIN_PAD = 8;            // records per chain: a multiple of this
+// Shape of eight consecutive operations (the records [8b, 8b + 8) of a chain), see ring_block in fused.hip
+enum : uint32_t { FUSED_BLOCK_GENERAL = 0, FUSED_BLOCK_ADD = 1, FUSED_BLOCK_COPY = 2 };
 constexpr uint32_t FUSED_EDGE_TILE = 0xffffffffu;  // wg_tile of the workgroup that does a chain's elements
                                                    // outside its whole 16-byte vectors
 

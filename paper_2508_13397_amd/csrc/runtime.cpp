@@ -620,17 +620,14 @@ la_status_t build_fused(const la_schedule& s, la_binding* b, size_t run, const s
         chain[c].pad = 0;
         O += chain[c].num_ops;
     }
-    // One vector per lane (a wave takes 1 KiB of its chain through all operations), unless the
-    // "unroll" knob asks for 2 or 4: more, smaller chains in flight did better at every size measured
-    // (16 ranks x 64 MiB: 467 / 489 / 517 us with 1 / 2 / 4 vectors; 1024 ranks x 4 MiB: 2927 / 2957 / 3331).
+    // One vector per lane: a wave takes 1 KiB of its chain through all operations.
     // One more workgroup per chain that has elements outside its whole vectors.
     auto workgroups_for = [&](uint64_t unroll) {
         uint64_t w = 0;
         for (size_t c = 0; c < C; ++c) w += (chain[c].nvec + FUSED_LANES * unroll - 1) / (FUSED_LANES * unroll);
         return w;
     };
-    uint64_t unroll = 1;
-    if (b->requested.unroll == 2 || b->requested.unroll == 4) unroll = (uint64_t)b->requested.unroll;
+    const uint64_t unroll = 1;
     uint64_t W = workgroups_for(unroll);
     for (size_t c = 0; c < C; ++c) W += chain[c].head + chain[c].tail > 0 ? 1 : 0;
     if (W > 0x7fffffffull || C > 0xffffffffull) return LA_OK;
@@ -659,6 +656,29 @@ la_status_t build_fused(const la_schedule& s, la_binding* b, size_t run, const s
             uint64_t* to = to_op->addr;
             for (int t = 0; t < p.k; ++t) *to++ = addr[p.src[g * p.k + t].buf] + f.chain_lo[c] * e;
             for (int d = 0; d < p.m; ++d) *to++ = addr[p.dst[g * p.m + d].buf] + f.chain_lo[c] * e;
+        }
+    }
+    // blocks of eight operations that are all "add what I hold to a prefetched input" or all "store
+    // what I hold", with the four operations behind them wanting a prefetch (resp. none): the kernel
+    // runs these without a branch
+    for (size_t c = 0; c < C; ++c) {
+        FusedOp* o = op + chain[c].first_op;
+        const uint32_t count = chain[c].num_ops;
+        auto at = [&](uint32_t i) -> const FusedOp* { return i < count ? o + i : nullptr; };
+        for (uint32_t j = 0; j < count; j += FUSED_CHAIN_PAD) {
+            bool add = true, copy = true;
+            for (uint32_t i = j; i < j + FUSED_CHAIN_PAD; ++i) {
+                const FusedOp& x = o[i];
+                add = add && x.live == 1 && x.k == 2 && x.m == 1 && x.prefetch == 0 && x.forward == 1;
+                copy = copy && x.live == 1 && x.k == 1 && x.m == 1 && x.forward == 0;
+            }
+            for (uint32_t i = j + 4; i < j + FUSED_CHAIN_PAD + 4; ++i) {
+                const FusedOp* x = at(i);
+                const bool wants = x && (x->live & 1u) && x->prefetch >= 0;
+                add = add && wants && x->prefetch == 0;
+                copy = copy && !wants;
+            }
+            o[j].live |= (add ? FUSED_BLOCK_ADD : copy ? FUSED_BLOCK_COPY : FUSED_BLOCK_GENERAL) << 8;
         }
     }
     uint32_t* wgc = reinterpret_cast<uint32_t*>(blob.data() + wgc_at);
