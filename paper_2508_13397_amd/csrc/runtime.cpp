@@ -744,8 +744,8 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void*
     std::lock_guard<std::mutex> lock(sched->mu);
     const Tuning tune = current_tuning();
     int dev = -1;
-    LA_HIP(hipGetDevice(&dev));
-    la_binding* b = find_binding(*sched, bufs, sendbufs, dev, tune);
+    if (hipGetDevice(&dev) != hipSuccess) dev = -1; // reported below, after the arguments have been checked
+    la_binding* b = dev >= 0 ? find_binding(*sched, bufs, sendbufs, dev, tune) : nullptr;
     if (!b) {
         try {
             std::vector<uint64_t> fresh;
