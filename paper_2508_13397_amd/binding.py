@@ -4,7 +4,9 @@ fallback: if the library has not been built, or a call fails, an exception is ra
 from __future__ import annotations
 
 import ctypes
+import importlib.util
 import os
+import sys
 from typing import Optional, Sequence
 
 import numpy as np
@@ -67,6 +69,16 @@ class LaError(RuntimeError):
 _lib = None
 
 
+def _share_hip_runtime_with_torch() -> None:
+    """PyTorch-ROCm ships a HIP runtime of its own under the system runtime's soname.  Whichever of
+    the two is loaded first serves every later user of that soname; if this library pulled in the
+    system's and torch then brought its own (with its own HSA runtime), the process would hold two,
+    and the second finds no device.  So where torch is installed it is imported before the library
+    is loaded, and both use torch's."""
+    if "torch" not in sys.modules and importlib.util.find_spec("torch") is not None:
+        import torch  # noqa: F401
+
+
 def lib() -> ctypes.CDLL:
     """Load the built library; raise loudly when it is missing."""
     global _lib
@@ -76,6 +88,7 @@ def lib() -> ctypes.CDLL:
         raise ImportError(
             f"{LIB_PATH} has not been built; run `python -m paper_2508_13397_amd.build` "
             "(hipcc, gfx950). There is no CPU fallback.")
+    _share_hip_runtime_with_torch()
     L = ctypes.CDLL(LIB_PATH)
     vp, i32, u32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint, ctypes.c_size_t
     pp = ctypes.POINTER

@@ -102,6 +102,32 @@ def test_c_abi_consumer_without_python_or_torch():
     assert r.returncode == 0 and r.stdout.strip().endswith("all ok"), (r.returncode, r.stdout[-1500:], r.stderr[-1500:])
 
 
+def test_package_used_before_torch_is_imported():
+    """A fresh process that loads the library (a tuning call) before it imports torch still finds
+    the GPU: the binding makes both share one HIP runtime.  An int32 all-reduce there equals the
+    plain sum."""
+    import os
+    import subprocess
+    import sys
+
+    code = (
+        "import sys\n"
+        "import paper_2508_13397_amd as la\n"
+        "assert 'torch' not in sys.modules\n"
+        "la.la_tuning_get('merge')\n"
+        "import torch\n"
+        "topo = la.la_topology_create(2, 2, 1)\n"
+        "sched = la.la_schedule_build(topo, la.LA_ALGO_LANE, 1000, la.LA_I32)\n"
+        "bufs = [torch.full((1000,), r + 1, dtype=torch.int32, device='cuda:0') for r in range(4)]\n"
+        "la.la_allreduce_emulated(sched, [b.data_ptr() for b in bufs], 1000, la.LA_I32, la.LA_SUM, torch.cuda.current_stream().cuda_stream)\n"
+        "torch.cuda.synchronize()\n"
+        "assert all(bool((b == 10).all()) for b in bufs)\n"
+        "print('ok')\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300, cwd=root)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), (r.returncode, r.stdout[-1500:], r.stderr[-1500:])
+
+
 # ------------------------------------------------------------------------------ config 1
 # ------------------------------------------------------------------------------ config 1
 
