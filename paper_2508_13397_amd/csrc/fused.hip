@@ -178,6 +178,10 @@ __device__ __forceinline__ void ring_block(const ChainContext<U>& c, uint32_t j,
     using P = Policy<1>;
 #pragma unroll
     for (int i = 0; i < RECORD_DEPTH; ++i) {
+        // The record is "produced" here as far as the compiler can tell, so its lane reads (cheap,
+        // free of side effects) are not gathered at the top of the block, where the wait for the
+        // youngest record would be a wait for a load issued one operation ago.
+        asm volatile("" : "+v"(r[i]));
         const uint32_t rec = r[i];
         if constexpr (KIND == FUSED_BLOCK_ADD) {
             const uint64_t d0 = record_address(rec, 2);
@@ -200,6 +204,7 @@ __device__ __forceinline__ void ring_block(const ChainContext<U>& c, uint32_t j,
             for (int u = 0; u < U; ++u) store16<P::ST>(rd, c.off[u], last[u]);
         }
         r[i] = load_record<U>(c, j + RECORD_DEPTH + (uint32_t)i);
+        __builtin_amdgcn_sched_barrier(0); // and the scheduler keeps every operation's instructions together
     }
 }
 
@@ -245,18 +250,30 @@ __global__ __launch_bounds__(FUSED_LANES) __attribute__((amdgpu_waves_per_eu(8, 
     // ones, by four operations that do nothing (a record of zeros is padding) but prefetch
 #pragma unroll
     for (int i = 0; i < PREFETCH_DEPTH; ++i) chain_op<T, U>(c, 0u, r[i], slot[i], none);
-    for (uint32_t j = 0; j < c.num_ops; j += RECORD_DEPTH) {
+    // Consecutive blocks of one ring shape run in a loop of their own: with a single path round the
+    // loop the values it carries (records, prefetched inputs, the vector in hand) stay in their
+    // registers, whereas at a join of the three paths they were moved, and a move waits for every
+    // load that is still in flight.
+    uint32_t j = 0;
+    while (j < c.num_ops) {
         const uint32_t kind = record_dword(r[0], 1) >> 8; // of the eight operations that start here
         if (MODE == MODE_SUM && kind == FUSED_BLOCK_ADD) {
-            ring_block<T, U, FUSED_BLOCK_ADD>(c, j, r, slot, last);
+            do {
+                ring_block<T, U, FUSED_BLOCK_ADD>(c, j, r, slot, last);
+                j += RECORD_DEPTH;
+            } while (j < c.num_ops && (record_dword(r[0], 1) >> 8) == FUSED_BLOCK_ADD);
         } else if (kind == FUSED_BLOCK_COPY) {
-            ring_block<T, U, FUSED_BLOCK_COPY>(c, j, r, slot, last);
+            do {
+                ring_block<T, U, FUSED_BLOCK_COPY>(c, j, r, slot, last);
+                j += RECORD_DEPTH;
+            } while (j < c.num_ops && (record_dword(r[0], 1) >> 8) == FUSED_BLOCK_COPY);
         } else {
 #pragma unroll
             for (int i = 0; i < RECORD_DEPTH; ++i) {
                 chain_op<T, U>(c, r[i], r[(i + PREFETCH_DEPTH) % RECORD_DEPTH], slot[i % PREFETCH_DEPTH], last);
                 r[i] = load_record<U>(c, j + RECORD_DEPTH + (uint32_t)i);
             }
+            j += RECORD_DEPTH;
         }
     }
 }

@@ -216,6 +216,13 @@ struct la_binding {
         bool ready = false, impossible = false;
     };
     std::vector<FusedRun> fused; // one per run of the schedule's fusion plan
+    // which runs the last call launched fused, kept so that a repeat call decides (and allocates) nothing
+    struct Selection {
+        int fuse = 0, first = -1, last = -1; // the "fuse" knob and the range of steps it was made for
+        std::vector<int> run_at;             // per step: the fused run that starts there, or -1
+        bool any = false;
+    };
+    Selection selection;
 };
 
 namespace la {
@@ -553,6 +560,7 @@ la_status_t bind(const la_schedule& s, std::vector<uint64_t>& addr, const Tuning
     for (la_binding::FusedRun& r : b->fused)
         if (r.tables) (void)hipFree(r.tables);
     b->fused.clear();
+    b->selection = la_binding::Selection();
     b->requested = tune;
     b->shape = std::move(shapes);
     b->used = false;
@@ -764,14 +772,18 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void*
     const bool want_graph = whole && last > 0 && (mode == 1 || (mode < 0 && last >= GRAPH_MIN_STEPS));
     // which runs of steps go out as one column-fused launch each
     const int fuse = g_fuse.load();
-    std::vector<int> run_at; // per step: the fused run that starts there, or -1
-    bool any_fused = false;
-    if (fuse != 0 && last - first >= 2) {
+    la_binding::Selection& sel = b->selection;
+    if (fuse == 0 || last - first < 2) {
+        sel.any = false;
+        sel.first = -1;
+    } else if (sel.fuse != fuse || sel.first != first || sel.last != last) {
+        sel.first = -1; // not valid until complete
+        sel.any = false;
         try {
             analyse_fusion(*sched);
             const std::vector<FusionRun>& runs = sched->fusion.runs;
             if (b->fused.size() != runs.size()) b->fused.resize(runs.size());
-            run_at.assign(sched->steps.size(), -1);
+            sel.run_at.assign(sched->steps.size(), -1);
             for (size_t r = 0; r < runs.size(); ++r) {
                 const FusionRun& f = runs[r];
                 if (f.first_step < first || f.first_step + f.num_steps > last) continue;
@@ -782,16 +794,20 @@ la_status_t run_steps(const la_schedule_t* sched, void* const* bufs, const void*
                     if (st != LA_OK) return st;
                 }
                 if (b->fused[r].ready) {
-                    run_at[f.first_step] = (int)r;
-                    any_fused = true;
+                    sel.run_at[f.first_step] = (int)r;
+                    sel.any = true;
                 }
             }
+            sel.fuse = fuse;
+            sel.first = first;
+            sel.last = last;
         } catch (const std::bad_alloc&) {
             sched->fusion = FusionPlan();
-            run_at.clear();
-            any_fused = false;
+            sel.any = false;
         }
     }
+    const bool any_fused = sel.any;
+    const std::vector<int>& run_at = sel.run_at;
     bool launched = false;
     if (!any_fused && want_graph && !b->graph_failed) {
         if (b->graph_exec && b->graph_op != op) drop_graph(b);
