@@ -64,7 +64,8 @@ def build_consumer(verbose: bool = False) -> str:
     only (no Python, no torch in the process); the GPU tests run it."""
     src = os.path.join(ROOT, "tests", "consumer", "consumer.cpp")
     exe = os.path.join(ROOT, "tests", "consumer", "consumer.exe")
-    cmd = [HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), src, "-o", exe,
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", os.path.join(ROOT, "include"), src, "-o", exe,
            "-L", HERE, "-llaneallreduce", "-Wl,-rpath,$ORIGIN/../../paper_2508_13397_amd"]
     if verbose:
         print(" ".join(cmd), flush=True)
