@@ -6,7 +6,8 @@
  * list of steps; every step is a table of segments, and a segment says "add these k source
  * ranges element by element, in this order, and store the sum to these m destination ranges".
  * Message exchanges of the distributed algorithm become reads of a peer's buffer; all
- * arithmetic runs in HIP kernels, one launch per step.
+ * arithmetic runs in HIP kernels, one launch per step (or one per run of consecutive two-operand
+ * steps, see la_schedule_fusion_runs).
  *
  * Rank numbering follows l_r = r mod PPG ("Multiple Processes Per GPU" subsection):
  *   r = (node * gpus_per_node + gpu) * procs_per_gpu + proc.
