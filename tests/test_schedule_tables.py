@@ -164,9 +164,14 @@ def test_schedule_build_errors():
 
 def test_tuning_knobs():
     assert (la.la_tuning_get("unroll"), la.la_tuning_get("cache_policy"), la.la_tuning_get("block")) == (0, -1, 0)
+    assert (la.la_tuning_get("merge"), la.la_tuning_get("forward"), la.la_tuning_get("fuse"), la.la_tuning_get("graph")) == (1, 1, -1, -1)
+    assert la.la_tuning_get("fused_launches") >= 0  # a counter, read-only
+    with pytest.raises(la.LaError):
+        la.la_tuning_set("fused_launches", 0)
     try:
         for key, good, bad in (("unroll", (1, 2, 4, 8, 0), (3, -1, 16)), ("cache_policy", (0, 1, 2, 3, 4, 5, 6, 7, -1), (8, -2)),
-                               ("block", (256, 1024, 0), (128, 512, 2048)), ("graph", (0, 1, -1), (2, -2))):
+                               ("block", (256, 1024, 0), (128, 512, 2048)), ("graph", (0, 1, -1), (2, -2)),
+                               ("merge", (0, 1), (2, -1)), ("forward", (0, 1), (2, -1)), ("fuse", (0, 1, -1), (2, -2))):
             for v in good:
                 la.la_tuning_set(key, v)
                 assert la.la_tuning_get(key) == v
