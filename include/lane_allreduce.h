@@ -238,8 +238,12 @@ la_status_t la_schedule_step_table(const la_schedule_t* sched, int step, uint64_
  * tables with a synchronous copy, after waiting for the work of the set it forgets in exchange.
  * Runs of steps with at most two sources and destinations per segment (the ring forms) go out as
  * one launch each (see la_schedule_fusion_runs); a schedule of 16 or more launches without such a
- * run is recorded once per buffer set into a HIP graph of kernel nodes and replayed.  Calls on one schedule are serialised by the library;
- * different schedules can be used from different host threads at the same time.
+ * run is recorded once per buffer set into a HIP graph of kernel nodes and replayed.  A call with
+ * a remembered set allocates nothing and enqueues kernel launches only (no copy, memset, event or
+ * synchronisation), so it may be recorded into a caller's own graph, provided the library does
+ * not replay a graph of its own for the schedule ("graph" knob 0, or fewer than 16 launches).
+ * Calls on one schedule are serialised by the library; different schedules can be used from
+ * different host threads at the same time.
  * int32 wraps; fp32 adds are IEEE, in the fixed operand order of the tables; bf16 operands are
  * widened to fp32, summed in fp32 and rounded to nearest-even once per reduce step.
  */

@@ -619,6 +619,43 @@ def test_graph_replays_match_step_by_step_launches(oracle, algo, flags, topo):
         la.la_tuning_set("fuse", -1)
 
 
+@pytest.mark.parametrize("algo,topo", [("lane_multiproc", (2, 2, 2)), ("ring", (3, 2, 1))])
+def test_repeat_calls_can_be_captured_in_a_callers_graph(oracle, algo, topo):
+    """A call on a buffer set the schedule already ran on makes kernel launches and nothing else
+    (no allocation, copy, memset, event or synchronisation), so a caller can record it into a graph
+    of their own: three launches for the lane schedule, one fused launch for the ring.  The graph
+    restores the inputs and runs the all-reduce; every replay, with eager work and synchronisations
+    in between, must give the oracle's bits."""
+    N, G, Q = topo
+    P, n = N * G * Q, 40003
+    x = make(P, n, "f32order", seed=9)
+    ref = oracle.allreduce(algo, N, G, Q, x)
+    sched = la.la_schedule_build(la.la_topology_create(N, G, Q), algo, n, "float32")
+    bufs = [to_dev(x[r]) for r in range(P)]
+    src = [b.clone() for b in bufs]
+    scratch = torch.zeros(1 << 20, device="cuda")
+    la.allreduce_tensors(sched, bufs)  # binds the schedule to these buffers (one upload), outside the graph
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(np.stack([to_host(b) for b in bufs])), bits(ref))
+    launches_before = la.la_tuning_get("fused_launches")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for b, s0 in zip(bufs, src):
+            b.copy_(s0)
+        la.allreduce_tensors(sched, bufs)  # on torch's current stream: the capturing one
+    assert la.la_tuning_get("fused_launches") - launches_before == (1 if algo == "ring" else 0)
+    for replay in range(3):
+        for b in bufs:
+            b.fill_(float(replay))  # whatever is there is overwritten by the graph's first nodes
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(np.stack([to_host(b) for b in bufs])), bits(ref)), replay
+        assert np.array_equal(bits(np.stack([to_host(b) for b in src])), bits(x))
+    assert float(scratch[0]) == 3.0
+
+
 # ------------------------------------------------------------------------------ operations and wide types
 
 def wide_inputs(P, n, kind, seed):
