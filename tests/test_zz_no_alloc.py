@@ -97,3 +97,30 @@ def test_static_entry_point_limits_and_errors():
     la.la_reduce_segments_static(d.data_ptr(), ptrs[:11], list(range(0, 8192 * 8, 8)), 8, "float32")
     torch.cuda.synchronize()
     assert float(d.min()) == 11.0 and float(d.max()) == 11.0
+
+
+def test_static_entry_point_recorded_into_a_callers_graph(oracle):
+    """What the entry point is for: a caller under graph capture.  After one eager call (which
+    looks up the array's device address), a call is recorded with torch.cuda.graph together with
+    the copy that restores dst, and replayed three times with eager calls of other shapes (which
+    rewrite the shared array) in between: every replay must give the oracle's bits."""
+    if not torch.cuda.is_available():
+        pytest.fail("this test needs a GPU")
+    k, n, seg_len = 5, 300000, 4001
+    offs = [i * 5000 + (i % 5) for i in range(55)]
+    x = inputs("f32", k + 1, n, seed=3)
+    ref = oracle.reduce_segments(x[0], list(x[1:]), offs, seg_len)
+    dev = [to_dev(x[t]) for t in range(k + 1)]
+    dst0 = dev[0].clone()
+    srcs = [t.data_ptr() for t in dev[1:]]
+    run_both(oracle, "f32", 2, 40000, [5, 9001, 30000], 777)  # eager: the symbol lookup happens here
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        dev[0].copy_(dst0)
+        la.la_reduce_segments_static(dev[0].data_ptr(), srcs, offs, seg_len, "float32", la.LA_SUM,
+                                     torch.cuda.current_stream().cuda_stream)
+    for replay in range(3):
+        run_both(oracle, "i32", 3, 50000, [0, 20000], 1234 + replay)  # other tables pass through the array
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(dev[0]).view(np.uint8), ref.view(np.uint8)), replay
