@@ -1397,6 +1397,108 @@ def test_random_flag_combinations_on_the_gpu(oracle):
     assert ran >= 350, ran
 
 
+def test_random_knobs_views_operations_and_types_on_the_gpu(oracle):
+    """Seeded sweep over what the sweep above holds fixed: all five element types, all four
+    operations, buffers that are views at element offsets inside larger allocations (one common
+    offset: vector path with heads and tails; independent offsets: no common 16-byte phase), and
+    the launch knobs (runs fused or not, forwarding, merging, forced tile shapes and cache
+    policies, graph replay).  Bit-equal to the oracle (NaN payloads aside), send buffers and the
+    guard elements around every view untouched."""
+    rng = np.random.default_rng(2508)
+    pool = [la.LA_SCHED_P2P_GATHER, la.LA_SCHED_STAGED, la.LA_SCHED_INNER_RING, la.LA_SCHED_SHARED_BUFFERS,
+            la.LA_SCHED_OUT_OF_PLACE, la.LA_SCHED_FUSED_GATHER, la.LA_SCHED_SINGLE_LAUNCH]
+    algos = ["ring", "lane", "lane_multiproc", "recursive_doubling", "rabenseifner"]
+    defaults = dict(fuse=-1, forward=1, merge=1, unroll=0, block=0, cache_policy=-1, graph=-1)
+    GUARD = 77
+
+    def draw(B, n, kind, op):
+        if kind == "i32":
+            x = rng.integers(-(1 << 31), 1 << 31, size=(B, n), dtype=np.int64).astype(np.int32)
+            if op == "prod":
+                x[:, ::2] = rng.integers(-5, 6, size=x[:, ::2].shape)
+            return x
+        if kind == "f32":
+            return (rng.standard_normal((B, n)) * np.exp2(rng.integers(-30, 30, size=(B, n)))).astype(np.float32)
+        if kind == "bf16":
+            return oracle.bf16_round((rng.standard_normal((B, n)) * np.exp2(rng.integers(-8, 8, size=(B, n)))).astype(np.float32))
+        if kind == "f16":
+            return (rng.standard_normal((B, n)) * np.exp2(rng.integers(-16, 4, size=(B, n)))).astype(np.float16)
+        return rng.standard_normal((B, n)) * np.exp2(rng.integers(-40, 40, size=(B, n)))
+
+    def view(row, off):
+        n = row.shape[0]
+        whole = np.full(n + off + 40, GUARD, dtype=row.dtype)
+        whole[off: off + n] = row
+        t = to_dev(whole)
+        return t, t[off: off + n]
+
+    ran = 0
+    for case in range(700):
+        algo = algos[rng.integers(len(algos))]
+        flags = 0
+        for b in pool:
+            if rng.random() < 0.25:
+                flags |= b
+        N, G, Q = (int(v) for v in rng.integers(1, 5, size=3))
+        if algo in ("recursive_doubling", "rabenseifner"):
+            N, G, Q = (int(v) for v in 2 ** rng.integers(0, 3, size=3))
+        n = int(rng.choice([1, 3, 17, 255, 1000, 4099, 40961, 150001]))
+        kind = ("i32", "f32", "bf16", "f16", "f64")[int(rng.integers(5))]
+        op = ("sum", "sum", "prod", "max", "min")[int(rng.integers(5))]
+        knobs = dict(fuse=int(rng.choice([-1, -1, 0, 1])), forward=int(rng.choice([1, 1, 0])), merge=int(rng.choice([1, 1, 0])),
+                     unroll=int(rng.choice([0, 0, 1, 2, 4, 8])), block=int(rng.choice([0, 0, 256, 1024])),
+                     cache_policy=int(rng.choice([-1, -1, 0, 3, 6, 7])), graph=int(rng.choice([-1, -1, 0, 1])))
+        mode = int(rng.integers(4))
+        name = NAME[draw(1, 1, kind, op).dtype]
+        try:
+            sched = la.la_schedule_build(la.la_topology_create(N, G, Q), algo, n, name, flags)
+        except la.LaError as err:
+            assert err.status in (la.LA_ERR_INVALID_ARG, la.LA_ERR_UNSUPPORTED)
+            continue
+        B = sched.num_buffers
+        x = draw(B, n, kind, op)
+        offs = [0] * B if mode < 2 else ([int(rng.integers(0, 33))] * B if mode == 2 else [int(v) for v in rng.integers(0, 9, size=B)])
+        print("knob case", case, algo, flags, (N, G, Q), n, kind, op, knobs, offs[:4], flush=True)
+        if flags & la.LA_SCHED_SHARED_BUFFERS:
+            oname, Qo = ("lane_multiproc", 1) if algo == "lane" else (algo, Q)
+            ref = oracle.allreduce(oname, N, G, Qo, x, shared=True, op=op)
+        else:
+            ref = oracle.allreduce(oracle_name(algo, flags) if algo.startswith("lane") else algo, N, G, Q, x, op=op)
+        stream = torch.cuda.current_stream().cuda_stream
+        try:
+            for key, v in knobs.items():
+                la.la_tuning_set(key, v)
+            out = [view(x[r], offs[r]) for r in range(B)]
+            if flags & la.LA_SCHED_OUT_OF_PLACE:
+                send = out
+                out = [view(np.full_like(x[r], 3), offs[r]) for r in range(B)]
+                la.la_allreduce_emulated_out_of_place(sched, [v.data_ptr() for _, v in send], [v.data_ptr() for _, v in out],
+                                                      n, name, la.OPS[op], stream)
+                torch.cuda.synchronize()
+                assert all(np.array_equal(bits(to_host(send[r][1])), bits(x[r])) for r in range(B)), "send buffers changed"
+            else:
+                la.la_allreduce_emulated(sched, [v.data_ptr() for _, v in out], n, name, la.OPS[op], stream)
+                torch.cuda.synchronize()
+        finally:
+            for key, v in defaults.items():
+                la.la_tuning_set(key, v)
+        got = np.stack([to_host(v) for _, v in out])
+        for r in range(B):
+            w = to_host(out[r][0])
+            assert np.all(w[: offs[r]] == GUARD) and np.all(w[offs[r] + n:] == GUARD), ("guard elements written", case, r)
+        u = {2: np.uint16, 4: np.uint32, 8: np.uint64}[x.dtype.itemsize]
+        if x.dtype == np.uint16:
+            nan_ref, nan_got = ((ref & 0x7f80) == 0x7f80) & ((ref & 0x7f) != 0), ((got & 0x7f80) == 0x7f80) & ((got & 0x7f) != 0)
+        elif x.dtype != np.int32:
+            nan_ref, nan_got = np.isnan(ref), np.isnan(got)
+        else:
+            nan_ref = nan_got = np.zeros(ref.shape, bool)
+        assert np.array_equal(nan_got, nan_ref), (case, "NaN pattern")
+        assert np.array_equal(got.view(u)[~nan_ref], ref.view(u)[~nan_ref]), (case, algo, flags, (N, G, Q), n, kind, op, knobs)
+        ran += 1
+    assert ran >= 250, ran
+
+
 # ------------------------------------------------------------------------------ full-size configs
 
 def full_size_case(oracle, topo, algo, n, dist, flags=la.LA_SCHED_DEFAULT, tol=True):
