@@ -95,7 +95,6 @@ bool analyse_run(const la_schedule& s, int first, int count, FusionRun& f)
     // per op: which sources are original inputs of the chain (never written by an earlier op of it),
     // which one is what the previous op stored
     f.op_prefetch.assign(total, -1);
-    f.op_dep_mask.assign(total, 0);
     f.op_forward.assign(total, -1);
     f.max_chain_ops = 0;
     const size_t bufs = 2 * (size_t)s.nbuf + 2;
@@ -107,14 +106,9 @@ bool analyse_run(const la_schedule& s, int first, int count, FusionRun& f)
             const Step& p = s.steps[f.op_step[o]];
             const size_t g = f.op_seg[o];
             int pf = -1;
-            uint32_t mask = 0;
-            for (int t = 0; t < p.k; ++t) {
-                const bool dep = written_by[p.src[g * p.k + t].buf] == c + 1;
-                if (dep) mask |= 1u << t;
-                if (!dep && pf < 0) pf = t;
-            }
+            for (int t = 0; t < p.k && pf < 0; ++t)
+                if (written_by[p.src[g * p.k + t].buf] != c + 1) pf = t;
             f.op_prefetch[o] = pf;
-            f.op_dep_mask[o] = mask;
             if (o > f.chain_first[c]) {
                 const Step& q = s.steps[f.op_step[o - 1]];
                 const size_t h = f.op_seg[o - 1];

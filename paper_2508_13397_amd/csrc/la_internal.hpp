@@ -155,7 +155,6 @@ struct FusionRun {
     // a source of the op that no earlier op of the chain has written (an original input of the run),
     // which the kernel may load ahead of time; -1: none
     std::vector<int32_t> op_prefetch;
-    std::vector<uint32_t> op_dep_mask;         // bit t: source t was written by an earlier op of the chain
     // a source that is exactly what the previous op of the chain stored (the message a rank has just
     // received and now passes on, or adds to): the lane that stored it still holds it; -1: none
     std::vector<int32_t> op_forward;
@@ -178,7 +177,7 @@ struct ChainInfo { // device record of one chain
 // Device record of one operation of a chain: one 64-byte line that holds everything the operation
 // needs, so that a wave fetches it with one load.
 struct FusedOp {
-    uint32_t dep_mask;  // bit t: source t was written by an earlier op of the chain
+    uint32_t reserved;  // zero
     uint32_t live;      // bit 0: 1 = an operation, 0 = padding behind a chain's last operation (chains are
                         // padded to a multiple of eight records, so that the kernel's loop needs no test
                         // per operation); bits 8 and up, in the first record of every eight: FUSED_BLOCK_*

@@ -652,7 +652,6 @@ la_status_t build_fused(const la_schedule& s, la_binding* b, size_t run, const s
         for (uint64_t o = f.chain_first[c]; o < f.chain_first[c + 1]; ++o, ++to_op) {
             const Step& p = s.steps[f.op_step[o]];
             const size_t g = f.op_seg[o];
-            to_op->dep_mask = f.op_dep_mask[o];
             to_op->live = 1;
             to_op->k = (uint16_t)p.k;
             to_op->m = (uint16_t)p.m;
